@@ -1,0 +1,132 @@
+/*
+ * w4a8.h -- C ABI of the MI355X (gfx950) W4A8 linear layer of arXiv 2311.05161:
+ *
+ *     Y = dequant( Q8(X diag(s)^-1) . dINT4(W diag(s))^T )                 (Eq. 1)
+ *
+ *     X [M,K]  activations, one token per row          (paper: X in R^{C x T}, T tokens)
+ *     W [N,K]  weights, one output channel per row     (paper: W in R^{M x C})
+ *     s [K]    AQAS per-input-channel scale, an input  (paper: s in R^C)
+ *
+ * Conventions for EVERY entry point
+ *   - All data pointers are DEVICE pointers (HIP global memory) owned by the caller; the
+ *     library allocates nothing, frees nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it and the call returns without synchronizing.
+ *   - The return value is a w4a8_status.  Argument errors are detected on the host before
+ *     anything is launched and leave the outputs untouched.  Nothing throws or aborts.
+ *   - Rows are contiguous; `ld*` is the distance between rows in ELEMENTS.
+ *   - Inputs must be finite and s[k] > 0; otherwise the result is undefined (no error).
+ */
+#ifndef W4A8_H
+#define W4A8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    W4A8_OK = 0,
+    W4A8_ERR_NULL = 1,      /* a required pointer is NULL                                   */
+    W4A8_ERR_SHAPE = 2,     /* a size, leading dimension, group size or alignment is invalid */
+    W4A8_ERR_DTYPE = 3,     /* unknown / unsupported element type or layout id              */
+    W4A8_ERR_WORKSPACE = 4, /* workspace missing or smaller than w4a8_gemm_workspace_bytes  */
+    W4A8_ERR_HIP = 5        /* the HIP runtime reported a launch error                      */
+} w4a8_status;
+
+typedef enum { W4A8_F32 = 0, W4A8_F16 = 1, W4A8_BF16 = 2 } w4a8_dtype;
+
+/* Packed-weight layouts (two 4-bit codes per byte).
+ *
+ * W4A8_LAYOUT_CANONICAL (0): row-major [N, K/2]; byte j of row n = code[n,2j] | code[n,2j+1]<<4.
+ *
+ * W4A8_LAYOUT_TILED (1): the same N*K/2 bytes rearranged for the GEMM kernels; requires
+ *   N % 16 == 0 and K % 128 == 0.  The matrix is cut into tiles of 16 rows x 128 columns;
+ *   tile (nt, kt) = (n/16, k/128) starts at byte (nt*(K/128) + kt) * 1024.  Inside a tile,
+ *   "lane" l = (n%16) + 16*((k%128)/32) owns 16 consecutive bytes at offset 16*l, seen as four
+ *   little-endian 32-bit words q = 0..3.  Word q holds the 8 codes of columns
+ *   kk = 32*(l/16) + 8q + 0..7 of the tile: nibble i (bits 4i..4i+3, i = 0..7) holds column
+ *   kk + (i>>1) + 4*(i&1), i.e. the low nibbles of the four bytes are columns +0..+3 and the
+ *   high nibbles are columns +4..+7.  Each nibble stores the code re-encoded as e:
+ *       code c <= 13 : e = (c >> 1) | ((c & 1) << 3)
+ *       code 14 (+step/2) : e = 15          code 15 (-step/2) : e = 7
+ *   so that e & 7 selects one of 8 base levels and bit 3 adds one whole step (= two half
+ *   steps): the pairs (2l, 2l+1) of integer codes and the pair (-step/2, +step/2) all differ
+ *   by exactly one step.
+ */
+enum { W4A8_LAYOUT_CANONICAL = 0, W4A8_LAYOUT_TILED = 1 };
+
+/* Per-token INT8 activation quantization with the AQAS scale folded in
+ * (Eq. 1, factor Q(diag(s)^-1 X); token-wise 8-bit, App. A.1):
+ *     t[m,k] = X[m,k] * (1 / s[k]);  a[m] = max_k |t[m,k]|;
+ *     sx[m] = a[m] / 127;  Xq[m,k] = clamp(rne(t[m,k] * (127 / a[m])), -127, 127);
+ *     an all-zero row gives sx = 1, Xq = 0.
+ * Every step is one IEEE binary32 operation; divisions are correctly rounded.
+ *   X   in   [M, ldx] elements of x_dtype (F32, F16 or BF16), ldx >= K
+ *   s   in   [K] float, or NULL for s = 1
+ *   Xq  out  [M, K] int8, contiguous
+ *   sx  out  [M] float
+ * M == 0 is a no-op.  K >= 1. */
+int quantize_act_int8(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                      const float *s, int8_t *Xq, float *sx, void *stream);
+
+/* dINT4 weight quantization of W diag(s) (Eq. 1 factor Q(W diag(s)); Sec. 4.2, Eq. 5 with
+ * b = 4, p = 13; min-max asymmetric per output channel or per group, App. A.1):
+ *     w' = W[n,k] * s[k];  per (n, group): lo = min(0, min w'), hi = max(0, max w'),
+ *     step = (hi - lo) / 13, z = clamp(rne(-lo * (1/step)), 0, 13)   (hi == lo: step 1, z 0);
+ *     u = w' * (1/step):  0.25 < u <= 0.75 -> code 14 (+step/2);
+ *                        -0.75 <= u < -0.25 -> code 15 (-step/2);
+ *                         else code = clamp(rne(u) + z, 0, 13).
+ *   W      in   [N, ldw] elements of w_dtype, ldw >= K
+ *   s      in   [K] float or NULL
+ *   group_size  0 or K: one (step, z) per output channel; else K % group_size == 0
+ *   use_given_params != 0: step/zero are INPUTS (externally chosen ranges, e.g. after the
+ *               weight clipping of App. A.4) and only the per-element rule runs
+ *   codes  out  [N, K] one code (0..15) per byte
+ *   step   i/o  [N, K/G] float        zero  i/o  [N, K/G] uint8 (0..13)                    */
+int quantize_weight_dint4(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                          const float *s, int64_t group_size, int use_given_params,
+                          uint8_t *codes, float *step, uint8_t *zero, void *stream);
+
+/* Bit-packing of dINT4 codes, two per byte (the storage format the 4-bit weights of
+ * Sec. 4.2 are kept in), and its inverse.  `layout` is one of the ids above.
+ *   codes  [N, K] bytes, values 0..15 (upper bits ignored)     packed  N*K/2 bytes
+ * K must be even (layout 0) or N % 16 == 0 and K % 128 == 0 (layout 1). */
+int pack_dint4(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout,
+               void *stream);
+int unpack_dint4(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout,
+                 void *stream);
+
+/* dINT4 x INT8 GEMM with int32 accumulation and fused dequantization (Eq. 1 product on the
+ * integer operands; Eq. 5 second half; the dINT4 x INT8 MAC of Sec. 4.3):
+ *     d[n,k]     = 2 (code - zero[n,g])  for code <= 13,  +1 for code 14,  -1 for code 15
+ *                  (the weight in units of step/2)
+ *     acc[m,n,g] = sum_{k in group g} Xq[m,k] * d[n,k]                      (int32, exact)
+ *     Y[m,n]     = cast( sx[m] * sum_g (step[n,g] / 2) * acc[m,n,g] )
+ *   Xq   in  [M, K] int8 contiguous        sx    in  [M] float
+ *   Wp   in  packed weights in `layout`    step  in  [N, K/G] float   zero in [N, K/G] uint8
+ *   group_size: 0 or K = per output channel, else a multiple of 128 dividing K
+ *   Y    out [M, ldy] elements of y_dtype (F16 or BF16), ldy >= N
+ *   acc_out  NULL, or int32 [M, N, K/G] (g fastest) that receives the exact accumulators
+ *   workspace / workspace_bytes: scratch of at least w4a8_gemm_workspace_bytes(...) bytes,
+ *               256-byte aligned; may be NULL when that function returns 0
+ * Requires N % 16 == 0, K % 128 == 0, K <= 131072.  M == 0 is a no-op.
+ * The M <= 16 path streams the packed weights once (memory-bound "decode" GEMV); larger M
+ * uses the MFMA tile kernel ("prefill").  Results are deterministic (fixed reduction order). */
+size_t w4a8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size,
+                                 int layout);
+int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
+              const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+              int64_t N, int64_t K, int64_t group_size,
+              void *Y, int y_dtype, int64_t ldy,
+              int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *w4a8_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A8_H */

@@ -1,0 +1,162 @@
+"""Thin ctypes binding of libw4a8.so (the C ABI declared in include/w4a8.h).
+
+Argument marshalling only: every step of the layer runs in the HIP kernels.  PyTorch supplies
+device memory (``tensor.data_ptr()``) and the current HIP stream, nothing else.  There is no CPU
+fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libw4a8.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_WORKSPACE, ERR_HIP = range(6)
+F32, F16, BF16 = 0, 1, 2
+LAYOUT_CANONICAL, LAYOUT_TILED = 0, 1
+
+_DTYPES = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+
+EXPORTS = (
+    "quantize_act_int8", "quantize_weight_dint4", "pack_dint4", "unpack_dint4",
+    "w4a8_gemm_workspace_bytes", "w4a8_gemm", "w4a8_status_string",
+)
+
+_lib = None
+
+
+class W4A8Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def load_library(path: str | None = None) -> ctypes.CDLL:
+    """Load libw4a8.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2311_05161_amd.build`")
+    lib = ctypes.CDLL(path)
+    i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.quantize_act_int8.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.quantize_act_int8.restype = ci
+    lib.quantize_weight_dint4.argtypes = [vp, ci, i64, i64, i64, vp, i64, ci, vp, vp, vp, vp]
+    lib.quantize_weight_dint4.restype = ci
+    lib.pack_dint4.argtypes = [vp, i64, i64, vp, ci, vp]
+    lib.pack_dint4.restype = ci
+    lib.unpack_dint4.argtypes = [vp, i64, i64, vp, ci, vp]
+    lib.unpack_dint4.restype = ci
+    lib.w4a8_gemm_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
+    lib.w4a8_gemm_workspace_bytes.restype = sz
+    lib.w4a8_gemm.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, vp, ci, i64, vp, vp, sz, vp]
+    lib.w4a8_gemm.restype = ci
+    lib.w4a8_status_string.argtypes = [ci]
+    lib.w4a8_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().w4a8_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise W4A8Error(status, where)
+
+
+def _rows(t: torch.Tensor, what: str):
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{what} must be 2-D with contiguous rows")
+    return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def quantize_act_int8(X: torch.Tensor, s: torch.Tensor | None = None, Xq=None, sx=None):
+    """Xq int8 [M,K], sx float32 [M] = per-token absmax INT8 of X diag(s)^-1."""
+    M, K, ldx = _rows(X, "X")
+    if Xq is None:
+        Xq = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    if sx is None:
+        sx = torch.empty((M,), dtype=torch.float32, device=X.device)
+    _check(load_library().quantize_act_int8(_ptr(X), _DTYPES[X.dtype], M, K, ldx, _ptr(s),
+                                            _ptr(Xq), _ptr(sx), _stream()), "quantize_act_int8")
+    return Xq, sx
+
+
+def quantize_weight_dint4(W: torch.Tensor, s: torch.Tensor | None = None, group_size: int = 0,
+                          step: torch.Tensor | None = None, zero: torch.Tensor | None = None):
+    """codes u8 [N,K], step f32 [N,K/G], zero u8 [N,K/G] = dINT4 quantization of W diag(s).
+
+    With ``step`` and ``zero`` given they are used as the quantization parameters.
+    """
+    N, K, ldw = _rows(W, "W")
+    G = K if group_size in (0, None) else int(group_size)
+    use_given = step is not None
+    ngr = K // G if G > 0 and K % G == 0 else 1
+    if not use_given:
+        step = torch.empty((N, ngr), dtype=torch.float32, device=W.device)
+        zero = torch.empty((N, ngr), dtype=torch.uint8, device=W.device)
+    codes = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    _check(load_library().quantize_weight_dint4(_ptr(W), _DTYPES[W.dtype], N, K, ldw, _ptr(s),
+                                                int(group_size or 0), int(use_given), _ptr(codes),
+                                                _ptr(step), _ptr(zero), _stream()),
+           "quantize_weight_dint4")
+    return codes, step, zero
+
+
+def pack_dint4(codes: torch.Tensor, layout: int = LAYOUT_TILED, out=None):
+    N, K = codes.shape
+    packed = out if out is not None else torch.empty((N * K // 2,), dtype=torch.uint8,
+                                                     device=codes.device)
+    _check(load_library().pack_dint4(_ptr(codes), N, K, _ptr(packed), int(layout), _stream()),
+           "pack_dint4")
+    return packed.view(N, K // 2) if layout == LAYOUT_CANONICAL and out is None else packed
+
+
+def unpack_dint4(packed: torch.Tensor, N: int, K: int, layout: int = LAYOUT_TILED):
+    codes = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(load_library().unpack_dint4(_ptr(packed), N, K, _ptr(codes), int(layout), _stream()),
+           "unpack_dint4")
+    return codes
+
+
+def gemm_workspace_bytes(M: int, N: int, K: int, group_size: int = 0,
+                         layout: int = LAYOUT_TILED) -> int:
+    return int(load_library().w4a8_gemm_workspace_bytes(M, N, K, int(group_size or 0), int(layout)))
+
+
+def w4a8_gemm(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.Tensor,
+              zero: torch.Tensor, N: int, K: int, group_size: int = 0, layout: int = LAYOUT_TILED,
+              out_dtype=torch.float16, Y=None, acc_out=None, workspace=None, want_acc=False):
+    """Y [M,N] = dequant(Xq . dINT4(Wp)^T); optionally also the exact int32 accumulators."""
+    M = Xq.shape[0]
+    if Y is None:
+        Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    G = K if group_size in (0, None) else int(group_size)
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((M, N, K // G), dtype=torch.int32, device=Xq.device)
+    need = gemm_workspace_bytes(M, N, K, group_size, layout)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=Xq.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ldy = Y.stride(0) if M > 1 else max(Y.stride(0), N)
+    _check(load_library().w4a8_gemm(_ptr(Xq), _ptr(sx), M, _ptr(Wp), int(layout), _ptr(step),
+                                    _ptr(zero), N, K, int(group_size or 0), _ptr(Y),
+                                    _DTYPES[Y.dtype], ldy, _ptr(acc_out), _ptr(workspace), ws_bytes,
+                                    _stream()), "w4a8_gemm")
+    return (Y, acc_out) if want_acc else Y

@@ -1,0 +1,172 @@
+// Bit-packing of dINT4 codes, two per byte (the 4-bit storage of Sec. 4.2), in the canonical
+// row-major layout and in the tiled layout the GEMM kernels stream (both defined in w4a8.h),
+// plus the inverse maps and the canonical -> tiled conversion.  Pure integer byte shuffling.
+#include "w4a8_common.hpp"
+
+namespace w4a8 {
+
+constexpr int PK_THREADS = 256;
+
+// code -> stored nibble of the tiled layout and back (w4a8.h): integer code c = 2l + h becomes
+// l | h << 3; the special pair (-step/2, +step/2) = codes (15, 14) becomes l = 7 with h = (0, 1).
+__device__ __forceinline__ uint32_t recode(uint32_t c)
+{
+    c &= 15u;
+    return c <= 13u ? ((c >> 1) | ((c & 1u) << 3)) : (c == 14u ? 15u : 7u);
+}
+__device__ __forceinline__ uint32_t uncode(uint32_t e)
+{
+    const uint32_t l = e & 7u, h = e >> 3;
+    return l < 7u ? (2u * l + h) : (h ? 14u : 15u);
+}
+
+__global__ __launch_bounds__(PK_THREADS) void pack_canonical_kernel(
+    const uint8_t *__restrict__ codes, int64_t total_bytes, uint8_t *__restrict__ packed)
+{
+    // rows are contiguous and K is even, so output byte i pairs codes 2i and 2i+1
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < total_bytes;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const uint32_t a = codes[2 * i] & 15u, b = codes[2 * i + 1] & 15u;
+        packed[i] = (uint8_t)(a | (b << 4));
+    }
+}
+
+__global__ __launch_bounds__(PK_THREADS) void unpack_canonical_kernel(
+    const uint8_t *__restrict__ packed, int64_t total_bytes, uint8_t *__restrict__ codes)
+{
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < total_bytes;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const uint32_t b = packed[i];
+        codes[2 * i] = (uint8_t)(b & 15u);
+        codes[2 * i + 1] = (uint8_t)(b >> 4);
+    }
+}
+
+// Word index o of the tiled buffer -> (row n, first column k) of its 8 codes.
+__device__ __forceinline__ void tiled_word_coords(int64_t o, int64_t KT, int64_t &n, int64_t &k)
+{
+    const int q = (int)(o & 3);
+    const int lane = (int)((o >> 2) & 63);
+    const int64_t tile = o >> 8;
+    const int64_t nt = tile / KT, kt = tile % KT;
+    n = nt * TILE_N + (lane & 15);
+    k = kt * TILE_K + (lane >> 4) * 32 + q * 8;
+}
+
+// SRC = 0: one code per byte [N,K];  SRC = 1: canonical packed [N,K/2].
+template <int SRC>
+__global__ __launch_bounds__(PK_THREADS) void pack_tiled_kernel(
+    const uint8_t *__restrict__ src, int64_t N, int64_t K, uint32_t *__restrict__ tiled)
+{
+    const int64_t words = N * K / 8;
+    const int64_t KT = K / TILE_K;
+    for (int64_t o = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; o < words;
+         o += (int64_t)gridDim.x * PK_THREADS) {
+        int64_t n, k;
+        tiled_word_coords(o, KT, n, k);
+        uint32_t c[8];
+        if (SRC == 0) {
+            const uint8_t *p = src + n * K + k;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) c[j] = p[j];
+        } else {
+            const uint8_t *p = src + (n * K + k) / 2;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t b = p[j];
+                c[2 * j] = b & 15u;
+                c[2 * j + 1] = b >> 4;
+            }
+        }
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {  // byte b: low nibble column +b, high nibble column +4+b
+            w |= recode(c[b]) << (8 * b);
+            w |= recode(c[4 + b]) << (8 * b + 4);
+        }
+        tiled[o] = w;
+    }
+}
+
+__global__ __launch_bounds__(PK_THREADS) void unpack_tiled_kernel(
+    const uint32_t *__restrict__ tiled, int64_t N, int64_t K, uint8_t *__restrict__ codes)
+{
+    const int64_t words = N * K / 8;
+    const int64_t KT = K / TILE_K;
+    for (int64_t o = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; o < words;
+         o += (int64_t)gridDim.x * PK_THREADS) {
+        int64_t n, k;
+        tiled_word_coords(o, KT, n, k);
+        const uint32_t w = tiled[o];
+        uint8_t *p = codes + n * K + k;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            p[b] = (uint8_t)uncode((w >> (8 * b)) & 15u);
+            p[4 + b] = (uint8_t)uncode((w >> (8 * b + 4)) & 15u);
+        }
+    }
+}
+
+__global__ __launch_bounds__(PK_THREADS) void fill_i32_kernel(int32_t *__restrict__ p, int64_t n,
+                                                             int32_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * PK_THREADS)
+        p[i] = v;
+}
+
+static unsigned grid_for(int64_t items)
+{
+    int64_t b = (items + PK_THREADS - 1) / PK_THREADS;
+    if (b < 1) b = 1;
+    if (b > 256 * 64) b = 256 * 64;  // grid-stride beyond that
+    return (unsigned)b;
+}
+
+int launch_pack(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout,
+                hipStream_t st)
+{
+    if (N * K == 0) return W4A8_OK;
+    if (layout == W4A8_LAYOUT_CANONICAL) {
+        const int64_t bytes = N * K / 2;
+        hipLaunchKernelGGL(pack_canonical_kernel, dim3(grid_for(bytes)), dim3(PK_THREADS), 0, st,
+                           codes, bytes, packed);
+    } else {
+        hipLaunchKernelGGL(pack_tiled_kernel<0>, dim3(grid_for(N * K / 8)), dim3(PK_THREADS), 0, st,
+                           codes, N, K, (uint32_t *)packed);
+    }
+    return hip_status(hipGetLastError());
+}
+
+int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout,
+                  hipStream_t st)
+{
+    if (N * K == 0) return W4A8_OK;
+    if (layout == W4A8_LAYOUT_CANONICAL) {
+        const int64_t bytes = N * K / 2;
+        hipLaunchKernelGGL(unpack_canonical_kernel, dim3(grid_for(bytes)), dim3(PK_THREADS), 0, st,
+                           packed, bytes, codes);
+    } else {
+        hipLaunchKernelGGL(unpack_tiled_kernel, dim3(grid_for(N * K / 8)), dim3(PK_THREADS), 0, st,
+                           (const uint32_t *)packed, N, K, codes);
+    }
+    return hip_status(hipGetLastError());
+}
+
+int launch_repack_canonical_to_tiled(const uint8_t *canon, int64_t N, int64_t K, uint8_t *tiled,
+                                     hipStream_t st)
+{
+    if (N * K == 0) return W4A8_OK;
+    hipLaunchKernelGGL(pack_tiled_kernel<1>, dim3(grid_for(N * K / 8)), dim3(PK_THREADS), 0, st,
+                       canon, N, K, (uint32_t *)tiled);
+    return hip_status(hipGetLastError());
+}
+
+int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st)
+{
+    if (n == 0) return W4A8_OK;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(n)), dim3(PK_THREADS), 0, st, p, n, v);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace w4a8

@@ -1,0 +1,139 @@
+// Shared device helpers of the gfx950 W4A8 kernels (wave64, CDNA4).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/w4a8.h"
+
+namespace w4a8 {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+
+constexpr int WAVE = 64;
+constexpr int DINT4_P = 13;       // uniform steps of dINT4, 2^4 - 3 (Sec. 4.2)
+constexpr int TILE_N = 16;        // rows of one packed-weight tile (layout 1)
+constexpr int TILE_K = 128;       // columns of one packed-weight tile
+constexpr int TILE_BYTES = 1024;  // 16 * 128 / 2
+
+// ---- element loads, widened exactly to binary32 -------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(__half v) { return __half2float(v); }
+__device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+
+// round-to-nearest-even narrowing of a finite binary32 value
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
+{
+    return __half_as_ushort(__float2half_rn(f));
+}
+
+// ---- wave-level reductions ------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fminf(v, __shfl_xor(v, off, WAVE));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i32(int v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+
+// ---- dINT4 nibble decode for the int8 matrix cores -----------------------------------------
+//
+// A stored nibble is e = l | h << 3 (see the tiled layout in w4a8.h): l in 0..6 names the pair
+// of integer codes (2l, 2l+1), l = 7 the pair (-step/2, +step/2); h picks the upper member,
+// which in every pair lies exactly one step = two half steps above the lower one.
+//
+// With z the zero-point of the (row, group), the weight in half steps is
+//     d = 4 l + 2 h - 2 z   (l < 7)        d = 2 h - 1   (l = 7)          (Eq. 5, second half)
+// The kernels feed the matrix cores  D = 4 (d + beta),  beta = 2 z + b0,  b0 = 1 - (z & 1):
+//     D = (16 l + 4 b0) | (h << 3)          (l < 7)
+//     D = (8 z + 4 b0 - 4) | (h << 3)       (l = 7)
+// Both base terms always have bit 3 clear (that is what the parity-dependent b0 buys), so the
+// per-byte "+8h" is a plain OR with the nibble's own bit 3 -- no carries between the four bytes
+// of a register.  0 <= D <= 108 fits int8.  The GEMM accumulates sum_k Xq * D and removes the
+// bias afterwards with the token's group row-sum:  sum_k Xq d = (acc - 4 beta * rowsum) / 4,
+// which is exact in int32 (4 beta * |rowsum| and |acc| stay below 2^31 for K <= 131072).
+struct DecodeLut {
+    uint32_t lo;     // base levels of l = 0..3, one per byte
+    uint32_t hi;     // base levels of l = 4..7
+    int beta_q;      // 4 * beta = 8 z + 4 b0
+};
+
+__device__ __forceinline__ DecodeLut make_decode_lut(int z)
+{
+    DecodeLut t;
+    const uint32_t c4 = ((uint32_t)(~z) & 1u) << 2;  // 4 * b0
+    const uint32_t c4x4 = c4 * 0x01010101u;
+    t.lo = 0x30201000u | c4x4;
+    t.hi = (0x00605040u | (c4x4 & 0x00ffffffu)) | ((uint32_t)(8 * z + (int)c4 - 4) << 24);
+    t.beta_q = 8 * z + (int)c4;
+    return t;
+}
+
+// Eight nibbles of one packed word -> eight int8 values D, columns +0..3 in `a`, +4..7 in `b`.
+__device__ __forceinline__ void decode_word(uint32_t p, const DecodeLut &t, int &a, int &b)
+{
+    const uint32_t q = p >> 4;
+    const uint32_t ra = __builtin_amdgcn_perm(t.hi, t.lo, p & 0x07070707u);
+    const uint32_t rb = __builtin_amdgcn_perm(t.hi, t.lo, q & 0x07070707u);
+    a = (int)(ra | (p & 0x08080808u));
+    b = (int)(rb | (q & 0x08080808u));
+}
+
+// One lane's 16 packed bytes (32 weights) -> the two 16-byte matrix-core operands.
+__device__ __forceinline__ void decode_lane(const v4u &p, const DecodeLut &t, v4i &w0, v4i &w1)
+{
+    int a, b;
+    decode_word(p.x, t, a, b); w0.x = a; w0.y = b;
+    decode_word(p.y, t, a, b); w0.z = a; w0.w = b;
+    decode_word(p.z, t, a, b); w1.x = a; w1.y = b;
+    decode_word(p.w, t, a, b); w1.z = a; w1.w = b;
+}
+
+// Host-side launchers (defined in the .hip files, called from the C ABI in api.hip).
+int launch_act_quant(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const float *s,
+                     int8_t *Xq, float *sx, hipStream_t st);
+int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                        const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
+                        uint8_t *zero, hipStream_t st);
+int launch_pack(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout,
+                hipStream_t st);
+int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout,
+                  hipStream_t st);
+int launch_repack_canonical_to_tiled(const uint8_t *canon, int64_t N, int64_t K, uint8_t *tiled,
+                                     hipStream_t st);
+int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st);
+int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt, const float *step,
+                const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
+                int64_t ldy, int32_t *acc_out, hipStream_t st);
+int launch_group_rowsum(const int8_t *Xq, int64_t M, int64_t K, int64_t G, int32_t *rs,
+                        hipStream_t st);
+int launch_gemm(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M, const uint8_t *Wt,
+                const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
+                int y_dtype, int64_t ldy, int32_t *acc_out, hipStream_t st);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
+
+}  // namespace w4a8

@@ -1,0 +1,174 @@
+// dINT4 weight quantization of W diag(s)  (Eq. 1 factor Q(W diag(s)); Sec. 4.2, Eq. 5 with b = 4,
+// p = 13; min-max asymmetric ranges per output channel or per group of G input channels, App. A.1).
+//
+// Offline and HBM-bound.  One wavefront owns one (output row, group) segment: a first sweep takes
+// the min / max of w' = W * s with the range extended to contain zero, the lane-0 value of
+// step = (hi - lo) / 13, 1/step and the zero-point z is shared through the wave reduction, and a
+// second sweep (served by the cache) applies Eq. 5 per element.  Every floating-point step is one
+// binary32 operation in the order of the definition (no contraction), divisions are IEEE.
+#include "w4a8_common.hpp"
+
+namespace w4a8 {
+
+constexpr int WQ_THREADS = 256;
+
+template <typename T, int V>
+__device__ __forceinline__ void loadv(const T *p, float (&v)[V])
+{
+    if constexpr (V == 1) {
+        v[0] = to_f32(p[0]);
+    } else if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < V; i += 2) {
+            const float2 a = *reinterpret_cast<const float2 *>(p + i);
+            v[i] = a.x;
+            v[i + 1] = a.y;
+        }
+    } else if constexpr (V == 2) {
+        const uint32_t a = *reinterpret_cast<const uint32_t *>(p);
+        T e[2];
+        __builtin_memcpy(e, &a, 4);
+        v[0] = to_f32(e[0]);
+        v[1] = to_f32(e[1]);
+    } else {
+        static_assert(V == 8, "vector width");
+        const uint4 a = *reinterpret_cast<const uint4 *>(p);
+        T e[8];
+        __builtin_memcpy(e, &a, 16);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = to_f32(e[i]);
+    }
+}
+
+__device__ __forceinline__ uint32_t dint4_code(float w, float istep, int z)
+{
+    const float u = w * istep;
+    if (u > 0.25f && u <= 0.75f) return 14u;     // c1: +step/2
+    if (u >= -0.75f && u < -0.25f) return 15u;   // c2: -step/2
+    int c = (int)__builtin_rintf(u) + z;
+    c = c < 0 ? 0 : c;
+    c = c > DINT4_P ? DINT4_P : c;
+    return (uint32_t)c;
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
+    const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
+    int64_t G, int use_given, uint8_t *__restrict__ codes, float *__restrict__ step,
+    uint8_t *__restrict__ zero)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t ng = K / G;
+    const int64_t seg = (int64_t)blockIdx.x * (WQ_THREADS / WAVE) + (threadIdx.x >> 6);
+    if (seg >= N * ng) return;  // whole wave leaves together
+    const int64_t n = seg / ng, g = seg % ng;
+    const T *w = W + n * ldw + g * G;
+    const float *sg = s ? s + g * G : nullptr;
+
+    float st, istep;
+    int z;
+    if (use_given) {
+        st = step[seg];
+        z = zero[seg];
+        istep = 1.0f / st;
+    } else {
+        float lo = 0.0f, hi = 0.0f;
+        for (int64_t k = (int64_t)lane * V; k < G; k += (int64_t)WAVE * V) {
+            float v[V];
+            loadv<T, V>(w + k, v);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float x = sg ? v[j] * sg[k + j] : v[j];
+                lo = fminf(lo, x);
+                hi = fmaxf(hi, x);
+            }
+        }
+        lo = wave_min(lo);
+        hi = wave_max(hi);
+        if (hi == lo) {
+            st = 1.0f;
+            istep = 1.0f;
+            z = 0;
+        } else {
+            const float range = hi - lo;
+            st = range / 13.0f;
+            istep = 1.0f / st;
+            const float nlo = -lo;
+            float zf = __builtin_rintf(nlo * istep);
+            zf = fminf(fmaxf(zf, 0.0f), 13.0f);
+            z = (int)zf;
+        }
+        if (lane == 0) {
+            step[seg] = st;
+            zero[seg] = (uint8_t)z;
+        }
+    }
+
+    uint8_t *c = codes + n * K + g * G;
+    for (int64_t k = (int64_t)lane * V; k < G; k += (int64_t)WAVE * V) {
+        float v[V];
+        loadv<T, V>(w + k, v);
+        uint32_t q[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float x = sg ? v[j] * sg[k + j] : v[j];
+            q[j] = dint4_code(x, istep, z);
+        }
+        if constexpr (V == 8) {
+            const uint32_t w0 = q[0] | q[1] << 8 | q[2] << 16 | q[3] << 24;
+            const uint32_t w1 = q[4] | q[5] << 8 | q[6] << 16 | q[7] << 24;
+            *reinterpret_cast<uint2 *>(c + k) = make_uint2(w0, w1);
+        } else if constexpr (V == 2) {
+            *reinterpret_cast<uint16_t *>(c + k) = (uint16_t)(q[0] | q[1] << 8);
+        } else {
+            c[k] = (uint8_t)q[0];
+        }
+    }
+}
+
+template <typename T>
+static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, const float *s,
+                                 int64_t G, int use_given, uint8_t *codes, float *step,
+                                 uint8_t *zero, hipStream_t st)
+{
+    const int64_t segs = N * (K / G);
+    if (segs == 0) return W4A8_OK;
+    const int64_t blocks = (segs + (WQ_THREADS / WAVE) - 1) / (WQ_THREADS / WAVE);
+    if (blocks > 0x7fffffffLL) return W4A8_ERR_SHAPE;
+    const auto aligned = [&](int v) {
+        return G % v == 0 && K % v == 0 && (ldw * sizeof(T)) % (v * sizeof(T)) == 0 &&
+               (uintptr_t)W % (v * sizeof(T)) == 0 && (uintptr_t)codes % v == 0 && ldw % v == 0;
+    };
+#define W4A8_WQ_LAUNCH(V_)                                                                        \
+    hipLaunchKernelGGL((weight_quant_kernel<T, V_>), dim3((unsigned)blocks), dim3(WQ_THREADS), 0, \
+                       st, W, N, K, ldw, s, G, use_given, codes, step, zero)
+    if (G >= 512 && aligned(8)) {
+        W4A8_WQ_LAUNCH(8);
+    } else if (aligned(2)) {
+        W4A8_WQ_LAUNCH(2);
+    } else {
+        W4A8_WQ_LAUNCH(1);
+    }
+#undef W4A8_WQ_LAUNCH
+    return hip_status(hipGetLastError());
+}
+
+int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                        const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
+                        uint8_t *zero, hipStream_t st)
+{
+    switch (w_dtype) {
+        case W4A8_F32:
+            return launch_weight_quant_t((const float *)W, N, K, ldw, s, G, use_given, codes, step,
+                                         zero, st);
+        case W4A8_F16:
+            return launch_weight_quant_t((const __half *)W, N, K, ldw, s, G, use_given, codes, step,
+                                         zero, st);
+        case W4A8_BF16:
+            return launch_weight_quant_t((const bf16_t *)W, N, K, ldw, s, G, use_given, codes, step,
+                                         zero, st);
+        default: return W4A8_ERR_DTYPE;
+    }
+}
+
+}  // namespace w4a8

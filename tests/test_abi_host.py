@@ -1,0 +1,98 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "w4a8.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2311_05161_amd as w
+    if not os.path.exists(w.LIB_PATH):
+        from paper_2311_05161_amd.build import build
+        build()
+    return w
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert {"quantize_act_int8", "quantize_weight_dint4", "pack_dint4", "unpack_dint4",
+            "w4a8_gemm", "w4a8_gemm_workspace_bytes", "w4a8_status_string"} <= set(names)
+    cdll = lib.load_library()
+    for n in names:
+        assert hasattr(cdll, n), f"{n} declared in w4a8.h but not exported"
+    assert set(lib.EXPORTS) == set(names)
+
+
+def test_status_strings(lib):
+    seen = {lib.status_string(i) for i in range(6)}
+    assert len(seen) == 6 and lib.status_string(0) == "ok"
+    assert lib.status_string(99) == "unknown status"
+
+
+def test_workspace_sizes(lib):
+    # decode needs none with the tiled layout; prefill needs the per-token group row-sums
+    assert lib.gemm_workspace_bytes(16, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(2048, 4096, 4096, 128, lib.LAYOUT_TILED) == 2048 * 32 * 4
+    assert lib.gemm_workspace_bytes(2048, 4096, 4096, 0, lib.LAYOUT_TILED) == 2048 * 4
+    need = lib.gemm_workspace_bytes(16, 4096, 4096, 128, lib.LAYOUT_CANONICAL)
+    assert need == 4096 * 4096 // 2
+    assert lib.gemm_workspace_bytes(16, 4096, 4096, 100, lib.LAYOUT_TILED) == 0  # invalid group
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    """Fake non-null pointers are never dereferenced: validation happens on the host."""
+    c = lib.load_library()
+    P = ctypes.c_void_p(0x1000)  # 16-byte aligned, never touched
+    Z = ctypes.c_void_p(0)
+    from paper_2311_05161_amd import binding as b
+    # activations
+    assert c.quantize_act_int8(P, 7, 4, 128, 128, Z, P, P, Z) == b.ERR_DTYPE
+    assert c.quantize_act_int8(P, b.F16, 4, 128, 64, Z, P, P, Z) == b.ERR_SHAPE
+    assert c.quantize_act_int8(P, b.F16, -1, 128, 128, Z, P, P, Z) == b.ERR_SHAPE
+    assert c.quantize_act_int8(P, b.F16, 4, 0, 0, Z, P, P, Z) == b.ERR_SHAPE
+    assert c.quantize_act_int8(Z, b.F16, 4, 128, 128, Z, P, P, Z) == b.ERR_NULL
+    assert c.quantize_act_int8(Z, b.F16, 0, 128, 128, Z, Z, Z, Z) == b.OK
+    # weights
+    assert c.quantize_weight_dint4(P, b.F16, 4, 128, 128, Z, 48, 0, P, P, P, Z) == b.ERR_SHAPE
+    assert c.quantize_weight_dint4(P, 9, 4, 128, 128, Z, 0, 0, P, P, P, Z) == b.ERR_DTYPE
+    assert c.quantize_weight_dint4(P, b.F16, 4, 128, 128, Z, 0, 0, Z, P, P, Z) == b.ERR_NULL
+    # packing
+    assert c.pack_dint4(P, 4, 127, P, 0, Z) == b.ERR_SHAPE
+    assert c.pack_dint4(P, 8, 128, P, 1, Z) == b.ERR_SHAPE       # tiled needs N % 16 == 0
+    assert c.pack_dint4(P, 16, 64, P, 1, Z) == b.ERR_SHAPE       # tiled needs K % 128 == 0
+    assert c.pack_dint4(P, 16, 128, P, 5, Z) == b.ERR_DTYPE
+    assert c.unpack_dint4(Z, 16, 128, P, 1, Z) == b.ERR_NULL
+    # gemm
+    def gemm(M=4, N=16, K=128, G=0, layout=1, ydt=b.F16, ldy=16, Xq=P, ws=Z, wsb=0, Wp=P):
+        return c.w4a8_gemm(Xq, P, M, Wp, layout, P, P, N, K, G, P, ydt, ldy, Z, ws, wsb, Z)
+    assert gemm(N=24) == b.ERR_SHAPE
+    assert gemm(K=192) == b.ERR_SHAPE
+    assert gemm(K=256, G=64) == b.ERR_SHAPE          # groups must be multiples of 128
+    assert gemm(K=256, G=100) == b.ERR_SHAPE
+    assert gemm(ldy=8) == b.ERR_SHAPE
+    assert gemm(K=128 * 2048) == b.ERR_SHAPE         # beyond the int32-safe K
+    assert gemm(ydt=b.F32) == b.ERR_DTYPE
+    assert gemm(layout=3) == b.ERR_DTYPE
+    assert gemm(Xq=Z) == b.ERR_NULL
+    assert gemm(Xq=ctypes.c_void_p(0x1004)) == b.ERR_SHAPE   # int8 rows must be 16-byte aligned
+    assert gemm(M=64) == b.ERR_WORKSPACE             # prefill needs the row-sum workspace
+    assert gemm(M=64, ws=P, wsb=8) == b.ERR_WORKSPACE
+    assert gemm(layout=0) == b.ERR_WORKSPACE         # canonical weights are re-tiled into workspace
+    assert gemm(M=0) == b.OK
+
+
+def test_product_path_has_no_cpu_fallback(lib, tmp_path):
+    with pytest.raises(FileNotFoundError):
+        lib.load_library(str(tmp_path / "missing_libw4a8.so"))

@@ -1,0 +1,241 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Integer results (int8 activations, 4-bit codes, packed bytes, zero-points, int32 accumulators)
+and the fp32 quantization parameters (token scales, steps) must be bit-identical; Y must lie
+within 1e-3 relative (fp16) of the oracle's float64 evaluation.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as syn
+from gpu_util import assert_y_close, dev, host, tiled_layout_np
+
+pytestmark = pytest.mark.gpu
+
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2311_05161_amd as w
+    w.load_library()  # raises if the HIP library has not been built: no fallback
+    assert torch.cuda.is_available()
+    return w
+
+
+def _x_for(dtype, X):
+    """Host array widened exactly the way the device sees it, plus the device tensor."""
+    if dtype == "bf16":
+        t = torch.from_numpy(X.astype(np.float32)).to(torch.bfloat16)
+        return t.float().numpy(), t.cuda()
+    a = X.astype(np.float16 if dtype == "f16" else np.float32)
+    return a, dev(a)
+
+
+# --------------------------------------------------------------------------- activations
+ACT_CASES = [
+    # name, M, K, dtype, use_s, ld_pad
+    ("c1_tiny", 16, 768, "f32", False, 0),
+    ("c2_decode", 16, 4096, "f16", True, 0),
+    ("one_row", 1, 4096, "f16", True, 0),
+    ("ragged_rows", 37, 5120, "f16", True, 0),
+    ("wide", 130, 13824, "f16", True, 0),
+    ("many_rows", 2100, 1024, "f16", True, 0),
+    ("bf16", 33, 2048, "bf16", True, 0),
+    ("odd_k_generic", 19, 1001, "f16", True, 0),
+    ("strided", 21, 512, "f32", True, 24),
+    ("strided_unaligned", 5, 264, "f16", True, 3),
+    ("very_wide_generic", 3, 16392, "f16", False, 0),
+]
+
+
+@pytest.mark.parametrize("case", ACT_CASES, ids=[c[0] for c in ACT_CASES])
+def test_act_quant_bit_exact(lib, oracle, case):
+    name, M, K, dtype, use_s, pad = case
+    X, _, s = syn.random_layer(sum(name.encode()) % 1000, M, K, 1, x_dtype="f32")
+    if M > 2:
+        X[1] = 0.0  # an all-zero token
+    Xh, _ = _x_for(dtype, X)
+    buf = torch.zeros((M, K + pad), dtype=TORCH_DT[dtype], device="cuda")
+    buf[:, :K] = torch.from_numpy(Xh).to(TORCH_DT[dtype]).cuda()
+    Xd = buf[:, :K]
+    sd = dev(s) if use_s else None
+    Xq, sx = lib.quantize_act_int8(Xd, sd)
+    ref_q, ref_s = oracle.quantize_act_int8(Xh.astype(np.float32), s if use_s else None)
+    assert np.array_equal(host(sx).view(np.uint32), ref_s.view(np.uint32))
+    assert np.array_equal(host(Xq), ref_q)
+
+
+def test_act_quant_empty(lib):
+    X = torch.zeros((0, 256), dtype=torch.float16, device="cuda")
+    Xq, sx = lib.quantize_act_int8(X)
+    assert Xq.shape == (0, 256) and sx.shape == (0,)
+
+
+# --------------------------------------------------------------------------- weights
+WQ_CASES = [
+    # name, N, K, G, dtype, use_s
+    ("c1_per_channel", 768, 768, 0, "f32", False),
+    ("c2_group128", 512, 4096, 128, "f16", True),
+    ("per_channel_wide", 100, 11008, 0, "f16", True),
+    ("group256_bf16", 48, 1024, 256, "bf16", True),
+    ("group50_pairs", 7, 100, 50, "f16", True),
+    ("group33_scalar", 5, 99, 33, "f32", True),
+    ("one_row", 1, 128, 128, "f16", False),
+]
+
+
+@pytest.mark.parametrize("case", WQ_CASES, ids=[c[0] for c in WQ_CASES])
+def test_weight_quant_bit_exact(lib, oracle, case):
+    name, N, K, G, dtype, use_s = case
+    _, W, s = syn.random_layer(sum(name.encode()) % 1000 + 1, 1, K, N, x_dtype="f32")
+    if N > 3:
+        W[2] = 0.0                 # degenerate group: step 1, z 0
+        W[3] = np.abs(W[3])        # all positive: range extended to 0
+    Wh, Wd = _x_for(dtype, W)
+    sd = dev(s) if use_s else None
+    codes, step, zero = lib.quantize_weight_dint4(Wd, sd, G)
+    rc, rs, rz = oracle.quantize_weight_dint4(Wh.astype(np.float32), s if use_s else None, G)
+    assert np.array_equal(host(step).view(np.uint32), rs.view(np.uint32))
+    assert np.array_equal(host(zero), rz)
+    assert np.array_equal(host(codes), rc)
+    # externally given parameters (clipped ranges): only the per-element rule runs
+    st2 = (rs * np.float32(0.8)).astype(np.float32)
+    codes2, _, _ = lib.quantize_weight_dint4(Wd, sd, G, step=dev(st2), zero=dev(rz))
+    rc2, _, _ = oracle.quantize_weight_dint4(Wh.astype(np.float32), s if use_s else None, G,
+                                             step=st2, zero=rz)
+    assert np.array_equal(host(codes2), rc2)
+
+
+# --------------------------------------------------------------------------- packing
+@pytest.mark.parametrize("N,K", [(16, 128), (48, 384), (768, 768), (4096, 4096)])
+def test_pack_layouts_bit_exact(lib, oracle, N, K):
+    rng = np.random.default_rng(N + K)
+    codes = rng.integers(0, 16, size=(N, K)).astype(np.uint8)
+    cd = dev(codes)
+    p0 = lib.pack_dint4(cd, lib.LAYOUT_CANONICAL)
+    assert np.array_equal(host(p0), oracle.pack_dint4(codes))
+    p1 = lib.pack_dint4(cd, lib.LAYOUT_TILED)
+    assert np.array_equal(host(p1).reshape(-1), tiled_layout_np(codes))
+    assert np.array_equal(host(lib.unpack_dint4(p0, N, K, lib.LAYOUT_CANONICAL)), codes)
+    assert np.array_equal(host(lib.unpack_dint4(p1, N, K, lib.LAYOUT_TILED)), codes)
+
+
+def test_pack_canonical_small_even_k(lib, oracle):
+    codes = np.arange(16, dtype=np.uint8).repeat(2).reshape(1, 32)[:, :30]
+    codes = np.ascontiguousarray(np.tile(codes, (3, 1)))
+    p0 = lib.pack_dint4(dev(codes), lib.LAYOUT_CANONICAL)
+    assert np.array_equal(host(p0), oracle.pack_dint4(codes))
+
+
+# --------------------------------------------------------------------------- GEMM
+def _gemm_case(lib, oracle, seed, M, K, N, G, out_dtype="f16", layout=1, x_dtype="f16"):
+    X, W, s = syn.random_layer(seed, M, K, N, x_dtype=x_dtype)
+    r = oracle.linear_w4a8(X, W, s, G)
+    Xq, sx = lib.quantize_act_int8(dev(X), dev(s))
+    codes, step, zero = lib.quantize_weight_dint4(dev(W), dev(s), G)
+    assert np.array_equal(host(Xq), r["Xq"]) and np.array_equal(host(codes), r["codes"])
+    Wp = lib.pack_dint4(codes, layout)
+    Y, acc = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, layout=layout,
+                           out_dtype=TORCH_DT[out_dtype], want_acc=True)
+    assert np.array_equal(host(acc), r["acc"]), "int32 accumulators differ"
+    assert_y_close(host(Y), r["Y64"], out_dtype)
+    # without the accumulator hook the same Y comes out (bitwise: fixed reduction order)
+    Y2 = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, layout=layout,
+                       out_dtype=TORCH_DT[out_dtype])
+    assert torch.equal(Y, Y2)
+    return r, Y
+
+
+DECODE_CASES = [
+    # name, M, K, N, G
+    ("c1_tiny", 16, 768, 768, 0),
+    ("c2_m1", 1, 4096, 4096, 128),
+    ("c2_m5", 5, 4096, 4096, 128),
+    ("c2_m16", 16, 4096, 4096, 128),
+    ("g256_ragged", 7, 1280, 400, 256),
+    ("per_channel_k_tail", 16, 1152, 272, 0),
+    ("one_tile", 3, 128, 16, 128),
+]
+
+
+@pytest.mark.parametrize("case", DECODE_CASES, ids=[c[0] for c in DECODE_CASES])
+def test_gemm_decode_parity(lib, oracle, case):
+    name, M, K, N, G = case
+    _gemm_case(lib, oracle, 11 + len(name), M, K, N, G, x_dtype="f32" if "c1" in name else "f16")
+
+
+PREFILL_CASES = [
+    ("m17", 17, 384, 272, 0),
+    ("m64_g128", 64, 512, 256, 128),
+    ("m100_ragged", 100, 640, 528, 0),
+    ("m130_g128", 130, 1024, 304, 128),
+    ("m300", 300, 768, 1040, 0),
+    ("m300_g256", 300, 768, 512, 256),
+    ("m600_multi_block", 600, 1024, 784, 0),
+]
+
+
+@pytest.mark.parametrize("case", PREFILL_CASES, ids=[c[0] for c in PREFILL_CASES])
+def test_gemm_prefill_parity(lib, oracle, case):
+    name, M, K, N, G = case
+    _gemm_case(lib, oracle, 23 + len(name), M, K, N, G)
+
+
+def test_gemm_bf16_output_and_canonical_layout(lib, oracle):
+    _gemm_case(lib, oracle, 5, 12, 512, 64, 128, out_dtype="bf16")
+    _gemm_case(lib, oracle, 6, 40, 512, 64, 0, out_dtype="bf16")
+    _gemm_case(lib, oracle, 7, 9, 256, 32, 128, layout=0)
+    _gemm_case(lib, oracle, 8, 70, 256, 48, 0, layout=0)
+
+
+def test_gemm_every_code_and_zero_point(lib, oracle):
+    """Random codes / zero-points / extreme activations straight into the GEMM (no quantizer)."""
+    rng = np.random.default_rng(77)
+    for M in (4, 48):
+        K, N, G = 512, 64, 128
+        Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+        Xq[0] = 127
+        Xq[1] = -127
+        codes = rng.integers(0, 16, size=(N, K)).astype(np.uint8)
+        codes[0] = 13
+        codes[1] = 0
+        zero = rng.integers(0, 14, size=(N, K // G)).astype(np.uint8)
+        zero[0] = 0
+        zero[1] = 13
+        step = rng.uniform(0.001, 0.1, size=(N, K // G)).astype(np.float32)
+        sx = rng.uniform(0.01, 1.0, size=M).astype(np.float32)
+        acc_ref = oracle.int_gemm(Xq, oracle.pack_dint4(codes), zero, G)
+        _, y64 = oracle.dequant_epilogue(acc_ref, sx, step)
+        Wp = lib.pack_dint4(dev(codes), lib.LAYOUT_TILED)
+        Y, acc = lib.w4a8_gemm(dev(Xq), dev(sx), Wp, dev(step), dev(zero), N, K, G, want_acc=True)
+        assert np.array_equal(host(acc), acc_ref)
+        assert_y_close(host(Y), y64)
+
+
+def test_gemm_empty_batch(lib):
+    N, K = 32, 128
+    Xq = torch.zeros((0, K), dtype=torch.int8, device="cuda")
+    sx = torch.zeros((0,), dtype=torch.float32, device="cuda")
+    Wp = torch.zeros((N * K // 2,), dtype=torch.uint8, device="cuda")
+    step = torch.ones((N, 1), dtype=torch.float32, device="cuda")
+    zero = torch.zeros((N, 1), dtype=torch.uint8, device="cuda")
+    Y = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, 0)
+    assert Y.shape == (0, N)
+
+
+def test_aqas_power_of_two_invariance_on_gpu(lib, oracle):
+    """s = 2^j for every channel rescales sx and step exactly and leaves Y unchanged (Eq. 1)."""
+    X, W, _ = syn.random_layer(3, 8, 512, 64)
+    outs = []
+    for j in (0, 2):
+        s = dev(np.full(512, 2.0 ** j, np.float32))
+        Xq, sx = lib.quantize_act_int8(dev(X), s)
+        codes, step, zero = lib.quantize_weight_dint4(dev(W), s, 128)
+        Y = lib.w4a8_gemm(Xq, sx, lib.pack_dint4(codes), step, zero, 64, 512, 128)
+        outs.append((host(Xq), host(sx), host(codes), host(step), host(Y)))
+    a, b = outs
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[2], b[2])
+    assert np.array_equal(a[1], b[1] * 4) and np.array_equal(a[3] * 4, b[3])
+    assert np.array_equal(a[4], b[4])
