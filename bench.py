@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 (dINT4 x INT8) linear layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-graph] [--no-prefill] [--no-cpu]
+
+A step is one pass of the online hot path -- quantize_act_int8 then w4a8_gemm -- over one batch
+of the decode workload (LLaMA-7B attention projection, M=16, K=N=4096, group-128 dINT4), with the
+weights of each step taken from a ring of distinct quantized copies larger than the 256 MB
+Infinity Cache so that they really stream from HBM.  The offline rows (weight quantization and
+packing) run once per weight matrix before the timed region, as in the method, and are timed
+separately ("offline").  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
+
+
+def decode_bytes(M, N, K, G):
+    """Algorithmic HBM bytes of one decode GEMM launch: packed weights, group parameters
+    (fp32 step + u8 zero), int8 activations, token scales, fp16 output."""
+    return N * K // 2 + N * (K // G) * 5 + M * K + 4 * M + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4096)
+    ap.add_argument("--warmup", type=int, default=256)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (compute-bound) side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2311_05161_amd as w
+    import synthetic_inputs as syn
+
+    lib = w.load_library()  # fails loudly if the HIP library is missing: no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    st = ctypes.c_void_p(stream.cuda_stream)
+
+    # ------------------------------------------------------------------ workload: C2, M = 16
+    cfg = syn.CONFIGS["C2"]
+    M, K, N, G = cfg["M"], cfg["K"], cfg["N"], cfg["group_size"]
+    X, W, s, _ = syn.make_layer("C2")
+    Xd, Wd, sd = torch.from_numpy(X).to(dev), torch.from_numpy(W).to(dev), torch.from_numpy(s).to(dev)
+
+    # offline rows: weight quantization + packing (timed, reported separately)
+    def offline():
+        codes, step, zero = w.quantize_weight_dint4(Wd, sd, G)
+        return w.pack_dint4(codes, w.LAYOUT_TILED), step, zero
+    offline()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        Wp, step, zero = offline()
+    torch.cuda.synchronize()
+    offline_ms = (time.perf_counter() - t0) / 5 * 1e3
+
+    per_copy = decode_bytes(M, N, K, G)
+    R = max(2, -(-2 * 256 * 2 ** 20 // per_copy))  # ring >= 2 x Infinity Cache
+    ring = []
+    for r in range(R):  # distinct buffers; rolled so that no two copies hold the same rows
+        sh = (r * 16) % N
+        ring.append((torch.roll(Wp.view(N // 16, -1), r, 0).contiguous().view(-1),
+                     torch.roll(step, sh, 0).contiguous(), torch.roll(zero, sh, 0).contiguous()))
+    ring[0] = (Wp, step, zero)
+
+    Xq = torch.empty((M, K), dtype=torch.int8, device=dev)
+    sx = torch.empty((M,), dtype=torch.float32, device=dev)
+    Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+    P = lambda t: ctypes.c_void_p(t.data_ptr())
+    aq_args = (P(Xd), w.F16, M, K, K, P(sd), P(Xq), P(sx), st)
+    gm_args = [(P(Xq), P(sx), M, P(wp), w.LAYOUT_TILED, P(sp), P(zp), N, K, G, P(Y), w.F16, N,
+                None, None, 0, st) for (wp, sp, zp) in ring]
+
+    def step_fn(i):
+        rc = lib.quantize_act_int8(*aq_args)
+        rc |= lib.w4a8_gemm(*gm_args[i % R])
+        if rc:
+            raise RuntimeError(f"kernel launch failed: status {rc}")
+
+    # parity of this very launch configuration against the CPU oracle (also the CPU baseline)
+    step_fn(0)
+    torch.cuda.synchronize()
+    y_gpu = Y.float().cpu().numpy().astype(np.float64)
+    cpu_baseline, parity = None, None
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
+        oracle.linear_w4a8(X[:1], W[:16], s, G)  # load + warm
+        codes_h, step_h, zero_h = oracle.quantize_weight_dint4(W, s, G)
+        packed_h = oracle.pack_dint4(codes_h)
+        t0 = time.perf_counter()
+        Xq_h, sx_h = oracle.quantize_act_int8(X, s)
+        acc_h = oracle.int_gemm(Xq_h, packed_h, zero_h, G)
+        y32_h, y64_h = oracle.dequant_epilogue(acc_h, sx_h, step_h)
+        cpu_s = time.perf_counter() - t0
+        cpu_baseline = {"value": round(N * K / 2 / cpu_s / 1e9, 4), "unit": "GB/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"the full step once (act-quant + int GEMM + dequant, M={M} K={K} N={N} "
+                                  f"g{G}), {cpu_s:.2f} s"}
+        floor = 1e-3 * np.sqrt(np.mean(y64_h ** 2, axis=1, keepdims=True))
+        ok = bool(np.all(np.abs(y_gpu - y64_h) <= 1e-3 * np.maximum(np.abs(y64_h), floor)))
+        parity = {"Xq_bit_exact": bool(np.array_equal(Xq.cpu().numpy(), Xq_h)),
+                  "codes_bit_exact": bool(np.array_equal(
+                      w.unpack_dint4(Wp, N, K, w.LAYOUT_TILED).cpu().numpy(), codes_h)),
+                  "Y_within_1e-3": ok}
+
+    # ------------------------------------------------------------------ timed region
+    use_graph = not args.no_graph
+    steps, warmup = args.steps, args.warmup
+    graph = None
+    if use_graph:
+        # one graph = one trip round the ring (R steps, 2R kernels); replayed steps / R times
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            st_side = ctypes.c_void_p(side.cuda_stream)
+            aq_g = aq_args[:-1] + (st_side,)
+            gm_g = [a[:-1] + (st_side,) for a in gm_args]
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(R):
+                    rc = lib.quantize_act_int8(*aq_g) | lib.w4a8_gemm(*gm_g[i])
+                    assert rc == 0
+        stream.wait_stream(side)
+        steps = max(R, steps // R * R)
+        warmup = max(R, -(-warmup // R) * R)
+        for _ in range(warmup // R):
+            graph.replay()
+        torch.cuda.synchronize()
+        # a replay must reproduce the eager result exactly
+        y_eager = Y.clone()
+        step_fn(R - 1)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, y_eager), "graph replay differs from eager launch"
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps // R):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        for i in range(warmup):
+            step_fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step_fn(i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed / steps * 1e3
+    weight_gbs = N * K / 2 / (elapsed / steps) / 1e9
+
+    # ------------------------------------------------------------------ roofline of the dominant kernel
+    # the decode GEMV, timed with HIP events on the launch stream: per-launch pairs around every GEMM
+    # launch of a second pass over the same steps (the act-quant kernels still run in between)
+    n_ev = min(steps, 1024)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for i in range(64):
+        step_fn(i)
+    torch.cuda.synchronize()
+    for i in range(n_ev):
+        lib.quantize_act_int8(*aq_args)
+        evs[i][0].record(stream)
+        lib.w4a8_gemm(*gm_args[i % R])
+        evs[i][1].record(stream)
+    torch.cuda.synchronize()
+    per_launch_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    # and back-to-back launches of the GEMM alone between one pair of events
+    L = 2048
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(L):
+        lib.w4a8_gemm(*gm_args[i % R])
+    e1.record(stream)
+    torch.cuda.synchronize()
+    loop_ms = e0.elapsed_time(e1) / L
+    kern_ms = float(np.median(per_launch_ms))
+    achieved = per_copy / (kern_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemv_kernel (w4a8_gemm, M<=16)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": per_copy, "avg_launch_us": round(kern_ms * 1e3, 3),
+                "mean_launch_us": round(float(per_launch_ms.mean()) * 1e3, 3),
+                "back_to_back_us": round(loop_ms * 1e3, 3)}
+
+    # ------------------------------------------------------------------ prefill side (compute-bound)
+    prefill = []
+    if not args.no_prefill:
+        for name in ("C3_up", "C3_down"):
+            c = syn.CONFIGS[name]
+            Mp, Kp, Np, Gp = c["M"], c["K"], c["N"], c["group_size"]
+            Xp, Wpf, sp, _ = syn.make_layer(name)
+            Xpd, Wpd, spd = (torch.from_numpy(a).to(dev) for a in (Xp, Wpf, sp))
+            cq, stq, zq = w.quantize_weight_dint4(Wpd, spd, Gp)
+            wpk = w.pack_dint4(cq, w.LAYOUT_TILED)
+            del cq, Wpd
+            xq, sxp = w.quantize_act_int8(Xpd, spd)
+            ws = torch.empty((max(1, w.gemm_workspace_bytes(Mp, Np, Kp, Gp)),), dtype=torch.uint8, device=dev)
+            Yp = torch.empty((Mp, Np), dtype=torch.float16, device=dev)
+            for _ in range(3):
+                w.w4a8_gemm(xq, sxp, wpk, stq, zq, Np, Kp, Gp, Y=Yp, workspace=ws)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            reps = 20
+            for _ in range(reps):
+                w.w4a8_gemm(xq, sxp, wpk, stq, zq, Np, Kp, Gp, Y=Yp, workspace=ws)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            tops = 2.0 * Mp * Np * Kp / (ms * 1e-3) / 1e12
+            prefill.append({"workload": f"{name} M={Mp} K={Kp} N={Np} per-channel", "ms": round(ms, 4),
+                            "TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
+            del Xpd, wpk, xq, Yp, ws
+
+    out = {
+        "metric": METRIC, "value": round(weight_gbs, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"C2 LLaMA-7B attention projection decode: M={M} K={K} N={N} group-{G} dINT4; "
+                               f"step = quantize_act_int8 + w4a8_gemm; ring of {R} weight copies "
+                               f"({R * per_copy / 2 ** 20:.0f} MiB)",
+                   "launch": "hip-graph" if use_graph else "eager"},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
+        "offline": {"what": "quantize_weight_dint4 + pack_dint4 (tiled), once per weight matrix",
+                    "ms": round(offline_ms, 4),
+                    "GBps": round((N * K * 2 + N * K + N * K + N * K // 2) / (offline_ms * 1e-3) / 1e9, 1)},
+        "prefill": prefill,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
