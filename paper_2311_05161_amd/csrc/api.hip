@@ -6,7 +6,7 @@ using namespace w4a8;
 
 namespace {
 
-constexpr int64_t MAX_K = 131072;  // keeps the biased int32 accumulators below 2^31
+constexpr int64_t MAX_K = 65536;   // keeps the biased int32 accumulators far below 2^31
 constexpr size_t WS_ALIGN = 256;
 
 inline size_t align_up(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
@@ -23,12 +23,13 @@ inline bool resolve_group(int64_t K, int64_t &G)
 struct WsPlan {
     size_t repack_off, repack_bytes;  // canonical -> tiled copy of the weights
     size_t rs_off, rs_bytes;          // per-token group row-sums (M > 16 only)
+    size_t part_off, part_bytes;      // fp32 partial sums of a K-split decode GEMV (M <= 16 only)
     size_t total;
 };
 
 WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
 {
-    WsPlan w{0, 0, 0, 0, 0};
+    WsPlan w{0, 0, 0, 0, 0, 0, 0};
     size_t off = 0;
     if (layout == W4A8_LAYOUT_CANONICAL) {
         w.repack_off = off;
@@ -39,6 +40,10 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
         w.rs_off = off;
         w.rs_bytes = (size_t)(M * (K / G)) * sizeof(int32_t);
         off = align_up(off + w.rs_bytes);
+    } else if (M > 0 && N > 0) {
+        w.part_off = off;
+        w.part_bytes = plan_gemv(M, N, K, G).partial_bytes;
+        off = align_up(off + w.part_bytes);
     }
     w.total = off;
     return w;
@@ -118,7 +123,9 @@ int unpack_dint4(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, in
 size_t w4a8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout)
 {
     int64_t G = group_size;
-    if (M < 0 || N < 0 || !resolve_group(K, G) || !valid_layout(layout)) return 0;
+    if (M < 0 || N < 0 || !resolve_group(K, G) || !valid_layout(layout) || K % TILE_K != 0 ||
+        G % TILE_K != 0 || N % TILE_N != 0)
+        return 0;
     return plan_workspace(M, N, K, G, layout).total;
 }
 
@@ -133,7 +140,7 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
     int64_t G = group_size;
     if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
     if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K || ldy < N ||
-        M > 0x7fffffffLL || N > 0x7fffffffLL)
+        M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL)  // 32-bit byte offsets into the weights
         return W4A8_ERR_SHAPE;
     if (M == 0 || N == 0) return W4A8_OK;
     if (!Xq || !sx || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;
@@ -161,7 +168,8 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
             const int rc = launch_fill_i32(acc_out, M * N * (K / G), 0, st);
             if (rc != W4A8_OK) return rc;
         }
-        return launch_gemv(Xq, sx, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out, st);
+        return launch_gemv(Xq, sx, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out,
+                           (float *)(wsb + ws.part_off), st);
     }
     int32_t *rs = (int32_t *)(wsb + ws.rs_off);
     const int rc = launch_group_rowsum(Xq, M, K, G, rs, st);

@@ -125,9 +125,20 @@ int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, i
 int launch_repack_canonical_to_tiled(const uint8_t *canon, int64_t N, int64_t K, uint8_t *tiled,
                                      hipStream_t st);
 int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st);
+// Launch shape of the decode GEMV for a problem size (also sizes its K-split workspace).
+struct GemvPlan {
+    int splits;            // K is cut into this many ranges, each handled by its own workgroups
+    int kt_per_split;      // 128-column k-tiles per range
+    int at;                // k-tile slots per compute wave (template instance)
+    int q;                 // consecutive 16-channel n-tiles per workgroup
+    int blocks_per_split;
+    int lds_bytes;
+    size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1, else 0
+};
+GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G);
 int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt, const float *step,
                 const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                int64_t ldy, int32_t *acc_out, hipStream_t st);
+                int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
 int launch_group_rowsum(const int8_t *Xq, int64_t M, int64_t K, int64_t G, int32_t *rs,
                         hipStream_t st);
 int launch_gemm(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M, const uint8_t *Wt,
