@@ -252,6 +252,7 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G)
     pl.at = tpw <= 4 ? 4 : (tpw <= 6 ? 6 : 8);
     const bool grouped = G != K;
     // equal numbers of n-tiles per workgroup, about one workgroup per CU
+    // (more, shorter-lived workgroups measured slower: each one reloads its activation fragments)
     int q = (int)(((int64_t)NT * pl.splits + 255) / 256);
     const int recs = grouped ? pl.kt_per_split : 1;
     const int q_lds = GV_LDS_BUDGET / (recs * 16 * 16);

@@ -74,7 +74,7 @@ __device__ __forceinline__ int wave_sum_i32(int v)
 // per-byte "+8h" is a plain OR with the nibble's own bit 3 -- no carries between the four bytes
 // of a register.  0 <= D <= 108 fits int8.  The GEMM accumulates sum_k Xq * D and removes the
 // bias afterwards with the token's group row-sum:  sum_k Xq d = (acc - 4 beta * rowsum) / 4,
-// which is exact in int32 (4 beta * |rowsum| and |acc| stay below 2^31 for K <= 131072).
+// which is exact in int32 (4 beta * |rowsum| and |acc| stay below 2^31 for K <= 65536).
 struct DecodeLut {
     uint32_t lo;     // base levels of l = 0..3, one per byte
     uint32_t hi;     // base levels of l = 4..7

@@ -49,6 +49,8 @@ def test_workspace_sizes(lib):
     need = lib.gemm_workspace_bytes(16, 4096, 4096, 128, lib.LAYOUT_CANONICAL)
     assert need == 4096 * 4096 // 2
     assert lib.gemm_workspace_bytes(16, 4096, 4096, 100, lib.LAYOUT_TILED) == 0  # invalid group
+    # K > 8192 at decode is split over workgroups: fp32 partial sums [splits][M][N]
+    assert lib.gemm_workspace_bytes(16, 5120, 13824, 128, lib.LAYOUT_TILED) == 2 * 16 * 5120 * 4
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):

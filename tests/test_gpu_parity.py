@@ -157,6 +157,11 @@ DECODE_CASES = [
     ("g256_ragged", 7, 1280, 400, 256),
     ("per_channel_k_tail", 16, 1152, 272, 0),
     ("one_tile", 3, 128, 16, 128),
+    ("k_split_2_g128", 16, 9216, 48, 128),        # K > 8192: two K-ranges + deterministic combine
+    ("k_split_2_per_channel", 5, 11008, 32, 0),
+    ("k_split_3_ragged", 9, 16512, 16, 384),
+    ("many_n_tiles_per_block", 16, 512, 9232, 128),  # 577 n-tiles: several per workgroup, ragged
+    ("many_n_tiles_per_channel", 2, 1024, 4640, 0),
 ]
 
 
