@@ -22,7 +22,7 @@ inline bool resolve_group(int64_t K, int64_t &G)
 
 struct WsPlan {
     size_t repack_off, repack_bytes;  // canonical -> tiled copy of the weights
-    size_t rs_off, rs_bytes;          // per-token group row-sums (M > 16 only)
+    size_t rs_off, rs_bytes;          // per-token row-sums (M > 16, per-channel weights only)
     size_t part_off, part_bytes;      // fp32 partial sums of a K-split decode GEMV (M <= 16 only)
     size_t total;
 };
@@ -37,9 +37,11 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
         off = align_up(off + w.repack_bytes);
     }
     if (M > 16) {
-        w.rs_off = off;
-        w.rs_bytes = (size_t)(M * (K / G)) * sizeof(int32_t);
-        off = align_up(off + w.rs_bytes);
+        if (G == K) {  // per-channel weights: bias removal needs one row-sum per token
+            w.rs_off = off;
+            w.rs_bytes = (size_t)M * sizeof(int32_t);
+            off = align_up(off + w.rs_bytes);
+        }
     } else if (M > 0 && N > 0) {
         w.part_off = off;
         w.part_bytes = plan_gemv(M, N, K, G).partial_bytes;
@@ -171,9 +173,12 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
         return launch_gemv(Xq, sx, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out,
                            (float *)(wsb + ws.part_off), st);
     }
-    int32_t *rs = (int32_t *)(wsb + ws.rs_off);
-    const int rc = launch_group_rowsum(Xq, M, K, G, rs, st);
-    if (rc != W4A8_OK) return rc;
+    int32_t *rs = nullptr;
+    if (G == K) {
+        rs = (int32_t *)(wsb + ws.rs_off);
+        const int rc = launch_group_rowsum(Xq, M, K, G, rs, st);
+        if (rc != W4A8_OK) return rc;
+    }
     return launch_gemm(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out, st);
 }
 

@@ -2,67 +2,82 @@
 // (Eq. 1 product on the integer operands with int32 accumulation; Eq. 5 second half fused as the
 // dequantizing epilogue; the dINT4 x INT8 multiply-accumulate of Sec. 4.3).
 //
-// A workgroup of 4 wavefronts computes a BM x 256 output tile; wave w owns all BM token rows of
-// 64 output channels, so each packed-weight tile is decoded by exactly one wave: the wave reads
-// its four 1 KB weight tiles per 128 columns of K straight from global memory (16 bytes per lane,
-// prefetched one step ahead), decodes them in registers through the per-(row, group) LUT and
-// reuses every decoded operand for all BM / 16 token sub-tiles.  The int8 activations are staged
-// through LDS (double buffered, 16-byte chunks XOR-swizzled by row so that both the staging
-// writes and the ds_read_b128 operand reads are bank-conflict free) and shared by the 4 waves.
-// The decode bias is removed with per-token group row-sums computed by a small pre-pass.
+// v_mfma_i32_32x32x32_i8 is the instruction to build on: measured on MI355X it sustains ~4.5 POPS,
+// twice what v_mfma_i32_16x16x64_i8 reaches.  A workgroup of 4 wavefronts computes a BM x 256
+// output tile; wave w owns all BM token rows of 64 output channels (two 32-channel sub-tiles), so
+// every packed weight is decoded by exactly one wave and never touches LDS: per 128 columns of K
+// the wave reads 4 KB of packed weights straight from global memory (16 bytes per lane per load,
+// prefetched one k-tile ahead), turns the nibbles into int8 through the per-channel register LUT
+// and reuses each decoded operand for all BM / 32 token sub-tiles.  The int8 activations are staged
+// through LDS (double buffered, 16-byte chunks XOR-swizzled by row so both the staging writes and
+// the ds_read_b128 operand reads are conflict free) and shared by the 4 waves.
+//
+// Per-channel weights use the biased decode (7 operations per 8 weights); the bias is removed once,
+// in the epilogue, with per-token row-sums from a small pre-pass.  Group-wise weights must rescale
+// every accumulator once per group, so they use the signed decode (no bias term) and keep fp32
+// running sums next to the int32 group accumulators (BM <= 128).
 #include "w4a8_common.hpp"
 
 namespace w4a8 {
 
-constexpr int GM_THREADS = 256;
-constexpr int GM_BN = 256;       // output channels per workgroup
-constexpr int GM_NS = 4;         // 16-channel sub-tiles per wave
+typedef int v16i __attribute__((ext_vector_type(16)));
 
-// ---- per-token group row-sums of Xq: rs[m,g] = sum_{k in g} Xq[m,k] -------------------------
-__global__ __launch_bounds__(256) void group_rowsum_kernel(const int8_t *__restrict__ Xq, int64_t M,
-                                                           int K, int G, int32_t *__restrict__ rs)
+constexpr int GM_BN = 256;  // output channels per workgroup
+constexpr int GM_NS = 2;    // 32-channel sub-tiles per wave
+constexpr int GM_OOB = 0x7fff0000;
+
+// ---- per-token row-sums of Xq over all of K (bias removal of the per-channel path) ------------
+__global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ Xq, int64_t M, int K,
+                                                     int32_t *__restrict__ rs)
 {
     const int lane = threadIdx.x & 63;
-    const int ng = K / G;
-    const int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (seg >= M * ng) return;
-    const int64_t m = seg / ng;
-    const int g = (int)(seg % ng);
-    const int *x = reinterpret_cast<const int *>(Xq + m * K + (int64_t)g * G);
+    const int64_t m = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const v4i *x = reinterpret_cast<const v4i *>(Xq + m * K);
     int sum = 0;
-    for (int i = lane; i < G / 4; i += WAVE) sum = __builtin_amdgcn_sdot4(x[i], 0x01010101, sum, false);
+    for (int i = lane; i < K / 16; i += WAVE) {
+        const v4i v = x[i];
+        sum = __builtin_amdgcn_sdot4(v.x, 0x01010101, sum, false);
+        sum = __builtin_amdgcn_sdot4(v.y, 0x01010101, sum, false);
+        sum = __builtin_amdgcn_sdot4(v.z, 0x01010101, sum, false);
+        sum = __builtin_amdgcn_sdot4(v.w, 0x01010101, sum, false);
+    }
     sum = wave_sum_i32(sum);
-    if (lane == 0) rs[seg] = sum;
+    if (lane == 0) rs[m] = sum;
 }
 
 int launch_group_rowsum(const int8_t *Xq, int64_t M, int64_t K, int64_t G, int32_t *rs,
                         hipStream_t st)
 {
-    const int64_t segs = M * (K / G);
-    if (segs == 0) return W4A8_OK;
-    hipLaunchKernelGGL(group_rowsum_kernel, dim3((unsigned)((segs + 3) / 4)), dim3(256), 0, st, Xq,
-                       M, (int)K, (int)G, rs);
+    (void)G;
+    if (M == 0) return W4A8_OK;
+    hipLaunchKernelGGL(rowsum_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, Xq, M, (int)K,
+                       rs);
     return hip_status(hipGetLastError());
 }
 
 // ---- the tile kernel ------------------------------------------------------------------------
-template <int BM, bool GROUPED>
-__global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
+// WM wave rows x 4 wave columns; a wave owns BM / WM token rows of 64 output channels.  With
+// WM = 2 every SIMD hosts two waves, so one wave's MFMAs cover the other's LDS and decode latency.
+template <int BM, int WM, bool GROUPED>
+__global__ __launch_bounds__(WM * 256) void gemm_kernel(
     const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ rs,
-    int M, const v4u *__restrict__ Wt, const float *__restrict__ step,
+    int M, const uint8_t *__restrict__ Wt, const float *__restrict__ step,
     const uint8_t *__restrict__ zero, int N, int K, int tiles_per_group, int ng,
     uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store,
     int32_t *__restrict__ acc_out, int grid_m, int grid_n)
 {
-    constexpr int MS = BM / 16;               // token sub-tiles, all owned by every wave
+    constexpr int GM_THREADS = WM * 256;
+    constexpr int WROWS = BM / WM;                 // token rows per wave
+    constexpr int MS = WROWS / 32;                 // 32-token sub-tiles per wave
     constexpr int LD_ITERS = BM * 8 / GM_THREADS;  // 16-byte chunks of the A tile per thread
     __shared__ __attribute__((aligned(16))) uint8_t lds[2][BM * TILE_K];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int ln = lane & 15;
-    const int kb = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r32 = lane & 31;   // operand row: output channel (weights) / token (activations)
+    const int kh = lane >> 5;    // which 16 of a k-step's 32 input channels this lane holds
     const int KT = K / TILE_K;
 
     // Workgroups are handed to the 8 XCDs round-robin; renumber so that each XCD works on a
@@ -76,41 +91,57 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     const int bm = bid % grid_m;
     const int bn = bid / grid_m;
     const int m0 = bm * BM;
-    const int n0 = bn * GM_BN + wave * (GM_NS * TILE_N);  // first output channel of this wave
+    const int nb0 = bn * GM_BN;                        // first output channel of the workgroup
+    const int wn = wave & 3;                           // wave column
+    const int wr0 = (wave >> 2) * WROWS;               // first token row of this wave within the tile
+    const int n0 = nb0 + wn * (GM_NS * 32);            // first output channel of this wave
 
+    __amdgpu_buffer_rsrc_t rw =
+        __builtin_amdgcn_make_buffer_rsrc((void *)Wt, 0, (int)((int64_t)N * K / 2), 0x00020000);
+    __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc((void *)Xq, 0, (int)((int64_t)M * K), 0x00020000);
+
+    // Weight operand of k-step s = 2 sp + h of a k-tile: MFMA lane (r32, kh) takes half h of the 16
+    // bytes that lane (r32 % 16) + 16 (2 sp + kh) of tile (n / 16, kt) holds (w4a8.h), i.e. input
+    // channels (2 sp + kh) * 32 + h * 16 + 0..15 of the tile.  One 16-byte load covers two k-steps.
+    int wvoff[GM_NS];   // per-lane byte offset inside the wave's tile row (out of range if n >= N)
+    int wsoff[GM_NS];   // byte offset of tile (n-subtile, kt = 0)
     bool ns_valid[GM_NS];
-    const v4u *wp[GM_NS];
 #pragma unroll
     for (int ns = 0; ns < GM_NS; ++ns) {
-        const int nn = n0 + ns * TILE_N;
+        const int nn = n0 + ns * 32;
         ns_valid[ns] = nn < N;
-        wp[ns] = Wt + (int64_t)(ns_valid[ns] ? nn / TILE_N : 0) * KT * WAVE + lane;
+        const bool lane_ok = nn + r32 < N;
+        wvoff[ns] = lane_ok ? (r32 >> 4) * KT * TILE_BYTES + ((r32 & 15) + 16 * kh) * 16 : GM_OOB;
+        wsoff[ns] = ns_valid[ns] ? (nn / TILE_N) * KT * TILE_BYTES : 0;
     }
 
-    v4i acc[MS][GM_NS];
+    v16i acc[MS][GM_NS];
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-        for (int ns = 0; ns < GM_NS; ++ns) acc[ms][ns] = v4i{0, 0, 0, 0};
+        for (int ns = 0; ns < GM_NS; ++ns)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[ms][ns][r] = 0;
 
     constexpr int YS = GROUPED ? MS : 1;
-    v4f y[YS][GM_NS];
+    float y[YS][GM_NS][16];
 #pragma unroll
     for (int ms = 0; ms < YS; ++ms)
 #pragma unroll
-        for (int ns = 0; ns < GM_NS; ++ns) y[ms][ns] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int ns = 0; ns < GM_NS; ++ns)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) y[ms][ns][r] = 0.f;
 
     // A-tile staging: chunk c (16 bytes) of row r lives at r*128 + ((c ^ (r & 7)) * 16)
-    v4i areg[LD_ITERS];
+    v4u areg[LD_ITERS];
     auto load_a = [&](int kt) {
 #pragma unroll
         for (int i = 0; i < LD_ITERS; ++i) {
             const int idx = tid + i * GM_THREADS;
             const int row = idx >> 3, ch = idx & 7;
-            areg[i] = v4i{0, 0, 0, 0};
-            if (m0 + row < M)
-                areg[i] = *reinterpret_cast<const v4i *>(Xq + (int64_t)(m0 + row) * K +
-                                                         (int64_t)kt * TILE_K + ch * 16);
+            // rows >= M lie beyond the buffer and read as zero
+            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (m0 + row) * K + ch * 16, kt * TILE_K, 0);
         }
     };
     auto store_a = [&](int buf) {
@@ -118,64 +149,94 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         for (int i = 0; i < LD_ITERS; ++i) {
             const int idx = tid + i * GM_THREADS;
             const int row = idx >> 3, ch = idx & 7;
-            *reinterpret_cast<v4i *>(&lds[buf][row * TILE_K + ((ch ^ (row & 7)) << 4)]) = areg[i];
+            *reinterpret_cast<v4u *>(&lds[buf][row * TILE_K + ((ch ^ (row & 7)) << 4)]) = areg[i];
         }
     };
 
-    v4u p[GM_NS], pn[GM_NS];
-    auto load_b = [&](int kt, v4u(&dst)[GM_NS]) {
+    v4u p[GM_NS][2], pn[GM_NS][2];
+    auto load_b = [&](int kt, v4u(&dst)[GM_NS][2]) {
 #pragma unroll
-        for (int ns = 0; ns < GM_NS; ++ns) dst[ns] = wp[ns][(int64_t)kt * WAVE];
+        for (int ns = 0; ns < GM_NS; ++ns)
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp)
+                dst[ns][sp] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rw, wvoff[ns] + sp * 512, wsoff[ns] + kt * TILE_BYTES, 0);
     };
 
+    // per-lane decode tables of its two output channels
     DecodeLut lut[GM_NS];
+    SignedLut slut[GM_NS];
     auto load_luts = [&](int g) {
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
-            const int nn = ns_valid[ns] ? n0 + ns * TILE_N + ln : 0;
-            lut[ns] = make_decode_lut(zero[(int64_t)nn * ng + g]);
+            const int nn = (n0 + ns * 32 + r32 < N) ? n0 + ns * 32 + r32 : 0;
+            const int z = zero[(int64_t)nn * ng + g];
+            if (GROUPED) slut[ns] = make_signed_lut(z);
+            else lut[ns] = make_decode_lut(z);
         }
     };
 
-    // Lane owns, per (ms, ns): token m = m0 + 16 ms + ln, channels n = n0 + 16 ns + 4 kb + r.
-    auto flush_group = [&](int g) {
-        int rsv[MS];
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
-            const int m = m0 + ms * 16 + ln;
-            rsv[ms] = (m < M) ? rs[(int64_t)m * ng + g] : 0;
-        }
+    // Accumulator layout (32x32): lane holds token m = 32 ms + r32 and the 16 output channels
+    // n = n0 + 32 ns + 8 (r / 4) + 4 kh + (r % 4), r = 0..15.
+    auto flush_group = [&](int g) {   // GROUPED only: y += (step / 8) * acc, acc = 0
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
-            float es[4];
-            int bq[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int nn = ns_valid[ns] ? n0 + ns * TILE_N + 4 * kb + r : 0;
-                const int z = zero[(int64_t)nn * ng + g];
-                es[r] = step[(int64_t)nn * ng + g] * 0.125f;
-                bq[r] = 8 * z + ((~z & 1) << 2);
-            }
-#pragma unroll
-            for (int ms = 0; ms < MS; ++ms) {
-                const int m = m0 + ms * 16 + ln;
+            for (int b = 0; b < 4; ++b) {
+                float es[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int v = acc[ms][ns][r] - bq[r] * rsv[ms];
-                    if (GROUPED) y[ms][ns][r] += es[r] * (float)v;
-                    else acc[ms][ns][r] = v;  // kept for the epilogue
-                    if (acc_out != nullptr && m < M && ns_valid[ns]) {
-                        const int nn = n0 + ns * TILE_N + 4 * kb + r;
-                        acc_out[((int64_t)m * N + nn) * ng + g] = v >> 2;
+                    const int nn = n0 + ns * 32 + 8 * b + 4 * kh + r;
+                    es[r] = step[(int64_t)(nn < N ? nn : 0) * ng + g] * 0.125f;
+                }
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms) {
+                    const int m = m0 + wr0 + ms * 32 + r32;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int v = acc[ms][ns][4 * b + r];
+                        y[GROUPED ? ms : 0][ns][4 * b + r] += es[r] * (float)v;
+                        if (acc_out != nullptr && m < M) {
+                            const int nn = n0 + ns * 32 + 8 * b + 4 * kh + r;
+                            if (nn < N) acc_out[((int64_t)m * N + nn) * ng + g] = v >> 2;
+                        }
+                        acc[ms][ns][4 * b + r] = 0;
                     }
-                    if (GROUPED) acc[ms][ns][r] = 0;
                 }
             }
         }
     };
 
+    // activation fragments of k-step s = 2 sp + h: 16-byte chunk 2 (2 sp + kh) + h of the token's row
+    auto read_a = [&](int buf, int s, v4i(&dst)[MS]) {
+        const int chunk = 2 * (2 * (s >> 1) + kh) + (s & 1);
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) {
+            const int row = wr0 + ms * 32 + r32;
+            dst[ms] = *reinterpret_cast<const v4i *>(&lds[buf][row * TILE_K + ((chunk ^ (row & 7)) << 4)]);
+        }
+    };
+    auto decode_step = [&](const v4u(&pk)[GM_NS][2], int s, v4i(&dst)[GM_NS]) {
+        const int sp = s >> 1, h = s & 1;
+#pragma unroll
+        for (int ns = 0; ns < GM_NS; ++ns) {
+            const uint32_t q0 = h ? pk[ns][sp].z : pk[ns][sp].x;
+            const uint32_t q1 = h ? pk[ns][sp].w : pk[ns][sp].y;
+            int a, b, c, d;
+            if (GROUPED) {
+                decode_word_signed(q0, slut[ns], a, b);
+                decode_word_signed(q1, slut[ns], c, d);
+            } else {
+                decode_word(q0, lut[ns], a, b);
+                decode_word(q1, lut[ns], c, d);
+            }
+            dst[ns] = v4i{a, b, c, d};
+        }
+    };
+
     load_a(0);
     load_b(0, p);
+    if (!GROUPED) load_luts(0);
     store_a(0);
     __syncthreads();
 
@@ -186,75 +247,96 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
             load_a(kt + 1);
             load_b(kt + 1, pn);
         }
-        if (kt % tiles_per_group == 0) load_luts(kt / tiles_per_group);
+        if (GROUPED && kt % tiles_per_group == 0) load_luts(kt / tiles_per_group);
 
-        v4i w0[GM_NS], w1[GM_NS];
+        // Software pipeline over the four 32-column k-steps of the tile: the activation fragments
+        // and the decoded weights of step s + 1 are produced while the MFMAs of step s run.
+        v4i af[2][MS], w[2][GM_NS];
+        read_a(cur, 0, af[0]);
+        decode_step(p, 0, w[0]);
 #pragma unroll
-        for (int ns = 0; ns < GM_NS; ++ns) decode_lane(p[ns], lut[ns], w0[ns], w1[ns]);
-
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
-            const int row = ms * 16 + ln;
-            const uint8_t *base = &lds[cur][row * TILE_K];
-            const v4i a0 = *reinterpret_cast<const v4i *>(base + (((2 * kb) ^ (row & 7)) << 4));
-            const v4i a1 = *reinterpret_cast<const v4i *>(base + (((2 * kb + 1) ^ (row & 7)) << 4));
-#pragma unroll
-            for (int ns = 0; ns < GM_NS; ++ns) {
-                // D[i][j]: rows i = output channels (weights operand), columns j = tokens
-                acc[ms][ns] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0[ns], a0, acc[ms][ns], 0, 0, 0);
-                acc[ms][ns] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1[ns], a1, acc[ms][ns], 0, 0, 0);
+        for (int s = 0; s < 4; ++s) {
+            if (s < 3) {
+                read_a(cur, s + 1, af[(s + 1) & 1]);
+                decode_step(p, s + 1, w[(s + 1) & 1]);
             }
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int ns = 0; ns < GM_NS; ++ns)
+                    // D[i][j]: rows i = output channels (weights operand), columns j = tokens
+                    acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                        acc[ms][ns], 0, 0, 0);
         }
         if (GROUPED && (kt + 1) % tiles_per_group == 0) flush_group(kt / tiles_per_group);
 
         if (more) {
             store_a(cur ^ 1);
 #pragma unroll
-            for (int ns = 0; ns < GM_NS; ++ns) p[ns] = pn[ns];
+            for (int ns = 0; ns < GM_NS; ++ns)
+#pragma unroll
+                for (int sp = 0; sp < 2; ++sp) p[ns][sp] = pn[ns][sp];
         }
         __syncthreads();
     }
-    if (!GROUPED) flush_group(0);
+
+    // epilogue parameters of the workgroup's 256 channels, in the (now free) staging buffer
+    float *s_es = reinterpret_cast<float *>(&lds[0][0]);          // step / 8
+    int *s_bq = reinterpret_cast<int *>(&lds[0][GM_BN * 4]);      // 4 beta
+    if (!GROUPED) {
+        if (tid < GM_BN) {
+            const int nn = nb0 + tid < N ? nb0 + tid : 0;
+            const int z = zero[(int64_t)nn * ng];
+            s_es[tid] = step[(int64_t)nn * ng] * 0.125f;
+            s_bq[tid] = 8 * z + ((~z & 1) << 2);
+        }
+        __syncthreads();
+    }
 
     // epilogue: Y[m, n..n+3] = cast(sx[m] * y)
-    float es[GM_NS][4];
-    if (!GROUPED) {
-#pragma unroll
-        for (int ns = 0; ns < GM_NS; ++ns)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int nn = ns_valid[ns] ? n0 + ns * TILE_N + 4 * kb + r : 0;
-                es[ns][r] = step[(int64_t)nn * ng] * 0.125f;
-            }
-    }
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms) {
-        const int m = m0 + ms * 16 + ln;
+        const int m = m0 + wr0 + ms * 32 + r32;
         if (m >= M) continue;
         const float sxm = sx[m];
+        const int rsm = GROUPED ? 0 : rs[m];
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
             if (!ns_valid[ns]) continue;
-            uint16_t h[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float yv = GROUPED ? y[GROUPED ? ms : 0][ns][r] : es[ns][r] * (float)acc[ms][ns][r];
-                const float out = sxm * yv;
-                h[r] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
-            }
-            uint16_t *yp = Y + (int64_t)m * ldy + n0 + ns * TILE_N + 4 * kb;
-            if (vec_store) {
-                *reinterpret_cast<uint2 *>(yp) =
-                    make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
-            } else {
+            for (int b = 0; b < 4; ++b) {
+                const int nl = wn * (GM_NS * 32) + ns * 32 + 8 * b + 4 * kh;   // channel within the workgroup
+                const int nn = nb0 + nl;
+                if (nn >= N) continue;   // N % 16 == 0 and nl % 4 == 0: the 4 channels are valid together
+                uint16_t hh[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) yp[r] = h[r];
+                for (int r = 0; r < 4; ++r) {
+                    float yv;
+                    if (GROUPED) {
+                        yv = y[GROUPED ? ms : 0][ns][4 * b + r];
+                    } else {
+                        // remove the decode bias: 4 sum Xq d = acc - 4 beta * rowsum (exact)
+                        const int v = acc[ms][ns][4 * b + r] - s_bq[nl + r] * rsm;
+                        if (acc_out != nullptr) acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                        yv = s_es[nl + r] * (float)v;
+                    }
+                    const float out = sxm * yv;
+                    hh[r] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+                }
+                uint16_t *yp = Y + (int64_t)m * ldy + nn;
+                if (vec_store) {
+                    *reinterpret_cast<uint2 *>(yp) = make_uint2(
+                        (uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16));
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) yp[r] = hh[r];
+                }
             }
         }
     }
 }
 
-template <int BM, bool GROUPED>
+template <int BM, int WM, bool GROUPED>
 static int launch_gemm_t(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M,
                          const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N,
                          int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out,
@@ -263,10 +345,10 @@ static int launch_gemm_t(const int8_t *Xq, const float *sx, const int32_t *rs, i
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
     const int vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
-    hipLaunchKernelGGL((gemm_kernel<BM, GROUPED>), dim3((unsigned)(grid_m * grid_n)),
-                       dim3(GM_THREADS), 0, st, Xq, sx, rs, (int)M, (const v4u *)Wt, step, zero,
-                       (int)N, (int)K, (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy,
-                       vec_store, acc_out, grid_m, grid_n);
+    hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED>), dim3((unsigned)(grid_m * grid_n)),
+                       dim3(WM * 256), 0, st, Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K,
+                       (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
+                       acc_out, grid_m, grid_n);
     return hip_status(hipGetLastError());
 }
 
@@ -275,18 +357,23 @@ int launch_gemm(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M,
                 int y_dtype, int64_t ldy, int32_t *acc_out, hipStream_t st)
 {
     const bool grouped = G != K;
-    if ((M + 255) / 256 * ((N + 255) / 256) > 0x7fffffLL) return W4A8_ERR_SHAPE;
-    if (grouped)  // int32 group accumulators plus fp32 running sums: 64 token rows fill the registers
-        return launch_gemm_t<64, true>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
-                                       acc_out, st);
-    if (M <= 64)
-        return launch_gemm_t<64, false>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
-                                        acc_out, st);
-    if (M <= 128)
-        return launch_gemm_t<128, false>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
-                                         acc_out, st);
-    return launch_gemm_t<256, false>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
-                                     acc_out, st);
+    if ((M + 63) / 64 * ((N + 255) / 256) > 0x7fffffLL || M * K > 0x7fffffffLL) return W4A8_ERR_SHAPE;
+#define W4A8_GM(BM_, WM_, GR_)                                                                     \
+    return launch_gemm_t<BM_, WM_, GR_>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
+                                        acc_out, st)
+    if (grouped) {  // int32 group accumulators plus fp32 running sums: at most 128 token rows
+        W4A8_GM(64, 1, true);
+    }
+    if (M <= 64) W4A8_GM(64, 1, false);
+    if (M <= 128) W4A8_GM(128, 2, false);
+    // 256-row tiles reuse each decoded weight twice as often, but whole rounds of 256 CUs are what
+    // count: take the 128-row tile when it needs clearly less machine time (measured cost ~0.6)
+    const int64_t gn = (N + GM_BN - 1) / GM_BN;
+    const double rounds256 = (double)(((M + 255) / 256 * gn + 255) / 256);
+    const double rounds128 = (double)(((M + 127) / 128 * gn + 255) / 256) * 0.6;
+    if (rounds128 < rounds256) W4A8_GM(128, 2, false);
+    W4A8_GM(256, 2, false);
+#undef W4A8_GM
 }
 
 }  // namespace w4a8

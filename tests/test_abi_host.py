@@ -42,9 +42,9 @@ def test_status_strings(lib):
 
 
 def test_workspace_sizes(lib):
-    # decode needs none with the tiled layout; prefill needs the per-token group row-sums
+    # decode needs none with the tiled layout; per-channel prefill needs one row-sum per token
     assert lib.gemm_workspace_bytes(16, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
-    assert lib.gemm_workspace_bytes(2048, 4096, 4096, 128, lib.LAYOUT_TILED) == 2048 * 32 * 4
+    assert lib.gemm_workspace_bytes(2048, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
     assert lib.gemm_workspace_bytes(2048, 4096, 4096, 0, lib.LAYOUT_TILED) == 2048 * 4
     need = lib.gemm_workspace_bytes(16, 4096, 4096, 128, lib.LAYOUT_CANONICAL)
     assert need == 4096 * 4096 // 2
