@@ -244,3 +244,67 @@ def test_aqas_power_of_two_invariance_on_gpu(lib, oracle):
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[2], b[2])
     assert np.array_equal(a[1], b[1] * 4) and np.array_equal(a[3] * 4, b[3])
     assert np.array_equal(a[4], b[4])
+
+
+# --------------------------------------------------------------------------- full-size configurations
+def _full_size_case(lib, oracle, name, M=None, n_samples=96, seed=0):
+    """A BASELINE configuration at its real size, in the launch configuration bench.py times:
+    quantizers compared in full (bit-exact), accumulators and Y on sampled outputs that the plain
+    oracle computes one by one (whole rows and columns would take the triple loop hours)."""
+    X, W, s, G = syn.make_layer(name, M=M)
+    Mq, K = X.shape
+    N = W.shape[0]
+    Xd, Wd, sd = dev(X), dev(W), dev(s)
+    Xq, sx = lib.quantize_act_int8(Xd, sd)
+    codes, step, zero = lib.quantize_weight_dint4(Wd, sd, G)
+    del Wd
+    ref_q, ref_sx = oracle.quantize_act_int8(X, s)
+    assert np.array_equal(host(Xq), ref_q) and np.array_equal(host(sx), ref_sx)
+    ref_codes, ref_step, ref_zero = oracle.quantize_weight_dint4(W, s, G)
+    assert np.array_equal(host(step), ref_step) and np.array_equal(host(zero), ref_zero)
+    assert np.array_equal(host(codes), ref_codes)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    del codes
+    ws = torch.empty((max(1, lib.gemm_workspace_bytes(Mq, N, K, G)),), dtype=torch.uint8, device="cuda")
+    Y = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, workspace=ws)     # the timed configuration
+    Y2, acc = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, workspace=ws, want_acc=True)
+    assert torch.equal(Y, Y2)
+    rng = np.random.default_rng(seed)
+    mi = rng.integers(0, Mq, size=n_samples)
+    ni = rng.integers(0, N, size=n_samples)
+    mi[:4] = [0, Mq - 1, 0, Mq - 1]                 # the corners of the output
+    ni[:4] = [0, 0, N - 1, N - 1]
+    acc_ref = oracle.int_gemm_sampled(ref_q, oracle.pack_dint4(ref_codes), ref_zero, G, mi, ni)
+    acc_gpu = acc[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()]
+    assert np.array_equal(host(acc_gpu), acc_ref), "sampled int32 accumulators differ"
+    ng = ref_step.shape[1]
+    y64 = ref_sx[mi].astype(np.float64) * np.sum(
+        0.5 * ref_step[ni].astype(np.float64) * acc_ref.astype(np.float64), axis=1)
+    y_gpu = host(Y[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()]).astype(np.float64)
+    rms = np.sqrt(np.mean(host(Y[mi[0]]).astype(np.float64) ** 2))
+    assert np.all(np.abs(y_gpu - y64) <= 1e-3 * np.maximum(np.abs(y64), 1e-3 * rms))
+    # properties that hold at any size: |acc| <= 127 * 26 * G, and Y reproduces from the returned
+    # accumulators as sx * sum_g (step / 2) acc
+    assert int(acc.abs().max()) <= 127 * 26 * (G if G else K)
+    rows = torch.from_numpy(np.unique(mi[:8])).cuda()
+    y_from_acc = (acc[rows].double() * (0.5 * step.double())[None]).sum(-1) * sx[rows].double()[:, None]
+    err = (Y[rows].double() - y_from_acc).abs()
+    bound = 1e-3 * torch.maximum(y_from_acc.abs(), torch.full_like(y_from_acc, 1e-3 * rms))
+    assert bool((err <= bound).all())
+
+
+def test_full_size_c2_decode_all_m(lib, oracle):
+    for M in (1, 2, 4, 8, 16):
+        _full_size_case(lib, oracle, "C2", M=M, seed=M)
+
+
+@pytest.mark.parametrize("name,M", [("C3_up", 2048), ("C3_down", 2048), ("C4_5120x13824", 2048),
+                                    ("C4_13824x5120", 16), ("C4_5120x5120", 512),
+                                    ("C4_5120x5120", 128), ("C4_5120x13824", 1)])
+def test_full_size_llama_shapes(lib, oracle, name, M):
+    _full_size_case(lib, oracle, name, M=M, seed=M)
+
+
+def test_full_size_c5_opt66b_end_to_end(lib, oracle):
+    """OPT-66B-shaped layer: activation quantization and GEMM back to back on one stream."""
+    _full_size_case(lib, oracle, "C5", n_samples=64, seed=5)
