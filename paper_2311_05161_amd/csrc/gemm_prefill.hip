@@ -71,10 +71,11 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     constexpr int WROWS = BM / WM;                 // token rows per wave
     constexpr int MS = WROWS / 32;                 // 32-token sub-tiles per wave
     constexpr int LD_ITERS = BM * 8 / GM_THREADS;  // 16-byte chunks of the A tile per thread
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2][BM * TILE_K];
-    // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, current + next group
-    __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 2 : 1][GROUPED ? GM_BN : 4];
-    __shared__ int s_gz[GROUPED ? 2 : 1][GROUPED ? GM_BN : 4];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    uint8_t(*lds)[BM * TILE_K] = reinterpret_cast<uint8_t(*)[BM * TILE_K]>(lds_raw);   // [3][BM * 128]
+    // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, three groups deep
+    __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 3 : 1][GROUPED ? GM_BN : 4];
+    __shared__ int s_gz[GROUPED ? 3 : 1][GROUPED ? GM_BN : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -136,7 +137,8 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) y[ms][ns][r] = 0.f;
 
-    // A-tile staging: chunk c (16 bytes) of row r lives at r*128 + ((c ^ (r & 7)) * 16)
+    // A-tile staging: chunk c (16 bytes) of row r lives at r*128 + ((c ^ ((r >> 1) & 7)) * 16): with 64
+    // LDS banks (256 B per clock) 16 consecutive rows x one chunk index cover all banks exactly once
     v4u areg[LD_ITERS];
     auto load_a = [&](int kt) {
 #pragma unroll
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
         for (int i = 0; i < LD_ITERS; ++i) {
             const int idx = tid + i * GM_THREADS;
             const int row = idx >> 3, ch = idx & 7;
-            *reinterpret_cast<v4u *>(&lds[buf][row * TILE_K + ((ch ^ (row & 7)) << 4)]) = areg[i];
+            *reinterpret_cast<v4u *>(&lds[buf][row * TILE_K + ((ch ^ ((row >> 1) & 7)) << 4)]) = areg[i];
         }
     };
 
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
             if (GROUPED) {
-                slut[ns] = make_signed_lut(s_gz[g & 1][wn * (GM_NS * 32) + ns * 32 + r32]);
+                slut[ns] = make_signed_lut(s_gz[g % 3][wn * (GM_NS * 32) + ns * 32 + r32]);
             } else {
                 const int nn = (n0 + ns * 32 + r32 < N) ? n0 + ns * 32 + r32 : 0;
                 lut[ns] = make_decode_lut(zero[(int64_t)nn * ng]);
@@ -192,8 +194,8 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     };
     auto publish_group = [&](int g) {
         if (tid < GM_BN) {
-            s_ges[g & 1][tid] = gp_es;
-            s_gz[g & 1][tid] = gp_z;
+            s_ges[g % 3][tid] = gp_es;
+            s_gz[g % 3][tid] = gp_z;
         }
     };
 
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int nl = wn * (GM_NS * 32) + ns * 32 + 8 * b + 4 * kh;
-                const v4f es = *reinterpret_cast<const v4f *>(&s_ges[g & 1][nl]);
+                const v4f es = *reinterpret_cast<const v4f *>(&s_ges[g % 3][nl]);
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
                     const int m = m0 + wr0 + ms * 32 + r32;
@@ -230,7 +232,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms) {
             const int row = wr0 + ms * 32 + r32;
-            dst[ms] = *reinterpret_cast<const v4i *>(&lds[buf][row * TILE_K + ((chunk ^ (row & 7)) << 4)]);
+            dst[ms] = *reinterpret_cast<const v4i *>(&lds[buf][row * TILE_K + ((chunk ^ ((row >> 1) & 7)) << 4)]);
         }
     };
     auto decode_step = [&](const v4u(&pk)[GM_NS][2], int s, v4i(&dst)[GM_NS]) {
@@ -251,41 +253,63 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
         }
     };
 
+    // ---- pipeline ------------------------------------------------------------------------------
+    // LDS holds three activation tiles: kt (being consumed), kt + 1 (published by the previous
+    // barrier, so its first fragments can be fetched before this iteration's barrier) and kt + 2
+    // (being written).  Global loads run three tiles ahead of the MFMAs; tile indices past the end
+    // are clamped to the last tile (a redundant but in-bounds reload).
+    const int ktl = KT - 1;
     load_a(0);
     load_b(0, p);
+    load_b(min(1, ktl), pn);
     if (GROUPED) {
         fetch_group(0);
         publish_group(0);
+        if (ng > 1) {
+            fetch_group(1);
+            publish_group(1);
+        }
+        if (ng > 2) fetch_group(2);
     } else {
         load_luts(0);
     }
     store_a(0);
+    load_a(min(1, ktl));
+    store_a(1);
+    load_a(min(2, ktl));
     __syncthreads();
+    if (GROUPED) load_luts(0);
 
+    v4i af[2][MS], w[2][GM_NS];
+    read_a(0, 0, af[0]);
+    decode_step(p, 0, w[0]);
+
+    int cur = 0;   // kt % 3
     for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            load_a(kt + 1);
-            load_b(kt + 1, pn);
-        }
+        const int nxt = cur == 2 ? 0 : cur + 1;
+        const int nx2 = nxt == 2 ? 0 : nxt + 1;
+        store_a(nx2);                     // tile kt + 2 (loaded one iteration ago)
+        load_a(min(kt + 3, ktl));
         const bool group_start = GROUPED && kt % tiles_per_group == 0;
+        const bool group_end = GROUPED && (kt + 1) % tiles_per_group == 0;
         const int g_cur = GROUPED ? kt / tiles_per_group : 0;
         if (group_start) {
-            load_luts(g_cur);
-            if (g_cur + 1 < ng) fetch_group(g_cur + 1);
+            if (g_cur + 2 < ng) publish_group(g_cur + 2);
+            if (g_cur + 3 < ng) fetch_group(g_cur + 3);
         }
 
-        // Software pipeline over the four 32-column k-steps of the tile: the activation fragments
-        // and the decoded weights of step s + 1 are produced while the MFMAs of step s run.
-        v4i af[2][MS], w[2][GM_NS];
-        read_a(cur, 0, af[0]);
-        decode_step(p, 0, w[0]);
+        // Software pipeline over the four 32-column k-steps: fragments and decoded weights of the
+        // next step (for the last step: of the next tile's first step) are produced while the
+        // MFMAs of the current step run.
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             if (s < 3) {
                 read_a(cur, s + 1, af[(s + 1) & 1]);
                 decode_step(p, s + 1, w[(s + 1) & 1]);
+            } else {
+                if (group_end && g_cur + 1 < ng) load_luts(g_cur + 1);
+                read_a(nxt, 0, af[0]);
+                decode_step(pn, 0, w[0]);
             }
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
@@ -294,17 +318,22 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                     // D[i][j]: rows i = output channels (weights operand), columns j = tokens
                     acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
                                                                         acc[ms][ns], 0, 0, 0);
-        }
-        if (GROUPED && (kt + 1) % tiles_per_group == 0) flush_group(g_cur);
-        if (group_start && g_cur + 1 < ng) publish_group(g_cur + 1);
-
-        if (more) {
-            store_a(cur ^ 1);
+            // issue order for this step: the LDS reads of the next step first, then the decode
+            // arithmetic spread evenly between the MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, MS, 0);
 #pragma unroll
-            for (int ns = 0; ns < GM_NS; ++ns)
-#pragma unroll
-                for (int sp = 0; sp < 2; ++sp) p[ns][sp] = pn[ns][sp];
+            for (int i = 0; i < MS * GM_NS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, GROUPED ? 6 : 4, 0);
+            }
         }
+        if (group_end) flush_group(g_cur);
+#pragma unroll
+        for (int ns = 0; ns < GM_NS; ++ns)
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) p[ns][sp] = pn[ns][sp];
+        load_b(min(kt + 2, ktl), pn);
+        cur = nxt;
         __syncthreads();
     }
 
@@ -373,8 +402,17 @@ static int launch_gemm_t2(const int8_t *Xq, const float *sx, const int32_t *rs, 
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
     const int vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
+    constexpr int lds_bytes = 3 * BM * TILE_K;
+    static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
+    if (!attr_set) {
+        if (lds_bytes > 48 * 1024 &&
+            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, GROUPED, ACC_OUT>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+            return W4A8_ERR_HIP;
+        attr_set = true;
+    }
     hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED, ACC_OUT>), dim3((unsigned)(grid_m * grid_n)),
-                       dim3(WM * 256), 0, st, Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K,
+                       dim3(WM * 256), lds_bytes, st, Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K,
                        (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
                        acc_out, grid_m, grid_n);
     return hip_status(hipGetLastError());
