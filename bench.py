@@ -27,6 +27,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+# HBM bytes per gemv_kernel launch on this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, scaled by a 256 MiB copy (profiles/gemv_kernel_C2_decode_hbm_traffic.md): 9,694,208 read + 131,072 written
+GEMV_C2_TRAFFIC_BYTES = 9825280
 METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
 
 
@@ -44,6 +47,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill (compute-bound) side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (known size) so that a rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE run of this command can be scaled to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
@@ -178,6 +184,14 @@ def main():
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
 
+    if args.pmc_calibration:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = elapsed / steps * 1e3
     weight_gbs = N * K / 2 / (elapsed / steps) / 1e9
 
@@ -202,7 +216,7 @@ def main():
     achieved = per_copy / (kern_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemv_kernel (w4a8_gemm, M<=16)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": GEMV_C2_TRAFFIC_BYTES,
                 "bytes_per_launch": per_copy, "avg_launch_us": round(kern_ms * 1e3, 3)}
 
     # ------------------------------------------------------------------ larger decode shapes (side figures)
