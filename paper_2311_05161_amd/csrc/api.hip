@@ -37,11 +37,13 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
         off = align_up(off + w.repack_bytes);
     }
     if (M > 16) {
-        if (G == K) {  // per-channel weights: bias removal needs one row-sum per token
-            w.rs_off = off;
-            w.rs_bytes = (size_t)M * sizeof(int32_t);
-            off = align_up(off + w.rs_bytes);
-        }
+        const GemmPlan gp = plan_gemm(M, N, K, G);
+        w.rs_off = off;            // per-channel weights: bias removal needs row-sums per token
+        w.rs_bytes = gp.rs_bytes;
+        off = align_up(off + w.rs_bytes);
+        w.part_off = off;          // few output tiles: K is split, fp32 partial sums
+        w.part_bytes = gp.partial_bytes;
+        off = align_up(off + w.part_bytes);
     } else if (M > 0 && N > 0) {
         w.part_off = off;
         w.part_bytes = plan_gemv(M, N, K, G).partial_bytes;
@@ -173,13 +175,12 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
         return launch_gemv(Xq, sx, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out,
                            (float *)(wsb + ws.part_off), st);
     }
-    int32_t *rs = nullptr;
-    if (G == K) {
-        rs = (int32_t *)(wsb + ws.rs_off);
-        const int rc = launch_group_rowsum(Xq, M, K, G, rs, st);
+    if (acc_out && ws.part_bytes > 0 && G == K) {  // K-split workgroups add exact partial sums
+        const int rc = launch_fill_i32(acc_out, M * N, 0, st);
         if (rc != W4A8_OK) return rc;
     }
-    return launch_gemm(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out, st);
+    return launch_gemm(Xq, sx, (int32_t *)(wsb + ws.rs_off), M, Wt, step, zero, N, K, G, Y, y_dtype,
+                       ldy, acc_out, (float *)(wsb + ws.part_off), st);
 }
 
 }  // extern "C"

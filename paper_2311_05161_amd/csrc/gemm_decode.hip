@@ -310,9 +310,15 @@ int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt,
     }
     int rc = hip_status(hipGetLastError());
     if (rc != W4A8_OK || pl.splits == 1) return rc;
+    return launch_gemv_combine(part, sx, M, N, pl.splits, Y, y_dtype, ldy, st);
+}
+
+int launch_gemv_combine(const float *partial, const float *sx, int64_t M, int64_t N, int splits, void *Y,
+                        int y_dtype, int64_t ldy, hipStream_t st)
+{
     const int64_t outs = M * N;
     hipLaunchKernelGGL(gemv_combine_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st,
-                       part, sx, (int)M, (int)N, pl.splits, y16, y_dtype, ldy);
+                       partial, sx, (int)M, (int)N, splits, (uint16_t *)Y, y_dtype, ldy);
     return hip_status(hipGetLastError());
 }
 

@@ -26,16 +26,21 @@ constexpr int GM_BN = 256;  // output channels per workgroup
 constexpr int GM_NS = 2;    // 32-channel sub-tiles per wave
 constexpr int GM_OOB = 0x7fff0000;
 
-// ---- per-token row-sums of Xq over all of K (bias removal of the per-channel path) ------------
+// ---- per-token row-sums of Xq over each K-range (bias removal of the per-channel path) ----------
 __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ Xq, int64_t M, int K,
+                                                     int splits, int k_per_split,
                                                      int32_t *__restrict__ rs)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t m = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (m >= M) return;
-    const v4i *x = reinterpret_cast<const v4i *>(Xq + m * K);
+    const int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // (split, token)
+    if (seg >= M * splits) return;
+    const int sp = (int)(seg / M);
+    const int64_t m = seg - (int64_t)sp * M;
+    const int k0 = sp * k_per_split;
+    const int kn = min(k_per_split, K - k0);
+    const v4i *x = reinterpret_cast<const v4i *>(Xq + m * K + k0);
     int sum = 0;
-    for (int i = lane; i < K / 16; i += WAVE) {
+    for (int i = lane; i < kn / 16; i += WAVE) {
         const v4i v = x[i];
         sum = __builtin_amdgcn_sdot4(v.x, 0x01010101, sum, false);
         sum = __builtin_amdgcn_sdot4(v.y, 0x01010101, sum, false);
@@ -43,17 +48,7 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ 
         sum = __builtin_amdgcn_sdot4(v.w, 0x01010101, sum, false);
     }
     sum = wave_sum_i32(sum);
-    if (lane == 0) rs[m] = sum;
-}
-
-int launch_group_rowsum(const int8_t *Xq, int64_t M, int64_t K, int64_t G, int32_t *rs,
-                        hipStream_t st)
-{
-    (void)G;
-    if (M == 0) return W4A8_OK;
-    hipLaunchKernelGGL(rowsum_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, Xq, M, (int)K,
-                       rs);
-    return hip_status(hipGetLastError());
+    if (lane == 0) rs[seg] = sum;
 }
 
 // ---- the tile kernel ------------------------------------------------------------------------
@@ -65,7 +60,8 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     int M, const uint8_t *__restrict__ Wt, const float *__restrict__ step,
     const uint8_t *__restrict__ zero, int N, int K, int tiles_per_group, int ng,
     uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store,
-    int32_t *__restrict__ acc_out, int grid_m, int grid_n)
+    int32_t *__restrict__ acc_out, int grid_m, int grid_n, int kt_per_split,
+    float *__restrict__ partial)
 {
     constexpr int GM_THREADS = WM * 256;
     constexpr int WROWS = BM / WM;                 // token rows per wave
@@ -86,10 +82,14 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 
     // Workgroups are handed to the 8 XCDs round-robin; renumber so that each XCD works on a
     // contiguous range of tiles (token tiles fastest) and its private L2 sees the reuse.
-    int bid = blockIdx.x;
+    // With few output tiles K is also split over workgroups (each writes an fp32 partial).
+    const int tiles = grid_m * grid_n;
+    const int split = blockIdx.x / tiles;
+    const int kt0 = split * kt_per_split;              // first k-tile of this workgroup
+    const int KTl = min(kt_per_split, KT - kt0);       // its number of k-tiles
+    int bid = blockIdx.x - split * tiles;
     {
-        const int total = grid_m * grid_n;
-        const int per = total / 8;
+        const int per = tiles / 8;
         if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
     }
     const int bm = bid % grid_m;
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
             const int idx = tid + i * GM_THREADS;
             const int row = idx >> 3, ch = idx & 7;
             // rows >= M lie beyond the buffer and read as zero
-            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (m0 + row) * K + ch * 16, kt * TILE_K, 0);
+            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (m0 + row) * K + ch * 16, (kt0 + kt) * TILE_K, 0);
         }
     };
     auto store_a = [&](int buf) {
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
             for (int sp = 0; sp < 2; ++sp)
                 dst[ns][sp] = __builtin_amdgcn_raw_buffer_load_b128(
-                    rw, wvoff[ns] + sp * 512, wsoff[ns] + kt * TILE_BYTES, 0);
+                    rw, wvoff[ns] + sp * 512, wsoff[ns] + (kt0 + kt) * TILE_BYTES, 0);
     };
 
     // per-lane decode tables of its two output channels
@@ -258,18 +258,20 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     // barrier, so its first fragments can be fetched before this iteration's barrier) and kt + 2
     // (being written).  Global loads run three tiles ahead of the MFMAs; tile indices past the end
     // are clamped to the last tile (a redundant but in-bounds reload).
-    const int ktl = KT - 1;
+    const int ktl = KTl - 1;
+    const int g0 = GROUPED ? kt0 / tiles_per_group : 0;            // groups [g0, g_end) of this split
+    const int g_end = GROUPED ? g0 + KTl / tiles_per_group : 1;
     load_a(0);
     load_b(0, p);
     load_b(min(1, ktl), pn);
     if (GROUPED) {
-        fetch_group(0);
-        publish_group(0);
-        if (ng > 1) {
-            fetch_group(1);
-            publish_group(1);
+        fetch_group(g0);
+        publish_group(g0);
+        if (g0 + 1 < g_end) {
+            fetch_group(g0 + 1);
+            publish_group(g0 + 1);
         }
-        if (ng > 2) fetch_group(2);
+        if (g0 + 2 < g_end) fetch_group(g0 + 2);
     } else {
         load_luts(0);
     }
@@ -278,24 +280,24 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     store_a(1);
     load_a(min(2, ktl));
     __syncthreads();
-    if (GROUPED) load_luts(0);
+    if (GROUPED) load_luts(g0);
 
     v4i af[2][MS], w[2][GM_NS];
     read_a(0, 0, af[0]);
     decode_step(p, 0, w[0]);
 
     int cur = 0;   // kt % 3
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = 0; kt < KTl; ++kt) {
         const int nxt = cur == 2 ? 0 : cur + 1;
         const int nx2 = nxt == 2 ? 0 : nxt + 1;
         store_a(nx2);                     // tile kt + 2 (loaded one iteration ago)
         load_a(min(kt + 3, ktl));
         const bool group_start = GROUPED && kt % tiles_per_group == 0;
         const bool group_end = GROUPED && (kt + 1) % tiles_per_group == 0;
-        const int g_cur = GROUPED ? kt / tiles_per_group : 0;
+        const int g_cur = GROUPED ? g0 + kt / tiles_per_group : 0;
         if (group_start) {
-            if (g_cur + 2 < ng) publish_group(g_cur + 2);
-            if (g_cur + 3 < ng) fetch_group(g_cur + 3);
+            if (g_cur + 2 < g_end) publish_group(g_cur + 2);
+            if (g_cur + 3 < g_end) fetch_group(g_cur + 3);
         }
 
         // Software pipeline over the four 32-column k-steps: fragments and decoded weights of the
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                 read_a(cur, s + 1, af[(s + 1) & 1]);
                 decode_step(p, s + 1, w[(s + 1) & 1]);
             } else {
-                if (group_end && g_cur + 1 < ng) load_luts(g_cur + 1);
+                if (group_end && g_cur + 1 < g_end) load_luts(g_cur + 1);
                 read_a(nxt, 0, af[0]);
                 decode_step(pn, 0, w[0]);
             }
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
         const int m = m0 + wr0 + ms * 32 + r32;
         if (m >= M) continue;
         const float sxm = sx[m];
-        const int rsm = GROUPED ? 0 : rs[m];
+        const int rsm = GROUPED ? 0 : rs[(int64_t)split * M + m];
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
             if (!ns_valid[ns]) continue;
@@ -366,6 +368,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                 const int nn = nb0 + nl;
                 if (nn >= N) continue;   // N % 16 == 0 and nl % 4 == 0: the 4 channels are valid together
                 uint16_t hh[4];
+                v4f part;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     float yv;
@@ -374,11 +377,19 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                     } else {
                         // remove the decode bias: 4 sum Xq d = acc - 4 beta * rowsum (exact)
                         const int v = acc[ms][ns][4 * b + r] - s_bq[nl + r] * rsm;
-                        if (ACC_OUT) acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                        if (ACC_OUT) {
+                            if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
+                            else acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                        }
                         yv = s_es[nl + r] * (float)v;
                     }
+                    part[r] = yv;
                     const float out = sxm * yv;
                     hh[r] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+                }
+                if (partial != nullptr) {   // K-split: the combine kernel applies sx and the cast
+                    *reinterpret_cast<v4f *>(&partial[((int64_t)split * M + m) * N + nn]) = part;
+                    continue;
                 }
                 uint16_t *yp = Y + (int64_t)m * ldy + nn;
                 if (vec_store) {
@@ -394,10 +405,10 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 }
 
 template <int BM, int WM, bool GROUPED, bool ACC_OUT>
-static int launch_gemm_t2(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M,
-                         const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N,
-                         int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out,
-                         hipStream_t st)
+static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, const int32_t *rs,
+                          int64_t M, const uint8_t *Wt, const float *step, const uint8_t *zero,
+                          int64_t N, int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy,
+                          int32_t *acc_out, float *partial, hipStream_t st)
 {
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
@@ -411,50 +422,94 @@ static int launch_gemm_t2(const int8_t *Xq, const float *sx, const int32_t *rs, 
             return W4A8_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED, ACC_OUT>), dim3((unsigned)(grid_m * grid_n)),
-                       dim3(WM * 256), lds_bytes, st, Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K,
-                       (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
-                       acc_out, grid_m, grid_n);
+    hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED, ACC_OUT>),
+                       dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * 256), lds_bytes, st,
+                       Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K, (int)(G / TILE_K),
+                       (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store, acc_out, grid_m, grid_n,
+                       pl.kt_per_split, pl.splits > 1 ? partial : nullptr);
     return hip_status(hipGetLastError());
 }
 
 template <int BM, int WM, bool GROUPED>
-static int launch_gemm_t(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M,
-                         const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N,
-                         int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out,
-                         hipStream_t st)
+static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, const int32_t *rs,
+                         int64_t M, const uint8_t *Wt, const float *step, const uint8_t *zero,
+                         int64_t N, int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy,
+                         int32_t *acc_out, float *partial, hipStream_t st)
 {
     // the accumulator test hook is a separate instance so that the fast path carries none of it
     if (acc_out)
-        return launch_gemm_t2<BM, WM, GROUPED, true>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype,
-                                                     ldy, acc_out, st);
-    return launch_gemm_t2<BM, WM, GROUPED, false>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype,
-                                                  ldy, acc_out, st);
+        return launch_gemm_t2<BM, WM, GROUPED, true>(pl, Xq, sx, rs, M, Wt, step, zero, N, K, G, Y,
+                                                     y_dtype, ldy, acc_out, partial, st);
+    return launch_gemm_t2<BM, WM, GROUPED, false>(pl, Xq, sx, rs, M, Wt, step, zero, N, K, G, Y,
+                                                  y_dtype, ldy, acc_out, partial, st);
 }
 
-int launch_gemm(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M, const uint8_t *Wt,
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
+{
+    GemmPlan pl;
+    const bool grouped = G != K;
+    const int64_t gn = (N + GM_BN - 1) / GM_BN;
+    if (M <= 64) {
+        pl.bm = 64;
+    } else if (grouped || M <= 128) {
+        pl.bm = 128;   // group-wise: int32 group accumulators plus fp32 running sums
+    } else {
+        // 256-row tiles reuse each decoded weight twice as often, but whole rounds of 256 CUs are
+        // what count: take the 128-row tile when it needs clearly less machine time (cost ~0.6)
+        const double rounds256 = (double)(((M + 255) / 256 * gn + 255) / 256);
+        const double rounds128 = (double)(((M + 127) / 128 * gn + 255) / 256) * 0.6;
+        pl.bm = rounds128 < rounds256 ? 128 : 256;
+    }
+    // too few output tiles for 256 CUs: split K as well (whole groups, at least 4 k-tiles each)
+    const int64_t tiles = (M + pl.bm - 1) / pl.bm * gn;
+    const int KT = (int)(K / TILE_K), tpg = (int)(G / TILE_K);
+    pl.splits = 1;
+    pl.kt_per_split = KT;
+    if (tiles < 128 && KT >= 8) {
+        const int want = (int)((256 + tiles - 1) / tiles);
+        int unit = grouped ? tpg : 1;           // k-tiles that must stay together
+        while (unit < 4) unit += grouped ? tpg : 1;
+        int kps = (KT + want - 1) / want;
+        kps = (kps + unit - 1) / unit * unit;
+        if (kps < KT) {
+            pl.kt_per_split = kps;
+            pl.splits = (KT + kps - 1) / kps;
+        }
+    }
+    pl.rs_bytes = grouped ? 0 : (size_t)pl.splits * M * sizeof(int32_t);
+    pl.partial_bytes = pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
+    return pl;
+}
+
+int launch_gemm(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
-                int y_dtype, int64_t ldy, int32_t *acc_out, hipStream_t st)
+                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
 {
     const bool grouped = G != K;
-    if ((M + 63) / 64 * ((N + 255) / 256) > 0x7fffffLL || M * K > 0x7fffffffLL) return W4A8_ERR_SHAPE;
-#define W4A8_GM(BM_, WM_, GR_)                                                                     \
-    return launch_gemm_t<BM_, WM_, GR_>(Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
-                                        acc_out, st)
-    if (grouped) {  // int32 group accumulators plus fp32 running sums: at most 128 token rows
-        if (M <= 64) W4A8_GM(64, 1, true);
-        W4A8_GM(128, 2, true);
+    if ((M + 63) / 64 * ((N + 255) / 256) * 64 > 0x7fffffLL || M * K > 0x7fffffffLL)
+        return W4A8_ERR_SHAPE;
+    const GemmPlan pl = plan_gemm(M, N, K, G);
+    if (!grouped) {
+        const int64_t segs = M * pl.splits;
+        hipLaunchKernelGGL(rowsum_kernel, dim3((unsigned)((segs + 3) / 4)), dim3(256), 0, st, Xq, M,
+                           (int)K, pl.splits, pl.kt_per_split * TILE_K, rs);
+        if (hipGetLastError() != hipSuccess) return W4A8_ERR_HIP;
     }
-    if (M <= 64) W4A8_GM(64, 1, false);
-    if (M <= 128) W4A8_GM(128, 2, false);
-    // 256-row tiles reuse each decoded weight twice as often, but whole rounds of 256 CUs are what
-    // count: take the 128-row tile when it needs clearly less machine time (measured cost ~0.6)
-    const int64_t gn = (N + GM_BN - 1) / GM_BN;
-    const double rounds256 = (double)(((M + 255) / 256 * gn + 255) / 256);
-    const double rounds128 = (double)(((M + 127) / 128 * gn + 255) / 256) * 0.6;
-    if (rounds128 < rounds256) W4A8_GM(128, 2, false);
-    W4A8_GM(256, 2, false);
+    int rc;
+#define W4A8_GM(BM_, WM_, GR_)                                                                     \
+    rc = launch_gemm_t<BM_, WM_, GR_>(pl, Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
+                                      acc_out, partial, st)
+    if (grouped) {
+        if (pl.bm == 64) W4A8_GM(64, 1, true);
+        else W4A8_GM(128, 2, true);
+    } else {
+        if (pl.bm == 64) W4A8_GM(64, 1, false);
+        else if (pl.bm == 128) W4A8_GM(128, 2, false);
+        else W4A8_GM(256, 2, false);
+    }
 #undef W4A8_GM
+    if (rc != W4A8_OK || pl.splits == 1) return rc;
+    return launch_gemv_combine(partial, sx, M, N, pl.splits, Y, y_dtype, ldy, st);
 }
 
 }  // namespace w4a8

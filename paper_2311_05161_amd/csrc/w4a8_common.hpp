@@ -164,11 +164,20 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G);
 int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt, const float *step,
                 const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
                 int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
-int launch_group_rowsum(const int8_t *Xq, int64_t M, int64_t K, int64_t G, int32_t *rs,
-                        hipStream_t st);
-int launch_gemm(const int8_t *Xq, const float *sx, const int32_t *rs, int64_t M, const uint8_t *Wt,
+int launch_gemv_combine(const float *partial, const float *sx, int64_t M, int64_t N, int splits, void *Y,
+                        int y_dtype, int64_t ldy, hipStream_t st);
+// Launch shape of the prefill GEMM (also sizes its workspace).
+struct GemmPlan {
+    int bm;                // token rows per workgroup tile
+    int splits;            // K ranges handled by separate workgroups (1 unless the output has few tiles)
+    int kt_per_split;
+    size_t rs_bytes;       // int32 row-sums [splits][M] (per-channel weights only)
+    size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1
+};
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G);
+int launch_gemm(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
-                int y_dtype, int64_t ldy, int32_t *acc_out, hipStream_t st);
+                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
 
