@@ -110,9 +110,14 @@ int unpack_dint4(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, in
  *   group_size: 0 or K = per output channel, else a multiple of 128 dividing K
  *   Y    out [M, ldy] elements of y_dtype (F16 or BF16), ldy >= N
  *   acc_out  NULL, or int32 [M, N, K/G] (g fastest) that receives the exact accumulators
- *   workspace / workspace_bytes: scratch of at least w4a8_gemm_workspace_bytes(...) bytes,
- *               256-byte aligned; may be NULL when that function returns 0
- * Requires N % 16 == 0, K % 128 == 0, K <= 131072.  M == 0 is a no-op.
+ *   workspace / workspace_bytes: device scratch of at least w4a8_gemm_workspace_bytes(...)
+ *               bytes, 256-byte aligned, owned by the caller and free for reuse once the call's
+ *               work on `stream` has finished; may be NULL when that function returns 0.  It
+ *               holds, as needed: the tiled copy of canonical weights (N*K/2 bytes), the int32
+ *               per-token row-sums of the per-channel prefill path, and the fp32 partial sums
+ *               [splits, M, N] of launches that cut K across workgroups.
+ * Requires N % 16 == 0, K % 128 == 0, K <= 65536, N*K/2 < 2^31 and, for M > 16, M*K < 2^31
+ * (W4A8_ERR_SHAPE otherwise).  M == 0 or N == 0 is a no-op.
  * The M <= 16 path streams the packed weights once (memory-bound "decode" GEMV); larger M
  * uses the MFMA tile kernel ("prefill").  Results are deterministic (fixed reduction order). */
 size_t w4a8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size,

@@ -23,7 +23,7 @@ inline bool resolve_group(int64_t K, int64_t &G)
 struct WsPlan {
     size_t repack_off, repack_bytes;  // canonical -> tiled copy of the weights
     size_t rs_off, rs_bytes;          // per-token row-sums (M > 16, per-channel weights only)
-    size_t part_off, part_bytes;      // fp32 partial sums of a K-split decode GEMV (M <= 16 only)
+    size_t part_off, part_bytes;      // fp32 partial sums [splits][M][N] of a launch that splits K
     size_t total;
 };
 
@@ -145,6 +145,9 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
     if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
     if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K || ldy < N ||
         M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL)  // 32-bit byte offsets into the weights
+        return W4A8_ERR_SHAPE;
+    // the tile kernel addresses Xq with 32-bit byte offsets and numbers its tiles in 32 bits
+    if (M > 16 && (M * K > 0x7fffffffLL || (M + 63) / 64 * ((N + 255) / 256) > 0x1ffffLL))
         return W4A8_ERR_SHAPE;
     if (M == 0 || N == 0) return W4A8_OK;
     if (!Xq || !sx || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;

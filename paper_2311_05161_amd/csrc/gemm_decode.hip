@@ -3,16 +3,18 @@
 // epilogue; the dINT4 x INT8 multiply-accumulate of Sec. 4.3 mapped onto the int8 matrix cores).
 //
 // Work decomposition.  The tiled weight layout cuts W into 1 KB tiles of 16 output channels x
-// 128 input channels.  A persistent workgroup owns q consecutive 16-channel "n-tiles" (all of K,
-// or one K-split of it) and runs 8 compute wavefronts plus 1 helper wavefront:
+// 128 input channels.  A persistent workgroup owns a run of consecutive 16-channel "n-tiles" (all
+// of K, or one K-split of it; runs differ by at most one tile) and has 8 compute wavefronts plus 1
+// helper wavefront:
 //   * compute wave w owns the k-tiles kt = w, w+8, ... (at most AT of them).  Its int8 activation
 //     fragments for those k-tiles are loaded once and stay in registers for the workgroup's
 //     lifetime, so in steady state the only memory instructions it issues are 16-byte-per-lane
 //     buffer loads of weight tiles (the wave reads one contiguous 1 KB tile per instruction).
-//     Weight slot u always holds k-tile u of the n-tile one ahead of the one being consumed; every
-//     load is issued unconditionally (tiles that do not exist are addressed out of range, which a
-//     buffer load answers with zeros and no traffic), so the s_waitcnt counts are static and a
-//     wave only ever waits for the one tile it is about to use.
+//     The weight registers form a ring D n-tiles deep: right after slot (j % D, u) has been
+//     consumed it is refilled with k-tile u of n-tile j + D, so D * AT KB per wave are in flight
+//     towards HBM at any time.  Every load is issued unconditionally (tiles that do not exist are
+//     addressed out of range, which a buffer load answers with zeros and no traffic), so the
+//     s_waitcnt counts are static and a wave only ever waits for the one tile it is about to use.
 //   * per tile: one ds_read_b128 fetches the precomputed decode record of (channel, k-tile), the
 //     nibbles become int8 through the register LUT (w4a8_common.hpp), two MFMAs
 //     (v_mfma_i32_16x16x64_i8, the <= 16 token rows are the other operand) accumulate the biased
@@ -29,7 +31,7 @@ namespace w4a8 {
 
 constexpr int GV_CW = 8;                          // compute waves per workgroup
 constexpr int GV_THREADS = (GV_CW + 1) * WAVE;    // + 1 helper wave
-constexpr int GV_MAX_AT = 8;                      // k-tiles per compute wave -> K per split <= 8192
+constexpr int GV_MAX_AT = 5;                      // k-tiles per compute wave -> K per split <= 5120
 constexpr int GV_STAGE = 6;                       // decode records staged per thread (grouped mode)
 constexpr int GV_LDS_BUDGET = 48 * 1024;          // bytes of decode records per workgroup
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
@@ -38,6 +40,14 @@ __device__ __forceinline__ void lds_barrier()
 {
     // LDS-only barrier: outstanding global loads (the prefetched weight ring) stay in flight
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Pins the program order of memory instructions and of everything scheduled around them, at
+// every level of the compiler (emits no instruction).
+__device__ __forceinline__ void order_fence()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 __device__ __forceinline__ v4u decode_record(int z, float st)
@@ -49,79 +59,111 @@ __device__ __forceinline__ v4u decode_record(int z, float st)
 
 __device__ __forceinline__ v4i as_v4i(const v4u &v) { return v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w}; }
 
+// Kernel arguments (one block, so the prologue issues few scalar loads).
+struct GemvArgs {
+    const int8_t *Xq;      // [M, K]
+    const float *sx;       // [M]
+    const uint8_t *Wt;     // tiled packed weights
+    const float *step;     // [N, ng]
+    const uint8_t *zero;   // [N, ng]
+    uint16_t *Y;           // [M, ldy]
+    float *partial;        // [splits, M, N] or null
+    int32_t *acc_out;      // test hook or null
+    int64_t ldy;
+    int M, N, K;
+    int tiles_per_group, ng, y_dtype;
+    int kt_per_split;      // k-tiles per K-split (blockIdx.y)
+    int nt_lo, nt_rem;     // workgroup b owns nt_lo (+1 if b < nt_rem) consecutive n-tiles
+};
+
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
-template <bool GROUPED, int AT, bool ACC_OUT>
-__global__ __launch_bounds__(GV_THREADS) void gemv_kernel(
-    const int8_t *__restrict__ Xq, const float *__restrict__ sx, int M,
-    const uint8_t *__restrict__ Wt, const float *__restrict__ step, const uint8_t *__restrict__ zero,
-    int N, int K, int tiles_per_group, int ng, uint16_t *__restrict__ Y, int y_dtype, int64_t ldy,
-    float *__restrict__ partial, int32_t *__restrict__ acc_out, int q, int blocks_per_split,
-    int kt_per_split)
+// AT k-tile slots per compute wave, weight ring D n-tiles deep.
+template <bool GROUPED, int AT, int D, bool ACC_OUT>
+__global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     float *red = reinterpret_cast<float *>(smem);                        // [2][GV_CW][256]
-    v4u *rec = reinterpret_cast<v4u *>(smem + 2 * GV_CW * 256 * 4);      // [q][KTs or 1][16]
+    v4u *rec = reinterpret_cast<v4u *>(smem + 2 * GV_CW * 256 * 4);      // [n-tile][channel][RS]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int M = a.M, N = a.N, K = a.K;
     const int KT = K >> 7;
-    const int NT = N >> 4;
-    const int split = blockIdx.x / blocks_per_split;
-    const int nt0 = (blockIdx.x - split * blocks_per_split) * q;
-    const int my_nt = min(q, NT - nt0);
-    const int kt_begin = split * kt_per_split;
-    const int KTs = min(kt_per_split, KT - kt_begin);     // k-tiles of this split
+    const int split = blockIdx.y;
+    const int blk = blockIdx.x;
+    // n-tiles are dealt out as evenly as possible, in consecutive runs
+    const int nt0 = blk * a.nt_lo + min(blk, a.nt_rem);
+    const int my_nt = a.nt_lo + (blk < a.nt_rem ? 1 : 0);
+    const int kt_begin = split * a.kt_per_split;
+    const int KTs = min(a.kt_per_split, KT - kt_begin);     // k-tiles of this split
     const int recs_per_nt = GROUPED ? KTs : 1;
+    // records of one channel are consecutive; an odd stride spreads the 16 channels that one
+    // ds_read_b128 touches over all LDS banks
+    const int RS = GROUPED ? (KTs | 1) : 1;
 
     // ---- quantization parameters of this workgroup -> decode records in LDS -------------------
-    // element e = ((j * recs_per_nt + ktl) * 16 + row); loads first, LUT arithmetic later
+    // element e = (n-tile j, channel row, k-tile ktl), ktl fastest: consecutive lanes read
+    // consecutive groups of one channel, i.e. consecutive addresses of step[] and zero[].
+    // Loads first, LUT arithmetic later.  Quotients by multiplication with an approximate
+    // reciprocal: exact here, since (e + 0.5) / d is at least 1 / (2 d) away from any integer
+    // and e < 2^13, d <= 64, against a relative error below 2^-21.
     int st_z[GV_STAGE];
     float st_s[GV_STAGE];
-    const int n_rec = my_nt * recs_per_nt * 16;
+    const int n_rec = my_nt * 16 * recs_per_nt;
+    const float inv_recs = __builtin_amdgcn_rcpf((float)recs_per_nt);
+    const float inv_tpg = __builtin_amdgcn_rcpf((float)a.tiles_per_group);
 #pragma unroll
     for (int i = 0; i < GV_STAGE; ++i) {
-        const int e = threadIdx.x + i * GV_THREADS;
-        st_z[i] = 0;
-        st_s[i] = 0.f;
-        if ((GROUPED || i == 0) && e < n_rec) {
-            const int row = e & 15, t = e >> 4;
-            const int j = t / recs_per_nt, ktl = t - j * recs_per_nt;
-            const int g = GROUPED ? (kt_begin + ktl) / tiles_per_group : 0;
-            const int64_t idx = (int64_t)((nt0 + j) * TILE_N + row) * ng + g;
-            st_z[i] = zero[idx];
-            st_s[i] = step[idx];
-        }
+        if (!GROUPED && i > 0) break;
+        // unconditional (index clamped): keeps the loads of all stages in flight together
+        const int e = min((int)threadIdx.x + i * GV_THREADS, n_rec - 1);
+        const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;   // 16 j + row
+        const int ktl = e - t * recs_per_nt;
+        const int g = GROUPED ? (int)(((float)(kt_begin + ktl) + 0.5f) * inv_tpg) : 0;
+        const int idx = (nt0 * TILE_N + t) * a.ng + g;   // < N * ng <= N * K / 128 < 2^31
+        st_z[i] = a.zero[idx];
+        st_s[i] = a.step[idx];
     }
     auto write_records = [&]() {
 #pragma unroll
         for (int i = 0; i < GV_STAGE; ++i) {
             const int e = threadIdx.x + i * GV_THREADS;
-            if ((GROUPED || i == 0) && e < n_rec) rec[e] = decode_record(st_z[i], st_s[i]);
+            if ((GROUPED || i == 0) && e < n_rec) {
+                const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
+                rec[t * RS + (e - t * recs_per_nt)] = decode_record(st_z[i], st_s[i]);
+            }
         }
     };
 
     if (wave == GV_CW) {
         // ================= helper wave: reduction across the compute waves + output ============
+        // lane owns outputs o = lane + 64 i: token m = 4 i + lane / 16, channel lane % 16
+        float sxm[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = 4 * i + (lane >> 4);
+            sxm[i] = (a.partial == nullptr && m < M) ? a.sx[m] : 0.f;
+        }
         write_records();
         lds_barrier();
         for (int j = 0; j < my_nt; ++j) {
             lds_barrier();  // the compute waves have published their partial sums of n-tile j
             const float *rb = red + (j & 1) * GV_CW * 256;
 #pragma unroll
-            for (int o4 = 0; o4 < 4; ++o4) {
-                const int o = lane + o4 * 64;  // output (token m = o >> 4, channel o & 15)
+            for (int i = 0; i < 4; ++i) {
+                const int o = lane + i * 64;
                 const int m = o >> 4;
                 float sum = 0.f;
 #pragma unroll
                 for (int w = 0; w < GV_CW; ++w) sum += rb[w * 256 + o];
                 if (m < M) {
                     const int n = (nt0 + j) * TILE_N + (o & 15);
-                    if (partial != nullptr) {
-                        partial[((int64_t)split * M + m) * N + n] = sum;
+                    if (a.partial != nullptr) {
+                        a.partial[((int64_t)split * M + m) * N + n] = sum;
                     } else {
-                        const float out = sx[m] * sum;
-                        Y[(int64_t)m * ldy + n] =
-                            (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+                        const float out = sxm[i] * sum;
+                        a.Y[(int64_t)m * a.ldy + n] =
+                            (a.y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
                     }
                 }
             }
@@ -134,86 +176,117 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(
     const int kb = lane >> 4;   // which 32 of the tile's 128 input channels this lane holds
     const int tpw = (KTs - wave + GV_CW - 1) / GV_CW;   // k-tiles of this wave: kt = wave + 8 u
     __amdgpu_buffer_rsrc_t rw =
-        __builtin_amdgcn_make_buffer_rsrc((void *)Wt, 0, (int)((int64_t)N * K / 2), 0x00020000);
-    __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)Xq, 0, M * K, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.Wt, 0, (int)((int64_t)N * K / 2), 0x00020000);
+    __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)a.Xq, 0, M * K, 0x00020000);
     // activation operand: token row ln, bytes kb*32 .. +32 of the k-tile; rows >= M lie beyond the
     // buffer and read as zero
     const int voff_x = ln * K + kb * 32 + kt_begin * TILE_K;
     const int wt_lane = lane * 16;
     const int tile0 = nt0 * KT + kt_begin + wave;       // first weight tile of this wave
 
-    v4u p[AT], a0[AT], a1[AT];
-#pragma unroll
-    for (int u = 0; u < AT; ++u)   // weights first: they come from HBM
-        p[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, u < tpw ? wt_lane : GV_OOB,
-                                                     u < tpw ? (tile0 + u * GV_CW) * TILE_BYTES : 0, 0);
+    // slot [d][u]: k-tile u of an n-tile j with j % D == d; out of range when there is none
+    v4u p[D][AT], a0[AT], a1[AT];
+    auto load_w = [&](int j, int u) {
+        const bool ok = j < my_nt && u < tpw;
+        return __builtin_amdgcn_raw_buffer_load_b128(
+            rw, ok ? wt_lane : GV_OOB, ok ? (tile0 + j * KT + u * GV_CW) * TILE_BYTES : 0, 0);
+    };
+    // decode record of (n-tile j, this lane's channel, slot u), clamped into the staged range
+    auto load_rec = [&](int j, int u) {
+        const int jr = min(j, my_nt - 1);
+        const int ktl = GROUPED ? min(wave + u * GV_CW, KTs - 1) : 0;
+        return rec[(jr * 16 + ln) * RS + ktl];
+    };
+    // Issue order = arrival order (a wave's loads return in order): after the parameters above,
+    // per slot the activations and the first n-tile's weights, then ring rows 1 .. D-1.
 #pragma unroll
     for (int u = 0; u < AT; ++u) {
+        // slots without a k-tile hold zero activations, so whatever is computed there adds nothing
         const int vo = u < tpw ? voff_x + (wave + u * GV_CW) * TILE_K : GV_OOB;
         a0[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, 0, 0);
         a1[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo + 16, 0, 0);
+        p[0][u] = load_w(0, u);
     }
+#pragma unroll
+    for (int d = 1; d < D; ++d)
+#pragma unroll
+        for (int u = 0; u < AT; ++u) p[d][u] = load_w(d, u);
+    order_fence();
     write_records();
     lds_barrier();
 
     const v4i zero4 = {0, 0, 0, 0};
     v4i acc = zero4;
     v4f y = {0.f, 0.f, 0.f, 0.f};
-    for (int j = 0; j < my_nt; ++j) {
-        const bool more = j + 1 < my_nt;
-        const v4u *rj = rec + j * recs_per_nt * 16 + ln;
-        v4u r = rj[0];   // per-channel record (overwritten per tile when GROUPED)
+    v4u r = load_rec(0, 0);
+    // one n-tile: consume ring row d, optionally refilling it for n-tile j + D
+    auto step_ntile = [&](int j, int d, bool refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < AT; ++u) {
-            const v4u pc = p[u];
-            // refill the slot with the same k-tile of the next n-tile (out of range when none)
-            const bool refill = more && u < tpw;
-            p[u] = __builtin_amdgcn_raw_buffer_load_b128(
-                rw, refill ? wt_lane : GV_OOB, refill ? (tile0 + (j + 1) * KT + u * GV_CW) * TILE_BYTES : 0, 0);
-            if (u < tpw) {
-                const int ktl = wave + u * GV_CW;
-                if (GROUPED) r = rj[ktl * 16];
-                const DecodeLut lut = {r.x, r.y, 0};
-                const v4i negb = {(int)r.w, (int)r.w, (int)r.w, (int)r.w};
-                const v4i c0 = as_v4i(a0[u]), c1 = as_v4i(a1[u]);
-                v4i w0, w1;
-                decode_lane(pc, lut, w0, w1);
-                // D[i][j] = sum_k A[i][k] B[k][j]: rows i = tokens, columns j = output channels.
-                // sum Xq 4(d + beta) - 4 beta sum Xq = 4 sum Xq d, exact in int32
+            // the record of the next slot is fetched one slot ahead
+            v4u rn = r;
+            if (u + 1 < AT) {
+                if (GROUPED) rn = load_rec(j, u + 1);
+            } else {
+                rn = load_rec(j + 1, 0);
+            }
+            const DecodeLut lut = {r.x, r.y, 0};
+            const v4i negb = {(int)r.w, (int)r.w, (int)r.w, (int)r.w};
+            const v4i c0 = as_v4i(a0[u]), c1 = as_v4i(a1[u]);
+            const bool live = u < tpw;   // uniform over the wave
+            // D[i][j] = sum_k A[i][k] B[k][j]: rows i = tokens, columns j = output channels.
+            // sum Xq 4(d + beta) - 4 beta sum Xq = 4 sum Xq d, exact in int32: the bias goes
+            // first (it needs no weights), then each half of the tile as soon as it is decoded.
+            v4i w1 = zero4;
+            if (live) {
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c0, negb, GROUPED ? zero4 : acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c1, negb, acc, 0, 0, 0);
+                v4i w0;
+                int x0, x1;
+                decode_word(p[d][u].x, lut, x0, x1); w0.x = x0; w0.y = x1;
+                decode_word(p[d][u].y, lut, x0, x1); w0.z = x0; w0.w = x1;
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c0, w0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c1, w1, acc, 0, 0, 0);
-                if (GROUPED) {
-                    const float es = __uint_as_float(r.z);
+                decode_word(p[d][u].z, lut, x0, x1); w1.x = x0; w1.y = x1;
+                decode_word(p[d][u].w, lut, x0, x1); w1.z = x0; w1.w = x1;
+            }
+            // Refill the slot with the same k-tile of the n-tile D further on.  The load comes
+            // after the last read of the old contents, so it can land in the same registers and
+            // the ring needs no copies (which would have to wait for the data to arrive).
+            order_fence();
+            if (refill) p[d][u] = load_w(j + D, u);
+            order_fence();
+            if (live) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c1, w1, acc, 0, 0, 0);
+            if (GROUPED && live) {
+                const float es = __uint_as_float(r.z);
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)acc[rr];
-                    if (ACC_OUT) {
-                        const int g = (kt_begin + ktl) / tiles_per_group;
+                for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)acc[rr];
+                if (ACC_OUT) {
+                    const int g = (kt_begin + wave + u * GV_CW) / a.tiles_per_group;
 #pragma unroll
-                        for (int rr = 0; rr < 4; ++rr) {
-                            const int m = 4 * kb + rr;
-                            if (m < M)
-                                atomicAdd(&acc_out[((int64_t)m * N + (nt0 + j) * TILE_N + ln) * ng + g],
-                                          acc[rr] >> 2);
-                        }
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int m = 4 * kb + rr;
+                        if (m < M)
+                            atomicAdd(&a.acc_out[((int64_t)m * N + (nt0 + j) * TILE_N + ln) * a.ng + g],
+                                      acc[rr] >> 2);
                     }
                 }
             }
-        }
-        if (!GROUPED) {
-            const float es = __uint_as_float(r.z);
+            if (!GROUPED && u == AT - 1) {
+                const float es = __uint_as_float(r.z);
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) y[rr] = es * (float)acc[rr];
-            if (ACC_OUT) {
+                for (int rr = 0; rr < 4; ++rr) y[rr] = es * (float)acc[rr];
+                if (ACC_OUT && tpw > 0) {
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const int m = 4 * kb + rr;
-                    if (m < M && tpw > 0)
-                        atomicAdd(&acc_out[(int64_t)m * N + (nt0 + j) * TILE_N + ln], acc[rr] >> 2);
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int m = 4 * kb + rr;
+                        if (m < M)
+                            atomicAdd(&a.acc_out[(int64_t)m * N + (nt0 + j) * TILE_N + ln], acc[rr] >> 2);
+                    }
                 }
+                acc = zero4;
             }
-            acc = zero4;
+            r = rn;
+            order_fence();   // keeps the unrolled slots from being interleaved
         }
         // accumulator layout: lane holds tokens m = 4 kb + rr of output channel ln
         float *rb = red + ((j & 1) * GV_CW + wave) * 256;
@@ -223,7 +296,18 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(
             y[rr] = 0.f;
         }
         lds_barrier();
+    };
+
+    // whole rounds of D n-tiles with refill (loads past the last n-tile go out of range), then
+    // the last my_nt % D n-tiles, which only consume
+    int j0 = 0;
+    for (; j0 + D <= my_nt; j0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) step_ntile(j0 + d, d, true);
     }
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)
+        if (j0 + d < my_nt) step_ntile(j0 + d, d, false);
 }
 
 // Y[m,n] = cast(sx[m] * sum_s partial[s,m,n]), fixed order over the K-splits.
@@ -249,37 +333,47 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G)
     pl.kt_per_split = (KT + pl.splits - 1) / pl.splits;
     pl.splits = (KT + pl.kt_per_split - 1) / pl.kt_per_split;
     const int tpw = (pl.kt_per_split + GV_CW - 1) / GV_CW;
-    pl.at = tpw <= 4 ? 4 : (tpw <= 6 ? 6 : 8);
+    pl.at = tpw;   // 1 .. GV_MAX_AT
     const bool grouped = G != K;
-    // equal numbers of n-tiles per workgroup, about one workgroup per CU
-    // (more, shorter-lived workgroups measured slower: each one reloads its activation fragments)
-    int q = (int)(((int64_t)NT * pl.splits + 255) / 256);
+    // about one workgroup per CU, n-tiles dealt out evenly (more, shorter-lived workgroups
+    // measured slower: each one reloads its activation fragments)
+    int bps = 256 / pl.splits;
+    if (bps < 1) bps = 1;
+    if (bps > NT) bps = NT;
+    int q = (NT + bps - 1) / bps;   // most n-tiles any workgroup gets
     const int recs = grouped ? pl.kt_per_split : 1;
-    const int q_lds = GV_LDS_BUDGET / (recs * 16 * 16);
-    const int q_stage = grouped ? (GV_STAGE * GV_THREADS) / (recs * 16) : GV_THREADS / 16;
-    if (q > q_lds) q = q_lds;
-    if (q > q_stage) q = q_stage;
-    if (q < 1) q = 1;
+    const int rs = grouped ? (pl.kt_per_split | 1) : 1;
+    const int q_lds = GV_LDS_BUDGET / (rs * 16 * 16);
+    const int q_stage = (grouped ? GV_STAGE * GV_THREADS : GV_THREADS) / (recs * 16);
+    const int q_cap = q_lds < q_stage ? q_lds : q_stage;
+    if (q > q_cap) {
+        q = q_cap;
+        bps = (NT + q - 1) / q;
+    }
     pl.q = q;
-    pl.blocks_per_split = (NT + q - 1) / q;
-    pl.lds_bytes = 2 * GV_CW * 256 * 4 + q * recs * 16 * 16;
+    pl.blocks_per_split = bps;
+    pl.nt_lo = NT / bps;
+    pl.nt_rem = NT % bps;
+    pl.lds_bytes = 2 * GV_CW * 256 * 4 + q * rs * 16 * 16;
     pl.partial_bytes = pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
     return pl;
 }
 
 template <bool GROUPED, bool ACC_OUT>
-static void launch_gemv_at(const GemvPlan &pl, dim3 grid, hipStream_t st, const int8_t *Xq,
-                           const float *sx, int M, const uint8_t *Wt, const float *step,
-                           const uint8_t *zero, int N, int K, int tpg, int ng, uint16_t *Y,
-                           int y_dtype, int64_t ldy, float *partial, int32_t *acc_out)
+static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, hipStream_t st)
 {
-#define W4A8_GV_LAUNCH(AT_)                                                                      \
-    hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, ACC_OUT>), grid, dim3(GV_THREADS), pl.lds_bytes, \
-                       st, Xq, sx, M, Wt, step, zero, N, K, tpg, ng, Y, y_dtype, ldy, partial,   \
-                       acc_out, pl.q, pl.blocks_per_split, pl.kt_per_split)
-    if (pl.at == 4) W4A8_GV_LAUNCH(4);
-    else if (pl.at == 6) W4A8_GV_LAUNCH(6);
-    else W4A8_GV_LAUNCH(8);
+    const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits);
+#define W4A8_GV_LAUNCH(AT_, D_)                                                           \
+    hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT>), grid, dim3(GV_THREADS), \
+                       pl.lds_bytes, st, ga)
+    // ring depth: 8 - 10 KB per wave in flight, within the register budget of 9 waves per CU
+    switch (pl.at) {
+        case 1: W4A8_GV_LAUNCH(1, 4); break;
+        case 2: W4A8_GV_LAUNCH(2, 4); break;
+        case 3: W4A8_GV_LAUNCH(3, 3); break;
+        case 4: W4A8_GV_LAUNCH(4, 2); break;
+        default: W4A8_GV_LAUNCH(5, 2); break;
+    }
 #undef W4A8_GV_LAUNCH
 }
 
@@ -289,24 +383,19 @@ int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt,
 {
     const GemvPlan pl = plan_gemv(M, N, K, G);
     const bool grouped = G != K;
-    const int ng = (int)(K / G), tpg = (int)(G / TILE_K);
-    const dim3 grid((unsigned)(pl.blocks_per_split * pl.splits));
     float *part = pl.splits > 1 ? partial : nullptr;
-    uint16_t *y16 = (uint16_t *)Y;
+    GemvArgs ga;
+    ga.Xq = Xq; ga.sx = sx; ga.Wt = Wt; ga.step = step; ga.zero = zero;
+    ga.Y = (uint16_t *)Y; ga.partial = part; ga.acc_out = acc_out; ga.ldy = ldy;
+    ga.M = (int)M; ga.N = (int)N; ga.K = (int)K;
+    ga.tiles_per_group = (int)(G / TILE_K); ga.ng = (int)(K / G); ga.y_dtype = y_dtype;
+    ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
     if (grouped) {
-        if (acc_out)
-            launch_gemv_at<true, true>(pl, grid, st, Xq, sx, (int)M, Wt, step, zero, (int)N, (int)K,
-                                       tpg, ng, y16, y_dtype, ldy, part, acc_out);
-        else
-            launch_gemv_at<true, false>(pl, grid, st, Xq, sx, (int)M, Wt, step, zero, (int)N, (int)K,
-                                        tpg, ng, y16, y_dtype, ldy, part, acc_out);
+        if (acc_out) launch_gemv_at<true, true>(pl, ga, st);
+        else launch_gemv_at<true, false>(pl, ga, st);
     } else {
-        if (acc_out)
-            launch_gemv_at<false, true>(pl, grid, st, Xq, sx, (int)M, Wt, step, zero, (int)N, (int)K,
-                                        tpg, ng, y16, y_dtype, ldy, part, acc_out);
-        else
-            launch_gemv_at<false, false>(pl, grid, st, Xq, sx, (int)M, Wt, step, zero, (int)N,
-                                         (int)K, tpg, ng, y16, y_dtype, ldy, part, acc_out);
+        if (acc_out) launch_gemv_at<false, true>(pl, ga, st);
+        else launch_gemv_at<false, false>(pl, ga, st);
     }
     int rc = hip_status(hipGetLastError());
     if (rc != W4A8_OK || pl.splits == 1) return rc;

@@ -3,19 +3,26 @@
 // dequantizing epilogue; the dINT4 x INT8 multiply-accumulate of Sec. 4.3).
 //
 // v_mfma_i32_32x32x32_i8 is the instruction to build on: measured on MI355X it sustains ~4.5 POPS,
-// twice what v_mfma_i32_16x16x64_i8 reaches.  A workgroup of 4 wavefronts computes a BM x 256
-// output tile; wave w owns all BM token rows of 64 output channels (two 32-channel sub-tiles), so
-// every packed weight is decoded by exactly one wave and never touches LDS: per 128 columns of K
-// the wave reads 4 KB of packed weights straight from global memory (16 bytes per lane per load,
-// prefetched one k-tile ahead), turns the nibbles into int8 through the per-channel register LUT
-// and reuses each decoded operand for all BM / 32 token sub-tiles.  The int8 activations are staged
-// through LDS (double buffered, 16-byte chunks XOR-swizzled by row so both the staging writes and
-// the ds_read_b128 operand reads are conflict free) and shared by the 4 waves.
+// twice what v_mfma_i32_16x16x64_i8 reaches.  A workgroup of WM x 4 wavefronts (WM = 1 or 2)
+// computes a BM x 256 output tile; a wave owns BM / WM token rows of 64 output channels (two
+// 32-channel sub-tiles).  Packed weights never touch LDS: per 128 columns of K a wave reads the
+// 4 KB of its 64 channels straight from global memory (16-byte buffer loads, issued two k-tiles
+// ahead), turns the nibbles into int8 through the per-channel register LUT and reuses each
+// decoded operand for all its 32-token sub-tiles.  The int8 activations are shared by the waves
+// through a three-deep ring of LDS tiles (global -> registers -> LDS, three k-tiles ahead of the
+// MFMAs; 16-byte chunks XOR-swizzled by row pair so that staging writes and ds_read_b128 operand
+// reads are conflict free on the 64-bank LDS).  One barrier per k-tile; the operands of the
+// first k-step of the next tile are fetched before it.
 //
 // Per-channel weights use the biased decode (7 operations per 8 weights); the bias is removed once,
 // in the epilogue, with per-token row-sums from a small pre-pass.  Group-wise weights must rescale
 // every accumulator once per group, so they use the signed decode (no bias term) and keep fp32
-// running sums next to the int32 group accumulators (BM <= 128).
+// running sums next to the int32 group accumulators (BM <= 128); the group's (step, zero) pairs
+// reach the waves through LDS, fetched three groups ahead.
+//
+// When the output has too few tiles to occupy 256 CUs (mid-size M) K is cut into ranges as well:
+// each workgroup writes an fp32 partial of its range and a small kernel adds the ranges in a fixed
+// order, applies the token scale and casts (deterministic; the int32 hook uses exact atomic adds).
 #include "w4a8_common.hpp"
 
 namespace w4a8 {

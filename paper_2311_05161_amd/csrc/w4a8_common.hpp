@@ -154,9 +154,10 @@ int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st);
 struct GemvPlan {
     int splits;            // K is cut into this many ranges, each handled by its own workgroups
     int kt_per_split;      // 128-column k-tiles per range
-    int at;                // k-tile slots per compute wave (template instance)
+    int at;                // k-tiles per compute wave (template instance)
     int q;                 // consecutive 16-channel n-tiles per workgroup
     int blocks_per_split;
+    int nt_lo, nt_rem;     // workgroup b of a split owns nt_lo (+1 if b < nt_rem) n-tiles
     int lds_bytes;
     size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1, else 0
 };

@@ -49,8 +49,14 @@ def test_workspace_sizes(lib):
     need = lib.gemm_workspace_bytes(16, 4096, 4096, 128, lib.LAYOUT_CANONICAL)
     assert need == 4096 * 4096 // 2
     assert lib.gemm_workspace_bytes(16, 4096, 4096, 100, lib.LAYOUT_TILED) == 0  # invalid group
-    # K > 8192 at decode is split over workgroups: fp32 partial sums [splits][M][N]
-    assert lib.gemm_workspace_bytes(16, 5120, 13824, 128, lib.LAYOUT_TILED) == 2 * 16 * 5120 * 4
+    # K > 5120 at decode is split over workgroups: fp32 partial sums [splits][M][N]
+    assert lib.gemm_workspace_bytes(16, 5120, 13824, 128, lib.LAYOUT_TILED) == 3 * 16 * 5120 * 4
+    assert lib.gemm_workspace_bytes(16, 13824, 5120, 128, lib.LAYOUT_TILED) == 0
+    # mid-size M with few output tiles: K is split as well (here 10 ranges of 4 k-tiles), and the
+    # per-channel variant adds one row-sum per (range, token), 256-byte aligned before the partials
+    part = 10 * 128 * 5120 * 4
+    assert lib.gemm_workspace_bytes(128, 5120, 5120, 128, lib.LAYOUT_TILED) == part
+    assert lib.gemm_workspace_bytes(128, 5120, 5120, 0, lib.LAYOUT_TILED) == 10 * 128 * 4 + part
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):
@@ -85,6 +91,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert gemm(K=256, G=100) == b.ERR_SHAPE
     assert gemm(ldy=8) == b.ERR_SHAPE
     assert gemm(K=128 * 2048) == b.ERR_SHAPE         # beyond the int32-safe K
+    assert gemm(K=65536 + 128) == b.ERR_SHAPE
+    assert gemm(M=1 << 20, K=4096, ws=P, wsb=1 << 40) == b.ERR_SHAPE   # 32-bit offsets into Xq
+    assert gemm(N=1 << 20, K=4096, ldy=1 << 20) == b.ERR_SHAPE         # 32-bit offsets into the weights
     assert gemm(ydt=b.F32) == b.ERR_DTYPE
     assert gemm(layout=3) == b.ERR_DTYPE
     assert gemm(Xq=Z) == b.ERR_NULL
