@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 # HBM bytes per gemv_kernel launch on this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by a 256 MiB copy (profiles/gemv_kernel_C2_decode_hbm_traffic.md): 9,694,208 read + 131,072 written
-GEMV_C2_TRAFFIC_BYTES = 9825280
+GEMV_C2_TRAFFIC_BYTES = 9830400
 METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
 
 
