@@ -336,3 +336,151 @@ int oracle_dequant_epilogue(const int32_t *acc, const float *sx, const float *st
         }
     return 0;
 }
+
+/* ========================================================================
+ * Asymmetric activations: the paper's own activation quantizer is min-max
+ * asymmetric, token-wise, 8 bit (App. A.1, "Quantization Settings").  Same
+ * convention as the weights: the range of a token is extended to contain 0, so
+ * that the real value 0 is a level.
+ *
+ *   t[m,k] = X[m,k] * r[k]                           r[k] = 1 / s[k]
+ *   lo = min(0, min_k t), hi = max(0, max_k t)
+ *   hi == lo : sx = 1, zx = 0, Q[m,:] = 0
+ *   else     : sx = (hi - lo) / 255 ; isx = 1 / sx
+ *              zx = clamp(rne(-lo * isx), 0, 255)
+ *              Q[m,k] = clamp(rne(t * isx) + zx, 0, 255)      (codes 0..255)
+ *   dequantized value: (Q - zx) * sx
+ * ---------------------------------------------------------------------- */
+int oracle_quantize_act_uint8_asym(const float *X, int64_t M, int64_t K, int64_t ldx,
+                                   const float *s, uint8_t *Q, float *sx, int32_t *zx,
+                                   float *rbuf)
+{
+    if (!X || !Q || !sx || !zx || !rbuf || M < 0 || K <= 0 || ldx < K) return 1;
+    for (int64_t k = 0; k < K; ++k) rbuf[k] = s ? 1.0f / s[k] : 1.0f;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + m * ldx;
+        float lo = 0.0f, hi = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = x[k] * rbuf[k];
+            if (t < lo) lo = t;
+            if (t > hi) hi = t;
+        }
+        uint8_t *q = Q + m * K;
+        if (hi == lo) {
+            sx[m] = 1.0f;
+            zx[m] = 0;
+            for (int64_t k = 0; k < K; ++k) q[k] = 0;
+            continue;
+        }
+        float range = hi - lo;
+        float st = range / 255.0f;
+        float isx = 1.0f / st;
+        float zf = nearbyintf(-lo * isx);
+        if (zf < 0.0f) zf = 0.0f;
+        if (zf > 255.0f) zf = 255.0f;
+        sx[m] = st;
+        zx[m] = (int32_t)zf;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = x[k] * rbuf[k];
+            float v = nearbyintf(t * isx) + zf;
+            if (v < 0.0f) v = 0.0f;
+            if (v > 255.0f) v = 255.0f;
+            q[k] = (uint8_t)(int)v;
+        }
+    }
+    return 0;
+}
+
+/* Integer GEMM with a token zero-point:
+ *   acc[m,n,g] = sum_{k in group g} (Q[m,k] - zx[m]) * decode(code[n,k], zero[n,g])
+ * (|Q - zx| <= 255, |decode| <= 26: exact in the 64-bit running sum, and the
+ * result fits int32 for any K < 300000.)  Layouts as in oracle_int_gemm. */
+int oracle_int_gemm_asym(const uint8_t *Q, const int32_t *zx, int64_t M, const uint8_t *packed,
+                         const uint8_t *zero, int64_t N, int64_t K, int64_t G, int32_t *acc)
+{
+    if (G == 0) G = K;
+    if (!Q || !zx || !packed || !zero || !acc || K <= 0 || (K & 1) || G <= 0 || K % G) return 1;
+    const int64_t ng = K / G;
+
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t g = 0; g < ng; ++g) {
+                int z = zero[n * ng + g];
+                int64_t sum = 0;
+                for (int64_t k = g * G; k < (g + 1) * G; ++k) {
+                    uint8_t b = packed[n * (K / 2) + k / 2];
+                    int code = (k & 1) ? (b >> 4) : (b & 0xF);
+                    int64_t xv = (int64_t)Q[m * K + k] - (int64_t)zx[m];
+                    sum += xv * (int64_t)oracle_decode_dint4(code, z);
+                }
+                acc[(m * N + n) * ng + g] = (int32_t)sum;
+            }
+    return 0;
+}
+
+/* The same for a list of output coordinates (see oracle_int_gemm_sampled). */
+int oracle_int_gemm_asym_sampled(const uint8_t *Q, const int32_t *zx, int64_t M,
+                                 const uint8_t *packed, const uint8_t *zero, int64_t N, int64_t K,
+                                 int64_t G, const int64_t *mi, const int64_t *ni, int64_t nidx,
+                                 int32_t *acc)
+{
+    if (G == 0) G = K;
+    if (!Q || !zx || !packed || !zero || !acc || !mi || !ni || K <= 0 || (K & 1) || G <= 0 ||
+        K % G)
+        return 1;
+    const int64_t ng = K / G;
+    for (int64_t i = 0; i < nidx; ++i)
+        if (mi[i] < 0 || mi[i] >= M || ni[i] < 0 || ni[i] >= N) return 1;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nidx; ++i) {
+        const int64_t m = mi[i], n = ni[i];
+        for (int64_t g = 0; g < ng; ++g) {
+            int z = zero[n * ng + g];
+            int64_t sum = 0;
+            for (int64_t k = g * G; k < (g + 1) * G; ++k) {
+                uint8_t b = packed[n * (K / 2) + k / 2];
+                int code = (k & 1) ? (b >> 4) : (b & 0xF);
+                int64_t xv = (int64_t)Q[m * K + k] - (int64_t)zx[m];
+                sum += xv * (int64_t)oracle_decode_dint4(code, z);
+            }
+            acc[i * ng + g] = (int32_t)sum;
+        }
+    }
+    return 0;
+}
+
+/* Sums of the weights of a group in half steps, and of a row in real units: what an
+ * implementation needs to take the token zero-point out of a product computed on the codes,
+ *   sum_k (Q - zx) d = sum_k Q d - zx * wsum.
+ *   wsum[n,g] = sum_{k in g} decode(code[n,k], zero[n,g])                      (exact)
+ *   c[n]      = 0 ; for g ascending: c += (0.5 * step[n,g]) * (float)wsum[n,g]  (binary32) */
+int oracle_weight_sums(const uint8_t *packed, const uint8_t *zero, const float *step, int64_t N,
+                       int64_t K, int64_t G, int32_t *wsum, float *c)
+{
+    if (G == 0) G = K;
+    if (!packed || !zero || !step || !wsum || !c || K <= 0 || (K & 1) || G <= 0 || K % G) return 1;
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float cn = 0.0f;
+        for (int64_t g = 0; g < ng; ++g) {
+            int z = zero[n * ng + g];
+            int64_t sum = 0;
+            for (int64_t k = g * G; k < (g + 1) * G; ++k) {
+                uint8_t b = packed[n * (K / 2) + k / 2];
+                int code = (k & 1) ? (b >> 4) : (b & 0xF);
+                sum += oracle_decode_dint4(code, z);
+            }
+            wsum[n * ng + g] = (int32_t)sum;
+            float h = 0.5f * step[n * ng + g];
+            float prod = h * (float)(int32_t)sum;
+            cn = cn + prod;
+        }
+        c[n] = cn;
+    }
+    return 0;
+}

@@ -21,6 +21,8 @@ __all__ = [
     "build", "num_threads", "quantize_act_int8", "quantize_weight_dint4", "pack_dint4",
     "unpack_dint4", "decode_dint4", "dequant_dint4", "int_gemm", "int_gemm_sampled",
     "dequant_epilogue", "cast_output", "linear_w4a8",
+    "quantize_act_uint8_asym", "int_gemm_asym", "int_gemm_asym_sampled", "weight_sums",
+    "linear_w4a8_asym",
 ]
 
 
@@ -51,6 +53,11 @@ def _load():
         lib.oracle_int_gemm.argtypes = [vp, i64, vp, vp, i64, i64, i64, vp]
         lib.oracle_int_gemm_sampled.argtypes = [vp, i64, vp, vp, i64, i64, i64, vp, vp, i64, vp]
         lib.oracle_dequant_epilogue.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
+        lib.oracle_quantize_act_uint8_asym.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
+        lib.oracle_int_gemm_asym.argtypes = [vp, vp, i64, vp, vp, i64, i64, i64, vp]
+        lib.oracle_int_gemm_asym_sampled.argtypes = [vp, vp, i64, vp, vp, i64, i64, i64, vp, vp,
+                                                     i64, vp]
+        lib.oracle_weight_sums.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
         _lib = lib
     return _lib
 
@@ -214,3 +221,81 @@ def linear_w4a8(X, W, s=None, group_size=0):
     y32, y64 = dequant_epilogue(acc, sx, step)
     return dict(Xq=Xq, sx=sx, codes=codes, step=step, zero=zero, packed=packed, acc=acc,
                 Y32=y32, Y64=y64)
+
+
+# ---- asymmetric (min-max, token zero-point) activations: App. A.1 ------------------------------
+def quantize_act_uint8_asym(X, s=None):
+    """Per-token min-max asymmetric 8-bit codes of X diag(s)^-1.
+    Returns (Q uint8 [M,K], sx float32 [M], zx int32 [M]); value = (Q - zx) * sx."""
+    X = _as_f32(X)
+    M, K = X.shape
+    s32 = None if s is None else np.ascontiguousarray(s, dtype=np.float32)
+    Q = np.empty((M, K), np.uint8)
+    sx = np.empty((M,), np.float32)
+    zx = np.empty((M,), np.int32)
+    rbuf = np.empty((K,), np.float32)
+    _check(_load().oracle_quantize_act_uint8_asym(_p(X), M, K, K, _p(s32), _p(Q), _p(sx), _p(zx),
+                                                  _p(rbuf)), "quantize_act_uint8_asym")
+    return Q, sx, zx
+
+
+def int_gemm_asym(Q, zx, packed, zero, group_size=0):
+    """acc[m,n,g] = sum_k (Q - zx) * d from uint8 codes with a token zero-point."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint8)
+    zx = np.ascontiguousarray(zx, dtype=np.int32)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    M, K = Q.shape
+    N = packed.shape[0]
+    if packed.shape[1] * 2 != K or zx.shape != (M,):
+        raise ValueError("oracle int_gemm_asym: shape mismatch")
+    G = K if group_size in (0, None) else int(group_size)
+    zero = np.ascontiguousarray(zero, dtype=np.uint8).reshape(N, K // G)
+    acc = np.empty((M, N, K // G), np.int32)
+    _check(_load().oracle_int_gemm_asym(_p(Q), _p(zx), M, _p(packed), _p(zero), N, K, G, _p(acc)),
+           "int_gemm_asym")
+    return acc
+
+
+def int_gemm_asym_sampled(Q, zx, packed, zero, group_size, mi, ni):
+    """acc[i,g] for the output coordinates (mi[i], ni[i])."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint8)
+    zx = np.ascontiguousarray(zx, dtype=np.int32)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    M, K = Q.shape
+    N = packed.shape[0]
+    G = K if group_size in (0, None) else int(group_size)
+    zero = np.ascontiguousarray(zero, dtype=np.uint8).reshape(N, K // G)
+    mi = np.ascontiguousarray(mi, dtype=np.int64)
+    ni = np.ascontiguousarray(ni, dtype=np.int64)
+    acc = np.empty((mi.size, K // G), np.int32)
+    _check(_load().oracle_int_gemm_asym_sampled(_p(Q), _p(zx), M, _p(packed), _p(zero), N, K, G,
+                                                _p(mi), _p(ni), mi.size, _p(acc)),
+           "int_gemm_asym_sampled")
+    return acc
+
+
+def weight_sums(packed, zero, step, group_size=0):
+    """(wsum int32 [N,ng], c float32 [N]): group sums of the weights in half steps and row sums
+    in real units."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    N, K = packed.shape[0], packed.shape[1] * 2
+    G = K if group_size in (0, None) else int(group_size)
+    zero = np.ascontiguousarray(zero, dtype=np.uint8).reshape(N, K // G)
+    step = np.ascontiguousarray(step, dtype=np.float32).reshape(N, K // G)
+    wsum = np.empty((N, K // G), np.int32)
+    c = np.empty((N,), np.float32)
+    _check(_load().oracle_weight_sums(_p(packed), _p(zero), _p(step), N, K, G, _p(wsum), _p(c)),
+           "weight_sums")
+    return wsum, c
+
+
+def linear_w4a8_asym(X, W, s=None, group_size=0):
+    """Whole path with asymmetric activations on the CPU."""
+    Q, sx, zx = quantize_act_uint8_asym(X, s)
+    codes, step, zero = quantize_weight_dint4(W, s, group_size)
+    packed = pack_dint4(codes)
+    acc = int_gemm_asym(Q, zx, packed, zero, group_size)
+    y32, y64 = dequant_epilogue(acc, sx, step)
+    wsum, c = weight_sums(packed, zero, step, group_size)
+    return dict(Q=Q, sx=sx, zx=zx, codes=codes, step=step, zero=zero, packed=packed, acc=acc,
+                wsum=wsum, c=c, Y32=y32, Y64=y64)
