@@ -128,6 +128,47 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
               void *Y, int y_dtype, int64_t ldy,
               int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- Asymmetric activations: the min-max, token-wise 8-bit quantizer with a zero-point that the
+ * paper itself uses for activations (App. A.1, "Quantization Settings"), and the GEMM for it. ----
+ *
+ * Per token m, with t = X[m,:] * (1 / s):  lo = min(0, min t), hi = max(0, max t),
+ *     sx = (hi - lo) / 255,  zx = clamp(rne(-lo / sx), 0, 255),
+ *     code[m,k] = clamp(rne(t[k] / sx) + zx, 0, 255)          (value = (code - zx) * sx)
+ * (1/s and 1/sx are correctly rounded reciprocals, one binary32 operation per step; an all-zero
+ * token gives sx = 1, zx = 0, codes 0).  Storage: the signed int8 matrix cores take
+ *     Xq[m,k] = code - 128      and      zx[m] = zero-point - 128        (both in -128..127),
+ * which leaves code - zero-point unchanged.
+ *   X, s, ldx, Xq, sx as in quantize_act_int8;   zx  out  [M] int32                          */
+int quantize_act_int8_asym(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                           const float *s, int8_t *Xq, float *sx, int32_t *zx, void *stream);
+
+/* Sums of the quantized weights, computed once per weight matrix (offline, after
+ * quantize_weight_dint4).  They take the token zero-point out of a product computed on the stored
+ * codes, exactly, in int32:  sum_k (q - zx) d = sum_k q d - zx * sum_k d.
+ *   codes  in  [N, K] one dINT4 code per byte      zero  in  [N, K/G]
+ *   wsum   out [N, K/G] int32:    sum over the group of d[n,k] (weights in units of step/2)
+ *   tsum   out [N, K/128] int32:  the same over each block of 128 input channels (the GEMM's
+ *               k-tiles); NULL to skip it.  Needs K % 128 == 0 and G % 128 == 0.
+ * With G = 128 the two arrays hold the same numbers. */
+int dint4_weight_sums(const uint8_t *codes, const uint8_t *zero, int64_t N, int64_t K,
+                      int64_t group_size, int32_t *wsum, int32_t *tsum, void *stream);
+
+/* w4a8_gemm for activations quantized by quantize_act_int8_asym:
+ *     acc[m,n,g] = sum_{k in g} (Xq[m,k] - zx[m]) * d[n,k]                    (int32, exact)
+ *     Y[m,n]     = cast( sx[m] * sum_g (step[n,g] / 2) * acc[m,n,g] )
+ * The kernels multiply the stored codes and subtract zx[m] * (sum of the weights) from the int32
+ * accumulators before anything is converted to floating point.
+ *   zx    in  [M] int32 (as written by quantize_act_int8_asym)
+ *   wsum  in  [N, K/G] int32, tsum in [N, K/128] int32 (from dint4_weight_sums)
+ * Everything else (shapes, limits, workspace, errors) as for w4a8_gemm, whose
+ * w4a8_gemm_workspace_bytes also sizes this call's workspace. */
+int w4a8_gemm_asym(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
+                   const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                   const int32_t *wsum, const int32_t *tsum,
+                   int64_t N, int64_t K, int64_t group_size,
+                   void *Y, int y_dtype, int64_t ldy,
+                   int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *w4a8_status_string(int status);
 

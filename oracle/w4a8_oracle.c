@@ -453,34 +453,30 @@ int oracle_int_gemm_asym_sampled(const uint8_t *Q, const int32_t *zx, int64_t M,
     return 0;
 }
 
-/* Sums of the weights of a group in half steps, and of a row in real units: what an
- * implementation needs to take the token zero-point out of a product computed on the codes,
- *   sum_k (Q - zx) d = sum_k Q d - zx * wsum.
- *   wsum[n,g] = sum_{k in g} decode(code[n,k], zero[n,g])                      (exact)
- *   c[n]      = 0 ; for g ascending: c += (0.5 * step[n,g]) * (float)wsum[n,g]  (binary32) */
-int oracle_weight_sums(const uint8_t *packed, const uint8_t *zero, const float *step, int64_t N,
-                       int64_t K, int64_t G, int32_t *wsum, float *c)
+/* Sums of the quantized weights in half steps over blocks of T consecutive input channels (T
+ * divides the group size G): what an implementation needs to take the token zero-point out of
+ * a product computed on the codes,  sum_k (Q - zx) d = sum_k Q d - zx * sum_k d.
+ *   wsum[n,b] = sum_{k in block b} decode(code[n,k], zero[n, group of k])        (exact)
+ * T = G gives the group sums.  wsum: [N, K/T]. */
+int oracle_weight_sums(const uint8_t *packed, const uint8_t *zero, int64_t N, int64_t K, int64_t G,
+                       int64_t T, int32_t *wsum)
 {
     if (G == 0) G = K;
-    if (!packed || !zero || !step || !wsum || !c || K <= 0 || (K & 1) || G <= 0 || K % G) return 1;
-    const int64_t ng = K / G;
+    if (T == 0) T = G;
+    if (!packed || !zero || !wsum || K <= 0 || (K & 1) || G <= 0 || K % G || T <= 0 || G % T)
+        return 1;
+    const int64_t ng = K / G, nb = K / T;
 #pragma omp parallel for schedule(static)
-    for (int64_t n = 0; n < N; ++n) {
-        float cn = 0.0f;
-        for (int64_t g = 0; g < ng; ++g) {
-            int z = zero[n * ng + g];
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t b = 0; b < nb; ++b) {
+            int z = zero[n * ng + (b * T) / G];
             int64_t sum = 0;
-            for (int64_t k = g * G; k < (g + 1) * G; ++k) {
-                uint8_t b = packed[n * (K / 2) + k / 2];
-                int code = (k & 1) ? (b >> 4) : (b & 0xF);
+            for (int64_t k = b * T; k < (b + 1) * T; ++k) {
+                uint8_t by = packed[n * (K / 2) + k / 2];
+                int code = (k & 1) ? (by >> 4) : (by & 0xF);
                 sum += oracle_decode_dint4(code, z);
             }
-            wsum[n * ng + g] = (int32_t)sum;
-            float h = 0.5f * step[n * ng + g];
-            float prod = h * (float)(int32_t)sum;
-            cn = cn + prod;
+            wsum[n * nb + b] = (int32_t)sum;
         }
-        c[n] = cn;
-    }
     return 0;
 }

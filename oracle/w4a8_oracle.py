@@ -57,7 +57,7 @@ def _load():
         lib.oracle_int_gemm_asym.argtypes = [vp, vp, i64, vp, vp, i64, i64, i64, vp]
         lib.oracle_int_gemm_asym_sampled.argtypes = [vp, vp, i64, vp, vp, i64, i64, i64, vp, vp,
                                                      i64, vp]
-        lib.oracle_weight_sums.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
+        lib.oracle_weight_sums.argtypes = [vp, vp, i64, i64, i64, i64, vp]
         _lib = lib
     return _lib
 
@@ -274,19 +274,17 @@ def int_gemm_asym_sampled(Q, zx, packed, zero, group_size, mi, ni):
     return acc
 
 
-def weight_sums(packed, zero, step, group_size=0):
-    """(wsum int32 [N,ng], c float32 [N]): group sums of the weights in half steps and row sums
-    in real units."""
+def weight_sums(packed, zero, group_size=0, block=0):
+    """wsum int32 [N, K/block]: sums of the weights in half steps over blocks of `block` input
+    channels (default: the quantization group)."""
     packed = np.ascontiguousarray(packed, dtype=np.uint8)
     N, K = packed.shape[0], packed.shape[1] * 2
     G = K if group_size in (0, None) else int(group_size)
+    T = G if block in (0, None) else int(block)
     zero = np.ascontiguousarray(zero, dtype=np.uint8).reshape(N, K // G)
-    step = np.ascontiguousarray(step, dtype=np.float32).reshape(N, K // G)
-    wsum = np.empty((N, K // G), np.int32)
-    c = np.empty((N,), np.float32)
-    _check(_load().oracle_weight_sums(_p(packed), _p(zero), _p(step), N, K, G, _p(wsum), _p(c)),
-           "weight_sums")
-    return wsum, c
+    wsum = np.empty((N, K // T), np.int32)
+    _check(_load().oracle_weight_sums(_p(packed), _p(zero), N, K, G, T, _p(wsum)), "weight_sums")
+    return wsum
 
 
 def linear_w4a8_asym(X, W, s=None, group_size=0):
@@ -296,6 +294,6 @@ def linear_w4a8_asym(X, W, s=None, group_size=0):
     packed = pack_dint4(codes)
     acc = int_gemm_asym(Q, zx, packed, zero, group_size)
     y32, y64 = dequant_epilogue(acc, sx, step)
-    wsum, c = weight_sums(packed, zero, step, group_size)
+    wsum = weight_sums(packed, zero, group_size)
     return dict(Q=Q, sx=sx, zx=zx, codes=codes, step=step, zero=zero, packed=packed, acc=acc,
-                wsum=wsum, c=c, Y32=y32, Y64=y64)
+                wsum=wsum, Y32=y32, Y64=y64)

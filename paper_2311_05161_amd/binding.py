@@ -23,6 +23,7 @@ _DTYPES = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 EXPORTS = (
     "quantize_act_int8", "quantize_weight_dint4", "pack_dint4", "unpack_dint4",
     "w4a8_gemm_workspace_bytes", "w4a8_gemm", "w4a8_status_string",
+    "quantize_act_int8_asym", "dint4_weight_sums", "w4a8_gemm_asym",
 )
 
 _lib = None
@@ -57,6 +58,13 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.w4a8_gemm_workspace_bytes.restype = sz
     lib.w4a8_gemm.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, vp, ci, i64, vp, vp, sz, vp]
     lib.w4a8_gemm.restype = ci
+    lib.quantize_act_int8_asym.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp, vp]
+    lib.quantize_act_int8_asym.restype = ci
+    lib.dint4_weight_sums.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
+    lib.dint4_weight_sums.restype = ci
+    lib.w4a8_gemm_asym.argtypes = [vp, vp, vp, i64, vp, ci, vp, vp, vp, vp, i64, i64, i64, vp, ci,
+                                   i64, vp, vp, sz, vp]
+    lib.w4a8_gemm_asym.restype = ci
     lib.w4a8_status_string.argtypes = [ci]
     lib.w4a8_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -159,4 +167,58 @@ def w4a8_gemm(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.
                                     _ptr(zero), N, K, int(group_size or 0), _ptr(Y),
                                     _DTYPES[Y.dtype], ldy, _ptr(acc_out), _ptr(workspace), ws_bytes,
                                     _stream()), "w4a8_gemm")
+    return (Y, acc_out) if want_acc else Y
+
+
+def quantize_act_int8_asym(X: torch.Tensor, s: torch.Tensor | None = None, Xq=None, sx=None,
+                           zx=None):
+    """Token-wise min-max asymmetric 8-bit quantization of X diag(s)^-1.
+    Returns (Xq int8 = code - 128, sx float32 [M], zx int32 [M] = zero-point - 128)."""
+    M, K, ldx = _rows(X, "X")
+    if Xq is None:
+        Xq = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    if sx is None:
+        sx = torch.empty((M,), dtype=torch.float32, device=X.device)
+    if zx is None:
+        zx = torch.empty((M,), dtype=torch.int32, device=X.device)
+    _check(load_library().quantize_act_int8_asym(_ptr(X), _DTYPES[X.dtype], M, K, ldx, _ptr(s),
+                                                 _ptr(Xq), _ptr(sx), _ptr(zx), _stream()),
+           "quantize_act_int8_asym")
+    return Xq, sx, zx
+
+
+def dint4_weight_sums(codes: torch.Tensor, zero: torch.Tensor, group_size: int = 0):
+    """(wsum int32 [N,K/G], tsum int32 [N,K/128]) of a quantized weight matrix (offline)."""
+    N, K = codes.shape
+    G = K if group_size in (0, None) else int(group_size)
+    ngr = K // G if G > 0 and K % G == 0 else 1
+    wsum = torch.empty((N, ngr), dtype=torch.int32, device=codes.device)
+    tsum = torch.empty((N, max(1, K // 128)), dtype=torch.int32, device=codes.device)
+    _check(load_library().dint4_weight_sums(_ptr(codes), _ptr(zero), N, K, int(group_size or 0),
+                                            _ptr(wsum), _ptr(tsum), _stream()),
+           "dint4_weight_sums")
+    return wsum, tsum
+
+
+def w4a8_gemm_asym(Xq: torch.Tensor, sx: torch.Tensor, zx: torch.Tensor, Wp: torch.Tensor,
+                   step: torch.Tensor, zero: torch.Tensor, wsum: torch.Tensor, tsum: torch.Tensor,
+                   N: int, K: int, group_size: int = 0, layout: int = LAYOUT_TILED,
+                   out_dtype=torch.float16, Y=None, acc_out=None, workspace=None, want_acc=False):
+    """w4a8_gemm for activations with a token zero-point (quantize_act_int8_asym)."""
+    M = Xq.shape[0]
+    if Y is None:
+        Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    G = K if group_size in (0, None) else int(group_size)
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((M, N, K // G), dtype=torch.int32, device=Xq.device)
+    need = gemm_workspace_bytes(M, N, K, group_size, layout)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=Xq.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ldy = Y.stride(0) if M > 1 else max(Y.stride(0), N)
+    _check(load_library().w4a8_gemm_asym(_ptr(Xq), _ptr(sx), _ptr(zx), M, _ptr(Wp), int(layout),
+                                         _ptr(step), _ptr(zero), _ptr(wsum), _ptr(tsum), N, K,
+                                         int(group_size or 0), _ptr(Y), _DTYPES[Y.dtype], ldy,
+                                         _ptr(acc_out), _ptr(workspace), ws_bytes, _stream()),
+           "w4a8_gemm_asym")
     return (Y, acc_out) if want_acc else Y

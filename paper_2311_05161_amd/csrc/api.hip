@@ -53,6 +53,65 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
     return w;
 }
 
+// w4a8_gemm and w4a8_gemm_asym (zx, wsum, tsum null for the former)
+int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
+                const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                const int32_t *wsum, const int32_t *tsum, int64_t N, int64_t K, int64_t group_size,
+                void *Y, int y_dtype, int64_t ldy,
+                int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!valid_layout(layout)) return W4A8_ERR_DTYPE;
+    if (y_dtype != W4A8_F16 && y_dtype != W4A8_BF16) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K || ldy < N ||
+        M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL)  // 32-bit byte offsets into the weights
+        return W4A8_ERR_SHAPE;
+    // the tile kernel addresses Xq with 32-bit byte offsets and numbers its tiles in 32 bits
+    if (M > 16 && (M * K > 0x7fffffffLL || (M + 63) / 64 * ((N + 255) / 256) > 0x1ffffLL))
+        return W4A8_ERR_SHAPE;
+    if (M == 0 || N == 0) return W4A8_OK;
+    if (!Xq || !sx || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;
+    if ((uintptr_t)Xq % 16 != 0 || (uintptr_t)Wp % 16 != 0 || (uintptr_t)Y % 2 != 0 ||
+        (acc_out && (uintptr_t)acc_out % 4 != 0))
+        return W4A8_ERR_SHAPE;
+
+    const WsPlan ws = plan_workspace(M, N, K, G, layout);
+    if (ws.total > 0) {
+        if (!workspace || workspace_bytes < ws.total) return W4A8_ERR_WORKSPACE;
+        if ((uintptr_t)workspace % WS_ALIGN != 0) return W4A8_ERR_WORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    uint8_t *wsb = (uint8_t *)workspace;
+    const ZeroPoint zp = {zx, wsum, tsum};
+
+    const uint8_t *Wt = Wp;
+    if (layout == W4A8_LAYOUT_CANONICAL) {
+        uint8_t *tiled = wsb + ws.repack_off;
+        const int rc = launch_repack_canonical_to_tiled(Wp, N, K, tiled, st);
+        if (rc != W4A8_OK) return rc;
+        Wt = tiled;
+    }
+    if (M <= 16) {
+        if (acc_out) {  // the split-K waves add exact partial sums into it
+            const int rc = launch_fill_i32(acc_out, M * N * (K / G), 0, st);
+            if (rc != W4A8_OK) return rc;
+        }
+        const int rc = launch_gemv(Xq, sx, zp, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
+                                   acc_out, (float *)(wsb + ws.part_off), st);
+        if (rc != W4A8_OK || !zx || !acc_out) return rc;
+        return launch_acc_zero_point(acc_out, zx, wsum, M, N * (K / G), st);
+    }
+    if (acc_out && ws.part_bytes > 0 && G == K) {  // K-split workgroups add exact partial sums
+        const int rc = launch_fill_i32(acc_out, M * N, 0, st);
+        if (rc != W4A8_OK) return rc;
+    }
+    const int rc = launch_gemm(Xq, sx, zp, (int32_t *)(wsb + ws.rs_off), M, Wt, step, zero, N,
+                               K, G, Y, y_dtype, ldy, acc_out, (float *)(wsb + ws.part_off), st);
+    if (rc != W4A8_OK || !zx || !acc_out) return rc;
+    return launch_acc_zero_point(acc_out, zx, wsum, M, N * (K / G), st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -77,7 +136,30 @@ int quantize_act_int8(const void *X, int x_dtype, int64_t M, int64_t K, int64_t 
     if (M < 0 || K < 1 || ldx < K || M > 0x7fffffffLL) return W4A8_ERR_SHAPE;
     if (M == 0) return W4A8_OK;
     if (!X || !Xq || !sx) return W4A8_ERR_NULL;
-    return launch_act_quant(X, x_dtype, M, K, ldx, s, Xq, sx, (hipStream_t)stream);
+    return launch_act_quant(X, x_dtype, M, K, ldx, s, Xq, sx, nullptr, (hipStream_t)stream);
+}
+
+int quantize_act_int8_asym(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                           const float *s, int8_t *Xq, float *sx, int32_t *zx, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return W4A8_ERR_DTYPE;
+    if (M < 0 || K < 1 || ldx < K || M > 0x7fffffffLL) return W4A8_ERR_SHAPE;
+    if (M == 0) return W4A8_OK;
+    if (!X || !Xq || !sx || !zx) return W4A8_ERR_NULL;
+    return launch_act_quant(X, x_dtype, M, K, ldx, s, Xq, sx, zx, (hipStream_t)stream);
+}
+
+int dint4_weight_sums(const uint8_t *codes, const uint8_t *zero, int64_t N, int64_t K,
+                      int64_t group_size, int32_t *wsum, int32_t *tsum, void *stream)
+{
+    int64_t G = group_size;
+    if (N < 0 || K < 1 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (tsum && (K % TILE_K != 0 || G % TILE_K != 0)) return W4A8_ERR_SHAPE;
+    if (N == 0) return W4A8_OK;
+    if (!codes || !zero || !wsum) return W4A8_ERR_NULL;
+    int rc = launch_weight_sums(codes, zero, N, K, G, G, wsum, (hipStream_t)stream);
+    if (rc != W4A8_OK || !tsum) return rc;
+    return launch_weight_sums(codes, zero, N, K, G, TILE_K, tsum, (hipStream_t)stream);
 }
 
 int quantize_weight_dint4(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
@@ -139,51 +221,20 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
               void *Y, int y_dtype, int64_t ldy,
               int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!valid_layout(layout)) return W4A8_ERR_DTYPE;
-    if (y_dtype != W4A8_F16 && y_dtype != W4A8_BF16) return W4A8_ERR_DTYPE;
-    int64_t G = group_size;
-    if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
-    if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K || ldy < N ||
-        M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL)  // 32-bit byte offsets into the weights
-        return W4A8_ERR_SHAPE;
-    // the tile kernel addresses Xq with 32-bit byte offsets and numbers its tiles in 32 bits
-    if (M > 16 && (M * K > 0x7fffffffLL || (M + 63) / 64 * ((N + 255) / 256) > 0x1ffffLL))
-        return W4A8_ERR_SHAPE;
-    if (M == 0 || N == 0) return W4A8_OK;
-    if (!Xq || !sx || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;
-    if ((uintptr_t)Xq % 16 != 0 || (uintptr_t)Wp % 16 != 0 || (uintptr_t)Y % 2 != 0 ||
-        (acc_out && (uintptr_t)acc_out % 4 != 0))
-        return W4A8_ERR_SHAPE;
+    return gemm_common(Xq, sx, nullptr, M, Wp, layout, step, zero, nullptr, nullptr, N, K,
+                       group_size, Y, y_dtype, ldy, acc_out, workspace, workspace_bytes, stream);
+}
 
-    const WsPlan ws = plan_workspace(M, N, K, G, layout);
-    if (ws.total > 0) {
-        if (!workspace || workspace_bytes < ws.total) return W4A8_ERR_WORKSPACE;
-        if ((uintptr_t)workspace % WS_ALIGN != 0) return W4A8_ERR_WORKSPACE;
-    }
-    hipStream_t st = (hipStream_t)stream;
-    uint8_t *wsb = (uint8_t *)workspace;
-
-    const uint8_t *Wt = Wp;
-    if (layout == W4A8_LAYOUT_CANONICAL) {
-        uint8_t *tiled = wsb + ws.repack_off;
-        const int rc = launch_repack_canonical_to_tiled(Wp, N, K, tiled, st);
-        if (rc != W4A8_OK) return rc;
-        Wt = tiled;
-    }
-    if (M <= 16) {
-        if (acc_out) {  // the split-K waves add exact partial sums into it
-            const int rc = launch_fill_i32(acc_out, M * N * (K / G), 0, st);
-            if (rc != W4A8_OK) return rc;
-        }
-        return launch_gemv(Xq, sx, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, acc_out,
-                           (float *)(wsb + ws.part_off), st);
-    }
-    if (acc_out && ws.part_bytes > 0 && G == K) {  // K-split workgroups add exact partial sums
-        const int rc = launch_fill_i32(acc_out, M * N, 0, st);
-        if (rc != W4A8_OK) return rc;
-    }
-    return launch_gemm(Xq, sx, (int32_t *)(wsb + ws.rs_off), M, Wt, step, zero, N, K, G, Y, y_dtype,
-                       ldy, acc_out, (float *)(wsb + ws.part_off), st);
+int w4a8_gemm_asym(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
+                   const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                   const int32_t *wsum, const int32_t *tsum,
+                   int64_t N, int64_t K, int64_t group_size,
+                   void *Y, int y_dtype, int64_t ldy,
+                   int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (M > 0 && N > 0 && (!zx || !wsum || !tsum)) return W4A8_ERR_NULL;
+    return gemm_common(Xq, sx, zx, M, Wp, layout, step, zero, wsum, tsum, N, K, group_size, Y,
+                       y_dtype, ldy, acc_out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -50,11 +50,14 @@ __device__ __forceinline__ void order_fence()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-__device__ __forceinline__ v4u decode_record(int z, float st)
+// Decode record of one (channel, k-tile): LUT halves, step / 8, and in the last word -4 beta as an
+// int8 in byte 0 with 4 * tsum in the upper 24 bits (tsum: sum of the tile's weights in half steps,
+// |4 tsum| <= 4 * 26 * 128; zero without a token zero-point).
+__device__ __forceinline__ v4u decode_record(int z, float st, int tsum)
 {
     const DecodeLut t = make_decode_lut(z);
-    const uint32_t nb8 = (uint32_t)(-t.beta_q) & 0xffu;  // -4 beta as an int8
-    return v4u{t.lo, t.hi, __float_as_uint(st * 0.125f), __builtin_amdgcn_perm(nb8, nb8, 0u)};
+    const uint32_t nb8 = (uint32_t)(-t.beta_q) & 0xffu;
+    return v4u{t.lo, t.hi, __float_as_uint(st * 0.125f), ((uint32_t)(4 * tsum) << 8) | nb8};
 }
 
 __device__ __forceinline__ v4i as_v4i(const v4u &v) { return v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w}; }
@@ -63,6 +66,9 @@ __device__ __forceinline__ v4i as_v4i(const v4u &v) { return v4i{(int)v.x, (int)
 struct GemvArgs {
     const int8_t *Xq;      // [M, K]
     const float *sx;       // [M]
+    const int32_t *zx;     // [M] token zero-points (asymmetric activations) or null
+    const int32_t *wsum;   // [N, ng] sums of the weights per group, in half steps (with zx)
+    const int32_t *tsum;   // [N, K / 128] the same per k-tile (with zx)
     const uint8_t *Wt;     // tiled packed weights
     const float *step;     // [N, ng]
     const uint8_t *zero;   // [N, ng]
@@ -78,7 +84,11 @@ struct GemvArgs {
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
 // AT k-tile slots per compute wave, weight ring D n-tiles deep.
-template <bool GROUPED, int AT, int D, bool ACC_OUT>
+// ASYM: the activations carry a token zero-point zx (stored codes and zx both offset by -128);
+// the exact term zx * (sum of the weights) is taken out in int32, per tile (GROUPED) or once per
+// output after the waves' int32 sums have been added (!GROUPED) -- never in floating point, where
+// the two large terms would cancel badly.
+template <bool GROUPED, int AT, int D, bool ACC_OUT, bool ASYM>
 __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -107,7 +117,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
     // Loads first, LUT arithmetic later.  Quotients by multiplication with an approximate
     // reciprocal: exact here, since (e + 0.5) / d is at least 1 / (2 d) away from any integer
     // and e < 2^13, d <= 64, against a relative error below 2^-21.
-    int st_z[GV_STAGE];
+    int st_z[GV_STAGE], st_t[GV_STAGE];
     float st_s[GV_STAGE];
     const int n_rec = my_nt * 16 * recs_per_nt;
     const float inv_recs = __builtin_amdgcn_rcpf((float)recs_per_nt);
@@ -123,6 +133,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
         const int idx = (nt0 * TILE_N + t) * a.ng + g;   // < N * ng <= N * K / 128 < 2^31
         st_z[i] = a.zero[idx];
         st_s[i] = a.step[idx];
+        st_t[i] = (ASYM && GROUPED) ? a.tsum[(nt0 * TILE_N + t) * KT + kt_begin + ktl] : 0;
     }
     auto write_records = [&]() {
 #pragma unroll
@@ -130,43 +141,57 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
             const int e = threadIdx.x + i * GV_THREADS;
             if ((GROUPED || i == 0) && e < n_rec) {
                 const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
-                rec[t * RS + (e - t * recs_per_nt)] = decode_record(st_z[i], st_s[i]);
+                rec[t * RS + (e - t * recs_per_nt)] = decode_record(st_z[i], st_s[i], st_t[i]);
             }
         }
     };
 
     if (wave == GV_CW) {
         // ================= helper wave: reduction across the compute waves + output ============
-        // lane owns outputs o = lane + 64 i: token m = 4 i + lane / 16, channel lane % 16
+        // lane owns outputs o = lane + 64 i: token m = 4 i + lane / 16, channel lane % 16.
+        // GROUPED: the waves publish fp32 sums (already scaled per group).  !GROUPED: they publish
+        // their int32 accumulators; the sum is exact, then zero-point term, step / 8, token scale.
         float sxm[4];
+        int zxm[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = 4 * i + (lane >> 4);
             sxm[i] = (a.partial == nullptr && m < M) ? a.sx[m] : 0.f;
+            zxm[i] = (ASYM && !GROUPED && a.partial == nullptr && m < M) ? a.zx[m] : 0;
         }
+        const bool zp = ASYM && !GROUPED && a.partial == nullptr;
+        int wn = zp ? a.wsum[nt0 * TILE_N + (lane & 15)] : 0;   // fetched one n-tile ahead
         write_records();
         lds_barrier();
         for (int j = 0; j < my_nt; ++j) {
             lds_barrier();  // the compute waves have published their partial sums of n-tile j
+            const int wn_next = (zp && j + 1 < my_nt) ? a.wsum[(nt0 + j + 1) * TILE_N + (lane & 15)] : 0;
             const float *rb = red + (j & 1) * GV_CW * 256;
+            const float es = GROUPED ? 0.f : __uint_as_float(rec[j * 16 + (lane & 15)].z);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int o = lane + i * 64;
                 const int m = o >> 4;
                 float sum = 0.f;
+                int isum = 0;
 #pragma unroll
-                for (int w = 0; w < GV_CW; ++w) sum += rb[w * 256 + o];
+                for (int w = 0; w < GV_CW; ++w) {
+                    if (GROUPED) sum += rb[w * 256 + o];
+                    else isum += __float_as_int(rb[w * 256 + o]);
+                }
                 if (m < M) {
                     const int n = (nt0 + j) * TILE_N + (o & 15);
                     if (a.partial != nullptr) {
-                        a.partial[((int64_t)split * M + m) * N + n] = sum;
+                        a.partial[((int64_t)split * M + m) * N + n] = GROUPED ? sum : __int_as_float(isum);
                     } else {
+                        if (!GROUPED) sum = es * (float)(isum - 4 * zxm[i] * wn);
                         const float out = sxm[i] * sum;
                         a.Y[(int64_t)m * a.ldy + n] =
                             (a.y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
                     }
                 }
             }
+            wn = wn_next;
         }
         return;
     }
@@ -219,6 +244,11 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
     v4i acc = zero4;
     v4f y = {0.f, 0.f, 0.f, 0.f};
     v4u r = load_rec(0, 0);
+    int nzx[4] = {0, 0, 0, 0};   // minus the zero-points of this lane's tokens m = 4 kb + rr
+    if (ASYM && GROUPED) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) nzx[rr] = 4 * kb + rr < M ? -a.zx[4 * kb + rr] : 0;
+    }
     // one n-tile: consume ring row d, optionally refilling it for n-tile j + D
     auto step_ntile = [&](int j, int d, bool refill) __attribute__((always_inline)) {
 #pragma unroll
@@ -231,7 +261,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
                 rn = load_rec(j + 1, 0);
             }
             const DecodeLut lut = {r.x, r.y, 0};
-            const v4i negb = {(int)r.w, (int)r.w, (int)r.w, (int)r.w};
+            const int nb = (int)__builtin_amdgcn_perm(r.w, r.w, 0u);   // byte 0 replicated
+            const v4i negb = {nb, nb, nb, nb};
             const v4i c0 = as_v4i(a0[u]), c1 = as_v4i(a1[u]);
             const bool live = u < tpw;   // uniform over the wave
             // D[i][j] = sum_k A[i][k] B[k][j]: rows i = tokens, columns j = output channels.
@@ -258,8 +289,14 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
             if (live) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c1, w1, acc, 0, 0, 0);
             if (GROUPED && live) {
                 const float es = __uint_as_float(r.z);
+                if (ASYM) {
+                    const int t4 = (int)r.w >> 8;   // 4 * (sum of the tile's weights)
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)acc[rr];
+                    for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)(acc[rr] + __mul24(nzx[rr], t4));
+                } else {
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)acc[rr];
+                }
                 if (ACC_OUT) {
                     const int g = (kt_begin + wave + u * GV_CW) / a.tiles_per_group;
 #pragma unroll
@@ -272,9 +309,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
                 }
             }
             if (!GROUPED && u == AT - 1) {
-                const float es = __uint_as_float(r.z);
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) y[rr] = es * (float)acc[rr];
+                for (int rr = 0; rr < 4; ++rr) y[rr] = __int_as_float(acc[rr]);   // summed exactly by the helper
                 if (ACC_OUT && tpw > 0) {
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
@@ -310,17 +346,29 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
         if (j0 + d < my_nt) step_ntile(j0 + d, d, false);
 }
 
-// Y[m,n] = cast(sx[m] * sum_s partial[s,m,n]), fixed order over the K-splits.
+// Y[m,n] = cast(sx[m] * sum_s partial[s,m,n]), fixed order over the K-splits.  int_step != null:
+// the partials are the int32 accumulators (times 4) of a per-channel launch; their exact sum,
+// minus the zero-point term when zx is given, is scaled by int_step[n] / 8.
 __global__ __launch_bounds__(256) void gemv_combine_kernel(const float *__restrict__ partial,
-                                                           const float *__restrict__ sx, int M, int N,
-                                                           int splits, uint16_t *__restrict__ Y,
+                                                           const float *__restrict__ sx,
+                                                           const float *__restrict__ int_step,
+                                                           const int32_t *__restrict__ zx,
+                                                           const int32_t *__restrict__ wsum, int M,
+                                                           int N, int splits, uint16_t *__restrict__ Y,
                                                            int y_dtype, int64_t ldy)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= (int64_t)M * N) return;
     const int m = (int)(i / N), n = (int)(i - (int64_t)m * N);
     float sum = 0.f;
-    for (int s = 0; s < splits; ++s) sum += partial[(int64_t)s * M * N + i];
+    if (int_step != nullptr) {
+        int isum = 0;
+        for (int s = 0; s < splits; ++s) isum += __float_as_int(partial[(int64_t)s * M * N + i]);
+        if (zx != nullptr) isum -= 4 * zx[m] * wsum[n];
+        sum = (int_step[n] * 0.125f) * (float)isum;
+    } else {
+        for (int s = 0; s < splits; ++s) sum += partial[(int64_t)s * M * N + i];
+    }
     const float out = sx[m] * sum;
     Y[(int64_t)m * ldy + n] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
 }
@@ -359,12 +407,12 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G)
     return pl;
 }
 
-template <bool GROUPED, bool ACC_OUT>
+template <bool GROUPED, bool ACC_OUT, bool ASYM>
 static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, hipStream_t st)
 {
     const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits);
-#define W4A8_GV_LAUNCH(AT_, D_)                                                           \
-    hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT>), grid, dim3(GV_THREADS), \
+#define W4A8_GV_LAUNCH(AT_, D_)                                                                  \
+    hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>), grid, dim3(GV_THREADS),  \
                        pl.lds_bytes, st, ga)
     // ring depth: 8 - 10 KB per wave in flight, within the register budget of 9 waves per CU
     switch (pl.at) {
@@ -377,37 +425,53 @@ static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, hipStream_t s
 #undef W4A8_GV_LAUNCH
 }
 
-int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt, const float *step,
-                const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
+int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
+                const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
+                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
 {
     const GemvPlan pl = plan_gemv(M, N, K, G);
     const bool grouped = G != K;
     float *part = pl.splits > 1 ? partial : nullptr;
     GemvArgs ga;
-    ga.Xq = Xq; ga.sx = sx; ga.Wt = Wt; ga.step = step; ga.zero = zero;
+    ga.Xq = Xq; ga.sx = sx; ga.zx = zp.zx; ga.wsum = zp.wsum; ga.tsum = zp.tsum; ga.Wt = Wt;
+    ga.step = step; ga.zero = zero;
     ga.Y = (uint16_t *)Y; ga.partial = part; ga.acc_out = acc_out; ga.ldy = ldy;
     ga.M = (int)M; ga.N = (int)N; ga.K = (int)K;
     ga.tiles_per_group = (int)(G / TILE_K); ga.ng = (int)(K / G); ga.y_dtype = y_dtype;
     ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
+    const bool asym = zp.zx != nullptr;
     if (grouped) {
-        if (acc_out) launch_gemv_at<true, true>(pl, ga, st);
-        else launch_gemv_at<true, false>(pl, ga, st);
+        // the per-tile zero-point term only exists in its own instances (asymmetric, grouped)
+        if (asym) {
+            if (acc_out) launch_gemv_at<true, true, true>(pl, ga, st);
+            else launch_gemv_at<true, false, true>(pl, ga, st);
+        } else {
+            if (acc_out) launch_gemv_at<true, true, false>(pl, ga, st);
+            else launch_gemv_at<true, false, false>(pl, ga, st);
+        }
     } else {
-        if (acc_out) launch_gemv_at<false, true>(pl, ga, st);
-        else launch_gemv_at<false, false>(pl, ga, st);
+        if (asym) {
+            if (acc_out) launch_gemv_at<false, true, true>(pl, ga, st);
+            else launch_gemv_at<false, false, true>(pl, ga, st);
+        } else {
+            if (acc_out) launch_gemv_at<false, true, false>(pl, ga, st);
+            else launch_gemv_at<false, false, false>(pl, ga, st);
+        }
     }
     int rc = hip_status(hipGetLastError());
     if (rc != W4A8_OK || pl.splits == 1) return rc;
-    return launch_gemv_combine(part, sx, M, N, pl.splits, Y, y_dtype, ldy, st);
+    return launch_gemv_combine(part, sx, grouped ? nullptr : step, zp, M, N, pl.splits, Y, y_dtype,
+                               ldy, st);
 }
 
-int launch_gemv_combine(const float *partial, const float *sx, int64_t M, int64_t N, int splits, void *Y,
-                        int y_dtype, int64_t ldy, hipStream_t st)
+int launch_gemv_combine(const float *partial, const float *sx, const float *int_step, ZeroPoint zp,
+                        int64_t M, int64_t N, int splits, void *Y, int y_dtype, int64_t ldy,
+                        hipStream_t st)
 {
     const int64_t outs = M * N;
     hipLaunchKernelGGL(gemv_combine_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st,
-                       partial, sx, (int)M, (int)N, splits, (uint16_t *)Y, y_dtype, ldy);
+                       partial, sx, int_step, int_step ? zp.zx : nullptr, zp.wsum, (int)M, (int)N,
+                       splits, (uint16_t *)Y, y_dtype, ldy);
     return hip_status(hipGetLastError());
 }
 

@@ -61,10 +61,16 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ 
 // ---- the tile kernel ------------------------------------------------------------------------
 // WM wave rows x 4 wave columns; a wave owns BM / WM token rows of 64 output channels.  With
 // WM = 2 every SIMD hosts two waves, so one wave's MFMAs cover the other's LDS and decode latency.
-template <int BM, int WM, bool GROUPED, bool ACC_OUT>
+// Token zero-points zx (asymmetric activations; codes and zx stored offset by -128): the exact
+// term zx * (sum of the weights) leaves the int32 accumulators before any floating-point step --
+// per group in the flush (GROUPED; its own instances, ASYM) or once in the epilogue (!GROUPED,
+// decided at run time by zx != null).
+template <int BM, int WM, bool GROUPED, bool ACC_OUT, bool ASYM>
 __global__ __launch_bounds__(WM * 256) void gemm_kernel(
-    const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ rs,
-    int M, const uint8_t *__restrict__ Wt, const float *__restrict__ step,
+    const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ zx,
+    const int32_t *__restrict__ wsum, const int32_t *__restrict__ tsum,
+    const int32_t *__restrict__ rs, int M,
+    const uint8_t *__restrict__ Wt, const float *__restrict__ step,
     const uint8_t *__restrict__ zero, int N, int K, int tiles_per_group, int ng,
     uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store,
     int32_t *__restrict__ acc_out, int grid_m, int grid_n, int kt_per_split,
@@ -79,6 +85,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, three groups deep
     __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 3 : 1][GROUPED ? GM_BN : 4];
     __shared__ int s_gz[GROUPED ? 3 : 1][GROUPED ? GM_BN : 4];
+    __shared__ __attribute__((aligned(16))) int s_gw[GROUPED && ASYM ? 3 : 1][GROUPED && ASYM ? GM_BN : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -191,20 +198,28 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     };
     // group parameters of channel nb0 + tid (threads 0..255), fetched one group ahead
     float gp_es = 0.f;
-    int gp_z = 0;
+    int gp_z = 0, gp_w = 0;
     auto fetch_group = [&](int g) {
         if (tid < GM_BN) {
             const int nn = nb0 + tid < N ? nb0 + tid : 0;
             gp_es = step[(int64_t)nn * ng + g] * 0.125f;
             gp_z = zero[(int64_t)nn * ng + g];
+            if (ASYM) gp_w = 4 * wsum[(int64_t)nn * ng + g];
         }
     };
     auto publish_group = [&](int g) {
         if (tid < GM_BN) {
             s_ges[g % 3][tid] = gp_es;
             s_gz[g % 3][tid] = gp_z;
+            if (ASYM) s_gw[g % 3][tid] = gp_w;
         }
     };
+    int nzx[MS];   // minus the zero-point of this lane's token in each sub-tile (GROUPED && ASYM)
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) {
+        const int m = m0 + wr0 + ms * 32 + r32;
+        nzx[ms] = (GROUPED && ASYM && m < M) ? -zx[m] : 0;
+    }
 
     // Accumulator layout (32x32): lane holds token m = 32 ms + r32 and the 16 output channels
     // n = n0 + 32 ns + 8 (r / 4) + 4 kh + (r % 4), r = 0..15.
@@ -215,13 +230,16 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
             for (int b = 0; b < 4; ++b) {
                 const int nl = wn * (GM_NS * 32) + ns * 32 + 8 * b + 4 * kh;
                 const v4f es = *reinterpret_cast<const v4f *>(&s_ges[g % 3][nl]);
+                v4i gw = {0, 0, 0, 0};   // 4 * (sum of the group's weights), |.| < 2^23
+                if (ASYM) gw = *reinterpret_cast<const v4i *>(&s_gw[g % 3][nl]);
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
                     const int m = m0 + wr0 + ms * 32 + r32;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int v = acc[ms][ns][4 * b + r];
-                        y[GROUPED ? ms : 0][ns][4 * b + r] += es[r] * (float)v;
+                        const int vz = ASYM ? v + __mul24(nzx[ms], gw[r]) : v;
+                        y[GROUPED ? ms : 0][ns][4 * b + r] += es[r] * (float)vz;
                         if (ACC_OUT && m < M) {
                             const int nn = nb0 + nl + r;
                             if (nn < N) acc_out[((int64_t)m * N + nn) * ng + g] = v >> 2;
@@ -358,6 +376,23 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
         }
         __syncthreads();
     }
+    // per-channel weights with token zero-points: sums of each channel's weights over this
+    // workgroup's K-range (all of K: the group sum; a K-split: its k-tiles added up)
+    const bool asym = !GROUPED && zx != nullptr;
+    int *s_w = reinterpret_cast<int *>(&lds[0][GM_BN * 8]);
+    if (asym) {
+        if (tid < GM_BN) {
+            const int nn = nb0 + tid < N ? nb0 + tid : 0;
+            int w = 0;
+            if (partial == nullptr) {
+                w = wsum[nn];
+            } else {
+                for (int kt = 0; kt < KTl; ++kt) w += tsum[(int64_t)nn * KT + kt0 + kt];
+            }
+            s_w[tid] = w;
+        }
+        __syncthreads();
+    }
 
     // epilogue: Y[m, n..n+3] = cast(sx[m] * y)
 #pragma unroll
@@ -365,6 +400,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
         const int m = m0 + wr0 + ms * 32 + r32;
         if (m >= M) continue;
         const float sxm = sx[m];
+        const int zx4m = asym ? 4 * zx[m] : 0;
         const int rsm = GROUPED ? 0 : rs[(int64_t)split * M + m];
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
@@ -383,11 +419,12 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                         yv = y[GROUPED ? ms : 0][ns][4 * b + r];
                     } else {
                         // remove the decode bias: 4 sum Xq d = acc - 4 beta * rowsum (exact)
-                        const int v = acc[ms][ns][4 * b + r] - s_bq[nl + r] * rsm;
+                        int v = acc[ms][ns][4 * b + r] - s_bq[nl + r] * rsm;
                         if (ACC_OUT) {
                             if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
                             else acc_out[(int64_t)m * N + nn + r] = v >> 2;
                         }
+                        if (asym) v -= zx4m * s_w[nl + r];   // the accumulator hook keeps the raw sum
                         yv = s_es[nl + r] * (float)v;
                     }
                     part[r] = yv;
@@ -411,11 +448,11 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     }
 }
 
-template <int BM, int WM, bool GROUPED, bool ACC_OUT>
-static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, const int32_t *rs,
-                          int64_t M, const uint8_t *Wt, const float *step, const uint8_t *zero,
-                          int64_t N, int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy,
-                          int32_t *acc_out, float *partial, hipStream_t st)
+template <int BM, int WM, bool GROUPED, bool ACC_OUT, bool ASYM>
+static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
+                          const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
+                          const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
+                          int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
 {
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
@@ -424,31 +461,37 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
     if (!attr_set) {
         if (lds_bytes > 48 * 1024 &&
-            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, GROUPED, ACC_OUT>,
+            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, GROUPED, ACC_OUT, ASYM>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return W4A8_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED, ACC_OUT>),
+    hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED, ACC_OUT, ASYM>),
                        dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * 256), lds_bytes, st,
-                       Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K, (int)(G / TILE_K),
-                       (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store, acc_out, grid_m, grid_n,
-                       pl.kt_per_split, pl.splits > 1 ? partial : nullptr);
+                       Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,
+                       (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
+                       acc_out, grid_m, grid_n, pl.kt_per_split, pl.splits > 1 ? partial : nullptr);
     return hip_status(hipGetLastError());
 }
 
 template <int BM, int WM, bool GROUPED>
-static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, const int32_t *rs,
-                         int64_t M, const uint8_t *Wt, const float *step, const uint8_t *zero,
-                         int64_t N, int64_t K, int64_t G, void *Y, int y_dtype, int64_t ldy,
-                         int32_t *acc_out, float *partial, hipStream_t st)
+static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
+                         const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
+                         const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
+                         int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
 {
-    // the accumulator test hook is a separate instance so that the fast path carries none of it
-    if (acc_out)
-        return launch_gemm_t2<BM, WM, GROUPED, true>(pl, Xq, sx, rs, M, Wt, step, zero, N, K, G, Y,
-                                                     y_dtype, ldy, acc_out, partial, st);
-    return launch_gemm_t2<BM, WM, GROUPED, false>(pl, Xq, sx, rs, M, Wt, step, zero, N, K, G, Y,
-                                                  y_dtype, ldy, acc_out, partial, st);
+    // The accumulator test hook is a separate instance so that the fast path carries none of it;
+    // so is the per-group zero-point term of group-wise weights.
+#define W4A8_GM2(AO_, AS_)                                                                       \
+    return launch_gemm_t2<BM, WM, GROUPED, AO_, AS_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
+                                                     G, Y, y_dtype, ldy, acc_out, partial, st)
+    if (GROUPED && zp.zx != nullptr) {
+        if (acc_out) W4A8_GM2(true, GROUPED);
+        W4A8_GM2(false, GROUPED);
+    }
+    if (acc_out) W4A8_GM2(true, false);
+    W4A8_GM2(false, false);
+#undef W4A8_GM2
 }
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
@@ -488,9 +531,10 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
     return pl;
 }
 
-int launch_gemm(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const uint8_t *Wt,
-                const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
-                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
+int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, int64_t M,
+                const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N, int64_t K,
+                int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, float *partial,
+                hipStream_t st)
 {
     const bool grouped = G != K;
     if ((M + 63) / 64 * ((N + 255) / 256) * 64 > 0x7fffffLL || M * K > 0x7fffffffLL)
@@ -504,7 +548,7 @@ int launch_gemm(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const
     }
     int rc;
 #define W4A8_GM(BM_, WM_, GR_)                                                                     \
-    rc = launch_gemm_t<BM_, WM_, GR_>(pl, Xq, sx, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
+    rc = launch_gemm_t<BM_, WM_, GR_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
                                       acc_out, partial, st)
     if (grouped) {
         if (pl.bm == 64) W4A8_GM(64, 1, true);
@@ -516,7 +560,8 @@ int launch_gemm(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const
     }
 #undef W4A8_GM
     if (rc != W4A8_OK || pl.splits == 1) return rc;
-    return launch_gemv_combine(partial, sx, M, N, pl.splits, Y, y_dtype, ldy, st);
+    return launch_gemv_combine(partial, sx, nullptr, ZeroPoint{nullptr, nullptr, nullptr}, M, N,
+                               pl.splits, Y, y_dtype, ldy, st);
 }
 
 }  // namespace w4a8

@@ -115,6 +115,21 @@ __global__ __launch_bounds__(PK_THREADS) void fill_i32_kernel(int32_t *__restric
         p[i] = v;
 }
 
+// acc[m,n,g] -= zx[m] * wsum[n,g]: turns accumulators of the stored codes into those of
+// (code - zero-point), exactly  (sum_k (q - zx) d = sum_k q d - zx sum_k d)
+__global__ __launch_bounds__(PK_THREADS) void acc_zero_point_kernel(int32_t *__restrict__ acc,
+                                                                   const int32_t *__restrict__ zx,
+                                                                   const int32_t *__restrict__ wsum,
+                                                                   int64_t M, int64_t per_token)
+{
+    const int64_t n = M * per_token;
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const int64_t m = i / per_token;
+        acc[i] -= zx[m] * wsum[i - m * per_token];
+    }
+}
+
 static unsigned grid_for(int64_t items)
 {
     int64_t b = (items + PK_THREADS - 1) / PK_THREADS;
@@ -166,6 +181,15 @@ int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st)
 {
     if (n == 0) return W4A8_OK;
     hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(n)), dim3(PK_THREADS), 0, st, p, n, v);
+    return hip_status(hipGetLastError());
+}
+
+int launch_acc_zero_point(int32_t *acc, const int32_t *zx, const int32_t *wsum, int64_t M,
+                          int64_t per_token, hipStream_t st)
+{
+    if (M * per_token == 0) return W4A8_OK;
+    hipLaunchKernelGGL(acc_zero_point_kernel, dim3(grid_for(M * per_token)), dim3(PK_THREADS), 0, st,
+                       acc, zx, wsum, M, per_token);
     return hip_status(hipGetLastError());
 }
 

@@ -138,8 +138,14 @@ __device__ __forceinline__ void decode_word_signed(uint32_t p, const SignedLut &
 }
 
 // Host-side launchers (defined in the .hip files, called from the C ABI in api.hip).
+// zx == nullptr: symmetric absmax; else asymmetric min-max, token zero-points (minus 128) to zx
 int launch_act_quant(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const float *s,
-                     int8_t *Xq, float *sx, hipStream_t st);
+                     int8_t *Xq, float *sx, int32_t *zx, hipStream_t st);
+// wsum[N, K/T]: sums of the weights in half steps over blocks of T columns (T divides G)
+int launch_weight_sums(const uint8_t *codes, const uint8_t *zero, int64_t N, int64_t K, int64_t G,
+                       int64_t T, int32_t *wsum, hipStream_t st);
+int launch_acc_zero_point(int32_t *acc, const int32_t *zx, const int32_t *wsum, int64_t M,
+                          int64_t per_token, hipStream_t st);
 int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
                         const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
                         uint8_t *zero, hipStream_t st);
@@ -162,11 +168,19 @@ struct GemvPlan {
     size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1, else 0
 };
 GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G);
-int launch_gemv(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt, const float *step,
-                const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
-int launch_gemv_combine(const float *partial, const float *sx, int64_t M, int64_t N, int splits, void *Y,
-                        int y_dtype, int64_t ldy, hipStream_t st);
+// Asymmetric activations: zx = token zero-points, wsum = weight sums per group [N, K/G],
+// tsum = weight sums per 128 columns [N, K/128]; all three null for the symmetric form.
+struct ZeroPoint {
+    const int32_t *zx, *wsum, *tsum;
+};
+int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
+                const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
+                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
+// Y = cast(sx * sum over splits of partial).  int_step != null: the partials are int32
+// accumulators of a per-channel launch, scaled by int_step[n] / 8 after the exact zero-point term.
+int launch_gemv_combine(const float *partial, const float *sx, const float *int_step, ZeroPoint zp,
+                        int64_t M, int64_t N, int splits, void *Y, int y_dtype, int64_t ldy,
+                        hipStream_t st);
 // Launch shape of the prefill GEMM (also sizes its workspace).
 struct GemmPlan {
     int bm;                // token rows per workgroup tile
@@ -176,9 +190,10 @@ struct GemmPlan {
     size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1
 };
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G);
-int launch_gemm(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const uint8_t *Wt,
-                const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
-                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
+int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, int64_t M,
+                const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N, int64_t K,
+                int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, float *partial,
+                hipStream_t st);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
 

@@ -171,4 +171,37 @@ int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_
     }
 }
 
+// ---- sums of the quantized weights (needed to take a token zero-point out of the product) ------
+// wsum[n,b] = sum_{k in block b} d[n,k], d in half steps (Eq. 5, second half), over blocks of T
+// consecutive input channels (T divides the group size G): one wave per (row, block).
+__global__ __launch_bounds__(256) void weight_block_sums_kernel(const uint8_t *__restrict__ codes,
+                                                                const uint8_t *__restrict__ zero,
+                                                                int64_t N, int64_t K, int64_t G,
+                                                                int64_t T, int32_t *__restrict__ wsum)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t ng = K / G, nb = K / T;
+    const int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // (row, block)
+    if (seg >= N * nb) return;
+    const int64_t n = seg / nb, b = seg - n * nb;
+    const int z = zero[n * ng + (b * T) / G];
+    const uint8_t *c = codes + n * K + b * T;
+    int sum = 0;
+    for (int64_t k = lane; k < T; k += WAVE) {
+        const int code = c[k] & 15;
+        sum += code <= DINT4_P ? 2 * (code - z) : (code == 14 ? 1 : -1);
+    }
+    sum = wave_sum_i32(sum);
+    if (lane == 0) wsum[seg] = sum;
+}
+
+int launch_weight_sums(const uint8_t *codes, const uint8_t *zero, int64_t N, int64_t K, int64_t G,
+                       int64_t T, int32_t *wsum, hipStream_t st)
+{
+    const int64_t segs = N * (K / T);
+    hipLaunchKernelGGL(weight_block_sums_kernel, dim3((unsigned)((segs + 3) / 4)), dim3(256), 0, st,
+                       codes, zero, N, K, G, T, wsum);
+    return hip_status(hipGetLastError());
+}
+
 }  // namespace w4a8

@@ -102,6 +102,21 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert gemm(M=64, ws=P, wsb=8) == b.ERR_WORKSPACE
     assert gemm(layout=0) == b.ERR_WORKSPACE         # canonical weights are re-tiled into workspace
     assert gemm(M=0) == b.OK
+    # asymmetric activations
+    assert c.quantize_act_int8_asym(P, b.F16, 4, 128, 128, Z, P, P, Z, Z) == b.ERR_NULL   # zx missing
+    assert c.quantize_act_int8_asym(P, b.F16, 4, 128, 64, Z, P, P, P, Z) == b.ERR_SHAPE
+    assert c.quantize_act_int8_asym(P, 5, 4, 128, 128, Z, P, P, P, Z) == b.ERR_DTYPE
+    assert c.dint4_weight_sums(P, P, 16, 128, 48, P, P, Z) == b.ERR_SHAPE
+    assert c.dint4_weight_sums(P, P, 16, 192, 0, P, P, Z) == b.ERR_SHAPE     # tile sums need K % 128
+    assert c.dint4_weight_sums(P, P, 16, 128, 0, Z, P, Z) == b.ERR_NULL
+
+    def gemm_asym(zx=P, wsum=P, tsum=P, N=16):
+        return c.w4a8_gemm_asym(P, P, zx, 4, P, 1, P, P, wsum, tsum, N, 128, 0, P, b.F16, 16, Z,
+                                Z, 0, Z)
+    assert gemm_asym(zx=Z) == b.ERR_NULL
+    assert gemm_asym(wsum=Z) == b.ERR_NULL
+    assert gemm_asym(tsum=Z) == b.ERR_NULL
+    assert gemm_asym(N=24) == b.ERR_SHAPE
 
 
 def test_product_path_has_no_cpu_fallback(lib, tmp_path):

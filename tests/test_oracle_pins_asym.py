@@ -161,16 +161,22 @@ def test_weight_sums_closed_form(oracle):
     N, K, G = 12, 256, 64
     codes = rng.integers(0, 16, (N, K)).astype(np.uint8)
     zero = rng.integers(0, 14, (N, K // G)).astype(np.uint8)
-    step = rng.uniform(1e-3, 0.1, (N, K // G)).astype(np.float32)
-    wsum, c = oracle.weight_sums(oracle.pack_dint4(codes), zero, step, G)
+    packed = oracle.pack_dint4(codes)
     d = half_steps(codes.reshape(N, K // G, G), zero.reshape(N, K // G, 1))
-    assert np.array_equal(wsum, d.sum(2))
-    c64 = (0.5 * step.astype(np.float64) * d.sum(2)).sum(1)
-    np.testing.assert_allclose(c, c64, rtol=1e-5, atol=1e-7)
+    assert np.array_equal(oracle.weight_sums(packed, zero, G), d.sum(2))
+    # finer blocks inside a group use the group's zero-point and add up to the group sums
+    fine = oracle.weight_sums(packed, zero, G, 16)
+    assert np.array_equal(fine, d.reshape(N, K // 16, 16).sum(2))
+    assert np.array_equal(fine.reshape(N, K // G, G // 16).sum(2), d.sum(2))
     # all codes equal to the zero-point: every sum is zero
     codes0 = np.repeat(zero, G, axis=1)
-    w0, c0 = oracle.weight_sums(oracle.pack_dint4(codes0), zero, step, G)
-    assert not w0.any() and not c0.any()
+    assert not oracle.weight_sums(oracle.pack_dint4(codes0), zero, G).any()
+    # the two denormal codes are +1 and -1 half steps whatever the zero-point
+    c14 = np.full((1, 32), 14, np.uint8); c15 = np.full((1, 32), 15, np.uint8)
+    for z in (0, 7, 13):
+        zz = np.array([[z]], np.uint8)
+        assert oracle.weight_sums(oracle.pack_dint4(c14), zz, 0)[0, 0] == 32
+        assert oracle.weight_sums(oracle.pack_dint4(c15), zz, 0)[0, 0] == -32
 
 
 def test_brute_force_tiny_asym(oracle):
