@@ -220,8 +220,9 @@ def main():
                 "bytes_per_launch": per_copy, "avg_launch_us": round(kern_ms * 1e3, 3)}
 
     # ------------------------------------------------------------------ larger decode shapes (side figures)
-    def time_gemm(Mq, Nq, Kq, Gq, reps, ring_bytes=600 << 20):
-        """Back-to-back w4a8_gemm launches over a ring of random packed weights (timing only)."""
+    def time_gemm(Mq, Nq, Kq, Gq, reps, ring_bytes=600 << 20, asym=False):
+        """Back-to-back w4a8_gemm (or w4a8_gemm_asym) launches over a ring of random packed weights
+        (timing only)."""
         g = torch.Generator(device=dev)
         g.manual_seed(20231105)
         Gs = Kq if Gq == 0 else Gq
@@ -236,14 +237,22 @@ def main():
         yq = torch.empty((Mq, Nq), dtype=torch.float16, device=dev)
         wsb = w.gemm_workspace_bytes(Mq, Nq, Kq, Gq)
         wsq = torch.empty((max(1, wsb),), dtype=torch.uint8, device=dev)
+        fn = lib.w4a8_gemm
         argsq = [(P(xq), P(sxq), Mq, P(wp), w.LAYOUT_TILED, P(stq), P(zq), Nq, Kq, Gq, P(yq), w.F16, Nq,
                   None, P(wsq), wsb, st) for wp in wps]
+        if asym:
+            fn = lib.w4a8_gemm_asym
+            zxq = torch.randint(-128, 128, (Mq,), dtype=torch.int32, device=dev, generator=g)
+            wsq_ = torch.randint(-3000, 3000, (Nq, Kq // Gs), dtype=torch.int32, device=dev, generator=g)
+            tsq_ = torch.randint(-3000, 3000, (Nq, Kq // 128), dtype=torch.int32, device=dev, generator=g)
+            argsq = [(P(xq), P(sxq), P(zxq), Mq, P(wp), w.LAYOUT_TILED, P(stq), P(zq), P(wsq_), P(tsq_),
+                      Nq, Kq, Gq, P(yq), w.F16, Nq, None, P(wsq), wsb, st) for wp in wps]
         for i in range(max(3, reps // 10)):
-            assert lib.w4a8_gemm(*argsq[i % nring]) == 0
+            assert fn(*argsq[i % nring]) == 0
         torch.cuda.synchronize()
         e0.record(stream)
         for i in range(reps):
-            lib.w4a8_gemm(*argsq[i % nring])
+            fn(*argsq[i % nring])
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps, per
@@ -268,6 +277,21 @@ def main():
             prefill.append({"workload": f"{name} M={Mp} K={Kp} N={Np} G={Gp or Kp}", "ms": round(ms, 4),
                             "TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
 
+    # ------------------------------------------------------------------ asymmetric activations (side)
+    asym_side = []
+    if not args.no_prefill:
+        for (name, Ma, Ka, Na, Ga, reps) in [("C2 decode", 16, 4096, 4096, 128, 400),
+                                             ("C4 decode", 16, 5120, 13824, 128, 400),
+                                             ("C3_up prefill", 2048, 4096, 11008, 0, 20),
+                                             ("C4 prefill", 2048, 5120, 13824, 128, 20)]:
+            ms, per = time_gemm(Ma, Na, Ka, Ga, reps, ring_bytes=(600 << 20) if Ma <= 16 else 0, asym=True)
+            row = {"workload": f"{name} M={Ma} K={Ka} N={Na} G={Ga or Ka}", "us": round(ms * 1e3, 3)}
+            if Ma <= 16:
+                row["GBps"] = round(per / ms / 1e6, 1)
+            else:
+                row["TOPS"] = round(2.0 * Ma * Na * Ka / (ms * 1e-3) / 1e12, 1)
+            asym_side.append(row)
+
     out = {
         "metric": METRIC, "value": round(weight_gbs, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
@@ -282,6 +306,9 @@ def main():
                     "ms": round(offline_ms, 4),
                     "GBps": round((N * K * 2 + N * K + N * K + N * K // 2) / (offline_ms * 1e-3) / 1e9, 1)},
         "decode_other_shapes": decode_side, "prefill": prefill,
+        "asymmetric_activations": {"what": "w4a8_gemm_asym (token zero-point taken out of the int32 "
+                                           "accumulators), same shapes and protocol as the lists above",
+                                   "shapes": asym_side},
     }
     print(json.dumps(out), flush=True)
 
