@@ -244,7 +244,6 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                             const int nn = nb0 + nl + r;
                             if (nn < N) acc_out[((int64_t)m * N + nn) * ng + g] = v >> 2;
                         }
-                        acc[ms][ns][4 * b + r] = 0;
                     }
                 }
             }
@@ -338,13 +337,24 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
                 read_a(nxt, 0, af[0]);
                 decode_step(pn, 0, w[0]);
             }
+            // D[i][j]: rows i = output channels (weights operand), columns j = tokens.  The first
+            // k-step of a group starts from a zero operand instead of cleared accumulators.
+            if (GROUPED && s == 0 && group_start) {
+                const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int ms = 0; ms < MS; ++ms)
+                for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                for (int ns = 0; ns < GM_NS; ++ns)
-                    // D[i][j]: rows i = output channels (weights operand), columns j = tokens
-                    acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
-                                                                        acc[ms][ns], 0, 0, 0);
+                    for (int ns = 0; ns < GM_NS; ++ns)
+                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                            z16, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                    for (int ns = 0; ns < GM_NS; ++ns)
+                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                            acc[ms][ns], 0, 0, 0);
+            }
             // issue order for this step: the LDS reads of the next step first, then the decode
             // arithmetic spread evenly between the MFMAs
             __builtin_amdgcn_sched_group_barrier(0x100, MS, 0);
