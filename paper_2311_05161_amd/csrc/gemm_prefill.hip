@@ -30,7 +30,6 @@ namespace w4a8 {
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int GM_BN = 256;  // output channels per workgroup
-constexpr int GM_NS = 2;    // 32-channel sub-tiles per wave
 constexpr int GM_OOB = 0x7fff0000;
 
 // ---- per-token row-sums of Xq over each K-range (bias removal of the per-channel path) ----------
@@ -59,14 +58,17 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ 
 }
 
 // ---- the tile kernel ------------------------------------------------------------------------
-// WM wave rows x 4 wave columns; a wave owns BM / WM token rows of 64 output channels.  With
-// WM = 2 every SIMD hosts two waves, so one wave's MFMAs cover the other's LDS and decode latency.
+// WM wave rows x WN wave columns (8 waves for BM >= 128: every SIMD hosts two, so one wave's
+// MFMAs cover the other's LDS and decode latency); a wave owns BM / WM token rows of 256 / WN output
+// channels.  WN = 4 (64 channels per wave) suits the per-channel kernel; group-wise weights take
+// WN = 8, WM = 1 (128 tokens x 32 channels per wave): every decoded weight then feeds twice as
+// many MFMAs, and instruction issue -- decode plus the per-group rescale -- is what bounds them.
 // Token zero-points zx (asymmetric activations; codes and zx stored offset by -128): the exact
 // term zx * (sum of the weights) leaves the int32 accumulators before any floating-point step --
 // per group in the flush (GROUPED; its own instances, ASYM) or once in the epilogue (!GROUPED,
 // decided at run time by zx != null).
-template <int BM, int WM, bool GROUPED, bool ACC_OUT, bool ASYM>
-__global__ __launch_bounds__(WM * 256) void gemm_kernel(
+template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ zx,
     const int32_t *__restrict__ wsum, const int32_t *__restrict__ tsum,
     const int32_t *__restrict__ rs, int M,
@@ -76,16 +78,17 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     int32_t *__restrict__ acc_out, int grid_m, int grid_n, int kt_per_split,
     float *__restrict__ partial)
 {
-    constexpr int GM_THREADS = WM * 256;
+    constexpr int GM_THREADS = WM * WN * 64;
+    constexpr int GM_NS = GM_BN / (WN * 32);       // 32-channel sub-tiles per wave
     constexpr int WROWS = BM / WM;                 // token rows per wave
     constexpr int MS = WROWS / 32;                 // 32-token sub-tiles per wave
     constexpr int LD_ITERS = BM * 8 / GM_THREADS;  // 16-byte chunks of the A tile per thread
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     uint8_t(*lds)[BM * TILE_K] = reinterpret_cast<uint8_t(*)[BM * TILE_K]>(lds_raw);   // [3][BM * 128]
-    // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, three groups deep
-    __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 3 : 1][GROUPED ? GM_BN : 4];
-    __shared__ int s_gz[GROUPED ? 3 : 1][GROUPED ? GM_BN : 4];
-    __shared__ __attribute__((aligned(16))) int s_gw[GROUPED && ASYM ? 3 : 1][GROUPED && ASYM ? GM_BN : 4];
+    // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, a ring of four groups
+    __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 4 : 1][GROUPED ? GM_BN : 4];
+    __shared__ int s_gz[GROUPED ? 4 : 1][GROUPED ? GM_BN : 4];
+    __shared__ __attribute__((aligned(16))) int s_gw[GROUPED && ASYM ? 4 : 1][GROUPED && ASYM ? GM_BN : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -110,8 +113,8 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     const int bn = bid / grid_m;
     const int m0 = bm * BM;
     const int nb0 = bn * GM_BN;                        // first output channel of the workgroup
-    const int wn = wave & 3;                           // wave column
-    const int wr0 = (wave >> 2) * WROWS;               // first token row of this wave within the tile
+    const int wn = wave % WN;                          // wave column
+    const int wr0 = (wave / WN) * WROWS;               // first token row of this wave within the tile
     const int n0 = nb0 + wn * (GM_NS * 32);            // first output channel of this wave
 
     __amdgpu_buffer_rsrc_t rw =
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
             if (GROUPED) {
-                slut[ns] = make_signed_lut(s_gz[g % 3][wn * (GM_NS * 32) + ns * 32 + r32]);
+                slut[ns] = make_signed_lut(s_gz[g & 3][wn * (GM_NS * 32) + ns * 32 + r32]);
             } else {
                 const int nn = (n0 + ns * 32 + r32 < N) ? n0 + ns * 32 + r32 : 0;
                 lut[ns] = make_decode_lut(zero[(int64_t)nn * ng]);
@@ -209,9 +212,9 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     };
     auto publish_group = [&](int g) {
         if (tid < GM_BN) {
-            s_ges[g % 3][tid] = gp_es;
-            s_gz[g % 3][tid] = gp_z;
-            if (ASYM) s_gw[g % 3][tid] = gp_w;
+            s_ges[g & 3][tid] = gp_es;
+            s_gz[g & 3][tid] = gp_z;
+            if (ASYM) s_gw[g & 3][tid] = gp_w;
         }
     };
     int nzx[MS];   // minus the zero-point of this lane's token in each sub-tile (GROUPED && ASYM)
@@ -229,9 +232,9 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int nl = wn * (GM_NS * 32) + ns * 32 + 8 * b + 4 * kh;
-                const v4f es = *reinterpret_cast<const v4f *>(&s_ges[g % 3][nl]);
+                const v4f es = *reinterpret_cast<const v4f *>(&s_ges[g & 3][nl]);
                 v4i gw = {0, 0, 0, 0};   // 4 * (sum of the group's weights), |.| < 2^23
-                if (ASYM) gw = *reinterpret_cast<const v4i *>(&s_gw[g % 3][nl]);
+                if (ASYM) gw = *reinterpret_cast<const v4i *>(&s_gw[g & 3][nl]);
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
                     const int m = m0 + wr0 + ms * 32 + r32;
@@ -310,68 +313,74 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     read_a(0, 0, af[0]);
     decode_step(p, 0, w[0]);
 
+    // Outer loop over the quantization groups of this K-range (one "group" spanning all of it for
+    // per-channel weights), inner loop over a group's k-tiles; the group is rescaled into the
+    // fp32 sums behind its last k-tile.  Ring of group parameters: group g + 2 is published while
+    // group g starts (its slot was last read for group g - 2, at least one barrier ago) and read
+    // from the end of group g + 1 on (at least one barrier later).
     int cur = 0;   // kt % 3
-    for (int kt = 0; kt < KTl; ++kt) {
-        const int nxt = cur == 2 ? 0 : cur + 1;
-        const int nx2 = nxt == 2 ? 0 : nxt + 1;
-        store_a(nx2);                     // tile kt + 2 (loaded one iteration ago)
-        load_a(min(kt + 3, ktl));
-        const bool group_start = GROUPED && kt % tiles_per_group == 0;
-        const bool group_end = GROUPED && (kt + 1) % tiles_per_group == 0;
-        const int g_cur = GROUPED ? g0 + kt / tiles_per_group : 0;
-        if (group_start) {
-            if (g_cur + 2 < g_end) publish_group(g_cur + 2);
-            if (g_cur + 3 < g_end) fetch_group(g_cur + 3);
+    int kt = 0;
+    const int tiles_in_group = GROUPED ? tiles_per_group : KTl;
+    for (int g = g0; g < g_end; ++g) {
+        if (GROUPED) {
+            if (g + 2 < g_end) publish_group(g + 2);
+            if (g + 3 < g_end) fetch_group(g + 3);
         }
+        for (int t = 0; t < tiles_in_group; ++t, ++kt) {
+            const int nxt = cur == 2 ? 0 : cur + 1;
+            const int nx2 = nxt == 2 ? 0 : nxt + 1;
+            store_a(nx2);                     // tile kt + 2 (loaded one iteration ago)
+            load_a(min(kt + 3, ktl));
 
-        // Software pipeline over the four 32-column k-steps: fragments and decoded weights of the
-        // next step (for the last step: of the next tile's first step) are produced while the
-        // MFMAs of the current step run.
+            // Software pipeline over the four 32-column k-steps: fragments and decoded weights of
+            // the next step (for the last step: of the next tile's first step) are produced while
+            // the MFMAs of the current step run.
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (s < 3) {
-                read_a(cur, s + 1, af[(s + 1) & 1]);
-                decode_step(p, s + 1, w[(s + 1) & 1]);
-            } else {
-                if (group_end && g_cur + 1 < g_end) load_luts(g_cur + 1);
-                read_a(nxt, 0, af[0]);
-                decode_step(pn, 0, w[0]);
+            for (int s = 0; s < 4; ++s) {
+                if (s < 3) {
+                    read_a(cur, s + 1, af[(s + 1) & 1]);
+                    decode_step(p, s + 1, w[(s + 1) & 1]);
+                } else {
+                    if (GROUPED && t == tiles_in_group - 1 && g + 1 < g_end) load_luts(g + 1);
+                    read_a(nxt, 0, af[0]);
+                    decode_step(pn, 0, w[0]);
+                }
+                // D[i][j]: rows i = output channels (weights operand), columns j = tokens.  The
+                // first k-step of a group starts from a zero operand instead of cleared accumulators.
+                if (GROUPED && s == 0 && t == 0) {
+                    const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int ns = 0; ns < GM_NS; ++ns)
+                            acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                                z16, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int ns = 0; ns < GM_NS; ++ns)
+                            acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                                acc[ms][ns], 0, 0, 0);
+                }
+                // issue order for this step: the LDS reads of the next step first, then the decode
+                // arithmetic spread evenly between the MFMAs
+                __builtin_amdgcn_sched_group_barrier(0x100, MS, 0);
+#pragma unroll
+                for (int i = 0; i < MS * GM_NS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, GROUPED ? 6 : 4, 0);
+                }
             }
-            // D[i][j]: rows i = output channels (weights operand), columns j = tokens.  The first
-            // k-step of a group starts from a zero operand instead of cleared accumulators.
-            if (GROUPED && s == 0 && group_start) {
-                const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int ms = 0; ms < MS; ++ms)
+            for (int ns = 0; ns < GM_NS; ++ns)
 #pragma unroll
-                    for (int ns = 0; ns < GM_NS; ++ns)
-                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
-                                                                            z16, 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                    for (int ns = 0; ns < GM_NS; ++ns)
-                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
-                                                                            acc[ms][ns], 0, 0, 0);
-            }
-            // issue order for this step: the LDS reads of the next step first, then the decode
-            // arithmetic spread evenly between the MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x100, MS, 0);
-#pragma unroll
-            for (int i = 0; i < MS * GM_NS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, GROUPED ? 6 : 4, 0);
-            }
+                for (int sp = 0; sp < 2; ++sp) p[ns][sp] = pn[ns][sp];
+            load_b(min(kt + 2, ktl), pn);
+            cur = nxt;
+            __syncthreads();
         }
-        if (group_end) flush_group(g_cur);
-#pragma unroll
-        for (int ns = 0; ns < GM_NS; ++ns)
-#pragma unroll
-            for (int sp = 0; sp < 2; ++sp) p[ns][sp] = pn[ns][sp];
-        load_b(min(kt + 2, ktl), pn);
-        cur = nxt;
-        __syncthreads();
+        if (GROUPED) flush_group(g);
     }
 
     // epilogue parameters of the workgroup's 256 channels, in the (now free) staging buffer
@@ -458,7 +467,7 @@ __global__ __launch_bounds__(WM * 256) void gemm_kernel(
     }
 }
 
-template <int BM, int WM, bool GROUPED, bool ACC_OUT, bool ASYM>
+template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM>
 static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                           const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                           const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
@@ -471,20 +480,20 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
     if (!attr_set) {
         if (lds_bytes > 48 * 1024 &&
-            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, GROUPED, ACC_OUT, ASYM>,
+            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return W4A8_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, WM, GROUPED, ACC_OUT, ASYM>),
-                       dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * 256), lds_bytes, st,
+    hipLaunchKernelGGL((gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM>),
+                       dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * WN * 64), lds_bytes, st,
                        Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,
                        (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
                        acc_out, grid_m, grid_n, pl.kt_per_split, pl.splits > 1 ? partial : nullptr);
     return hip_status(hipGetLastError());
 }
 
-template <int BM, int WM, bool GROUPED>
+template <int BM, int WM, int WN, bool GROUPED>
 static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                          const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                          const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
@@ -493,7 +502,7 @@ static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, 
     // The accumulator test hook is a separate instance so that the fast path carries none of it;
     // so is the per-group zero-point term of group-wise weights.
 #define W4A8_GM2(AO_, AS_)                                                                       \
-    return launch_gemm_t2<BM, WM, GROUPED, AO_, AS_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
+    return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
                                                      G, Y, y_dtype, ldy, acc_out, partial, st)
     if (GROUPED && zp.zx != nullptr) {
         if (acc_out) W4A8_GM2(true, GROUPED);
@@ -557,16 +566,16 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
         if (hipGetLastError() != hipSuccess) return W4A8_ERR_HIP;
     }
     int rc;
-#define W4A8_GM(BM_, WM_, GR_)                                                                     \
-    rc = launch_gemm_t<BM_, WM_, GR_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
+#define W4A8_GM(BM_, WM_, WN_, GR_)                                                                \
+    rc = launch_gemm_t<BM_, WM_, WN_, GR_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
                                       acc_out, partial, st)
     if (grouped) {
-        if (pl.bm == 64) W4A8_GM(64, 1, true);
-        else W4A8_GM(128, 2, true);
+        if (pl.bm == 64) W4A8_GM(64, 1, 4, true);
+        else W4A8_GM(128, 1, 8, true);
     } else {
-        if (pl.bm == 64) W4A8_GM(64, 1, false);
-        else if (pl.bm == 128) W4A8_GM(128, 2, false);
-        else W4A8_GM(256, 2, false);
+        if (pl.bm == 64) W4A8_GM(64, 1, 4, false);
+        else if (pl.bm == 128) W4A8_GM(128, 2, 4, false);
+        else W4A8_GM(256, 2, 4, false);
     }
 #undef W4A8_GM
     if (rc != W4A8_OK || pl.splits == 1) return rc;
