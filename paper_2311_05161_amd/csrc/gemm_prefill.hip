@@ -574,7 +574,7 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
         else W4A8_GM(128, 1, 8, true);
     } else {
         if (pl.bm == 64) W4A8_GM(64, 1, 4, false);
-        else if (pl.bm == 128) W4A8_GM(128, 2, 4, false);
+        else if (pl.bm == 128) W4A8_GM(128, 1, 8, false);
         else W4A8_GM(256, 2, 4, false);
     }
 #undef W4A8_GM
