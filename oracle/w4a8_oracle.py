@@ -22,7 +22,7 @@ __all__ = [
     "unpack_dint4", "decode_dint4", "dequant_dint4", "int_gemm", "int_gemm_sampled",
     "dequant_epilogue", "cast_output", "linear_w4a8",
     "quantize_act_uint8_asym", "int_gemm_asym", "int_gemm_asym_sampled", "weight_sums",
-    "linear_w4a8_asym",
+    "linear_w4a8_asym", "quantize_value_dint4", "attention_value_w4a8",
 ]
 
 
@@ -297,3 +297,50 @@ def linear_w4a8_asym(X, W, s=None, group_size=0):
     wsum = weight_sums(packed, zero, group_size)
     return dict(Q=Q, sx=sx, zx=zx, codes=codes, step=step, zero=zero, packed=packed, acc=acc,
                 wsum=wsum, Y32=y32, Y64=y64)
+
+
+# ---- 4-bit Value cache: attention probabilities times Value (Sec. 5.1, App. A.1) ----------------
+def quantize_value_dint4(V, group_size=0):
+    """Channel-wise dINT4 of the cached Value tensor V [B, T, D] (B heads, T tokens, D channels).
+
+    The product P.V accumulates over the tokens, so one (step, zero) belongs to a channel d (or to
+    a group of `group_size` consecutive tokens of it) and is shared along the accumulation
+    dimension: V^T [D, T] of every head is quantized exactly like a weight matrix with one output
+    channel per row.  Returns (codes u8 [B, D, T], step f32 [B, D, T/G], zero u8 [B, D, T/G])."""
+    V = np.asarray(V)
+    B, T, D = V.shape
+    G = T if group_size in (0, None) else int(group_size)
+    codes = np.empty((B, D, T), np.uint8)
+    step = np.empty((B, D, T // G), np.float32)
+    zero = np.empty((B, D, T // G), np.uint8)
+    for b in range(B):
+        Vt = np.ascontiguousarray(V[b].T)            # [D, T]: accumulation dimension last
+        codes[b], step[b], zero[b] = quantize_weight_dint4(Vt, None, G)
+    return codes, step, zero
+
+
+def attention_value_w4a8(P, V, group_size=0, asym=False):
+    """O[b] = dequant( Q8(P[b]) . dINT4(V[b]) ) for every head b.
+
+    P [B, M, T]: attention probabilities of M query tokens, 8-bit token-wise (absmax form, or the
+    min-max form with a zero-point when ``asym``); V [B, T, D] as in quantize_value_dint4.
+    Returns a dict of every intermediate, stacked over b."""
+    P = np.asarray(P)
+    B, M, T = P.shape
+    D = V.shape[2]
+    G = T if group_size in (0, None) else int(group_size)
+    codes, step, zero = quantize_value_dint4(V, G)
+    out = dict(codes=codes, step=step, zero=zero,
+               Q=np.empty((B, M, T), np.uint8 if asym else np.int8), sx=np.empty((B, M), np.float32),
+               zx=np.zeros((B, M), np.int32), acc=np.empty((B, M, D, T // G), np.int32),
+               Y32=np.empty((B, M, D), np.float32), Y64=np.empty((B, M, D), np.float64))
+    for b in range(B):
+        packed = pack_dint4(codes[b])
+        if asym:
+            out["Q"][b], out["sx"][b], out["zx"][b] = quantize_act_uint8_asym(P[b])
+            out["acc"][b] = int_gemm_asym(out["Q"][b], out["zx"][b], packed, zero[b], G)
+        else:
+            out["Q"][b], out["sx"][b] = quantize_act_int8(P[b])
+            out["acc"][b] = int_gemm(out["Q"][b], packed, zero[b], G)
+        out["Y32"][b], out["Y64"][b] = dequant_epilogue(out["acc"][b], out["sx"][b], step[b])
+    return out

@@ -104,3 +104,27 @@ def random_layer(seed: int, M: int, K: int, N: int, x_dtype="f16", outlier_frac=
     W = (rng.standard_normal((N, K), dtype=np.float32) * 0.02).astype(xdt)
     s = rng.uniform(s_range[0], s_range[1], size=K).astype(np.float32)
     return X, W, s
+
+
+def attention_value(seed: int, B: int, M: int, T: int, D: int, v_dtype="f16"):
+    """Attention probabilities P [B, M, T] (fp32 rows that sum to 1: a softmax over seeded scores
+    with a heavily attended first token and a few peaked positions, the usual shape of decoder
+    attention maps) and a cached Value tensor V [B, T, D] ~ N(0, 1) whose channels have seeded
+    gains in [0.25, 4] plus two 8x outlier channels per head.  Stands in for the attention maps and
+    Value caches of the OPT / LLaMA runs the paper quantizes (Sec. 5.1); values only."""
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 104729 * seed + 17))
+    sc = rng.standard_normal((B, M, T), dtype=np.float32) * 2.0
+    if T > 0:
+        sc[:, :, 0] += 4.0
+        hot = rng.integers(0, T, size=(B, M, min(3, T)))
+        np.put_along_axis(sc, hot, np.take_along_axis(sc, hot, 2) + 5.0, 2)
+        sc -= sc.max(axis=2, keepdims=True)
+    P = np.exp(sc)
+    P /= np.maximum(P.sum(axis=2, keepdims=True), 1e-30)
+    gain = np.exp2(rng.uniform(-2.0, 2.0, size=(B, 1, D))).astype(np.float32)
+    if D >= 2:
+        for b in range(B):
+            gain[b, 0, rng.choice(D, size=2, replace=False)] *= 8.0
+    V = rng.standard_normal((B, T, D), dtype=np.float32) * gain
+    vdt = np.float32 if v_dtype == "f32" else np.float16
+    return P.astype(np.float32), np.clip(V, -65504.0, 65504.0).astype(vdt)
