@@ -292,6 +292,54 @@ def main():
                 row["TOPS"] = round(2.0 * Ma * Na * Ka / (ms * 1e-3) / 1e12, 1)
             asym_side.append(row)
 
+    # ------------------------------------------------------------------ 4-bit Value cache (side)
+    value_side = None
+    if not args.no_prefill:
+        # decode attention of 16 sequences x 32 heads (LLaMA-7B): one query token per head against 4096
+        # cached tokens of 128 channels, channel-wise dINT4 Value, 8-bit probabilities
+        Bv, Mv, Tv, Dv = 512, 1, 4096, 128
+        g = torch.Generator(device=dev)
+        g.manual_seed(20231106)
+        Vv = torch.randn((Bv, Tv, Dv), device=dev, generator=g).to(torch.float16)
+        Pv = torch.softmax(torch.randn((Bv * Mv, Tv), device=dev, generator=g) * 2.0, dim=1)
+        for _ in range(2):
+            codes_v, step_v, zero_v = w.quantize_value_dint4(Vv, 0)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(5):
+            w.quantize_value_dint4(Vv, 0)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        vq_ms = e0.elapsed_time(e1) / 5
+        nring_v = 5
+        wps_v = [w.pack_dint4(codes_v, w.LAYOUT_TILED)] + [
+            torch.randint(0, 256, (Bv * Dv * Tv // 2,), dtype=torch.uint8, device=dev, generator=g)
+            for _ in range(nring_v - 1)]
+        del codes_v
+        xq_v, sx_v = w.quantize_act_int8(Pv, None)
+        y_v = torch.empty((Bv * Mv, Dv), dtype=torch.float16, device=dev)
+        args_v = [(P(xq_v), P(sx_v), None, Mv, P(wp), P(step_v), P(zero_v), None, None, Dv, Tv, 0, P(y_v),
+                   w.F16, Dv, Bv, st) for wp in wps_v]
+        for i in range(nring_v):
+            assert lib.w4a8_gemm_batched(*args_v[i]) == 0
+        torch.cuda.synchronize()
+        reps_v = 100
+        e0.record(stream)
+        for i in range(reps_v):
+            lib.w4a8_gemm_batched(*args_v[i % nring_v])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        av_ms = e0.elapsed_time(e1) / reps_v
+        per_v = Bv * decode_bytes(Mv, Dv, Tv, Tv)
+        value_side = {"what": "quantize_value_dint4 (channel-wise dINT4 of V along the tokens) and "
+                              "w4a8_gemm_batched (8-bit probabilities x 4-bit Value, one launch for all heads)",
+                      "workload": f"heads={Bv} query_tokens={Mv} cached_tokens={Tv} channels={Dv}",
+                      "attn_value_us": round(av_ms * 1e3, 2), "attn_value_GBps": round(per_v / av_ms / 1e6, 1),
+                      "attn_value_frac_of_hbm_peak": round(per_v / av_ms / 1e6 / HBM_PEAK_GBS, 4),
+                      "quantize_value_ms": round(vq_ms, 4),
+                      "quantize_value_GBps": round(Bv * Tv * Dv * 3 / vq_ms / 1e6, 1)}
+        del Vv, Pv, wps_v
+
     out = {
         "metric": METRIC, "value": round(weight_gbs, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
@@ -309,6 +357,7 @@ def main():
         "asymmetric_activations": {"what": "w4a8_gemm_asym (token zero-point taken out of the int32 "
                                            "accumulators), same shapes and protocol as the lists above",
                                    "shapes": asym_side},
+        "value_cache": value_side,
     }
     print(json.dumps(out), flush=True)
 

@@ -169,6 +169,39 @@ int w4a8_gemm_asym(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t
                    void *Y, int y_dtype, int64_t ldy,
                    int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- 4-bit Value cache ("W4A8V4", Sec. 5.1).  Value is quantized channel-wise along the dimension
+ * over which the product with the attention map accumulates (App. A.1), i.e. along the tokens:
+ * for every head b and channel d, the T cached values V[b, :, d] (or each group of `group_size`
+ * consecutive tokens of them) share one (step, zero), and are coded by the rule of
+ * quantize_weight_dint4 (with s = 1).  The output is V^T per head -- exactly the operand layout of
+ * a weight matrix with N = D output channels and K = T input channels -- so pack_dint4(codes,
+ * batch*D, T, ...), dint4_weight_sums and w4a8_gemm_batched apply to it unchanged.
+ *   V      in   element (b, t, d) at V[b*ld_b + t*ld_t + d], v_dtype F32 / F16 / BF16;
+ *               ld_t >= D, ld_b >= 0 (token-major, as a cache is appended to; heads may be
+ *               interleaved, e.g. a [T, heads, D] cache has ld_t = heads*D, ld_b = D)
+ *   group_size  0 or T: per channel; else tokens per group, T % group_size == 0
+ *   codes  out  [batch*D, T] one code per byte (row b*D + d, token fastest)
+ *   step   out  [batch*D, T/G] float          zero  out  [batch*D, T/G] uint8
+ * batch <= 65535, T/G <= 65535.  batch == 0 or D == 0 is a no-op. */
+int quantize_value_dint4(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D,
+                         int64_t ld_t, int64_t ld_b, int64_t group_size, uint8_t *codes,
+                         float *step, uint8_t *zero, void *stream);
+
+/* `batch` independent decode products of one shape in one launch -- e.g. the attention-times-Value
+ * product with a 4-bit Value cache (Value is quantized channel-wise along the accumulation
+ * dimension, App. A.1: each head's V^T [head_dim, tokens] is a per-channel dINT4 "weight" matrix
+ * and the INT8 attention probabilities are the activations).  Problem b uses
+ *     Xq + b*M*K, sx + b*M, zx + b*M, Wp + b*N*K/2, step/zero/wsum + b*N*(K/G), tsum + b*N*(K/128),
+ *     Y + b*M*ldy
+ * with the meaning of w4a8_gemm_asym (zx == NULL: of w4a8_gemm; wsum, tsum then unused).
+ * Wp in the tiled layout only.  Requires M <= 16 (M*K a multiple of 16), K <= 5120, N % 16 == 0,
+ * K % 128 == 0, batch <= 65535; needs no workspace and has no accumulator hook. */
+int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
+                      const uint8_t *Wp, const float *step, const uint8_t *zero,
+                      const int32_t *wsum, const int32_t *tsum,
+                      int64_t N, int64_t K, int64_t group_size,
+                      void *Y, int y_dtype, int64_t ldy, int64_t batch, void *stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *w4a8_status_string(int status);
 

@@ -7,5 +7,6 @@ from .binding import (  # noqa: F401
     BF16, EXPORTS, F16, F32, LAYOUT_CANONICAL, LAYOUT_TILED, LIB_PATH, W4A8Error,
     gemm_workspace_bytes, load_library, pack_dint4, quantize_act_int8, quantize_weight_dint4,
     status_string, unpack_dint4, w4a8_gemm,
-    dint4_weight_sums, quantize_act_int8_asym, w4a8_gemm_asym,
+    dint4_weight_sums, quantize_act_int8_asym, w4a8_gemm_asym, w4a8_gemm_batched,
+    quantize_value_dint4,
 )

@@ -23,7 +23,8 @@ _DTYPES = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 EXPORTS = (
     "quantize_act_int8", "quantize_weight_dint4", "pack_dint4", "unpack_dint4",
     "w4a8_gemm_workspace_bytes", "w4a8_gemm", "w4a8_status_string",
-    "quantize_act_int8_asym", "dint4_weight_sums", "w4a8_gemm_asym",
+    "quantize_act_int8_asym", "dint4_weight_sums", "w4a8_gemm_asym", "w4a8_gemm_batched",
+    "quantize_value_dint4",
 )
 
 _lib = None
@@ -65,6 +66,11 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.w4a8_gemm_asym.argtypes = [vp, vp, vp, i64, vp, ci, vp, vp, vp, vp, i64, i64, i64, vp, ci,
                                    i64, vp, vp, sz, vp]
     lib.w4a8_gemm_asym.restype = ci
+    lib.w4a8_gemm_batched.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, i64, i64, i64, vp, ci,
+                                      i64, i64, vp]
+    lib.w4a8_gemm_batched.restype = ci
+    lib.quantize_value_dint4.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, vp, vp, vp]
+    lib.quantize_value_dint4.restype = ci
     lib.w4a8_status_string.argtypes = [ci]
     lib.w4a8_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -222,3 +228,35 @@ def w4a8_gemm_asym(Xq: torch.Tensor, sx: torch.Tensor, zx: torch.Tensor, Wp: tor
                                          _ptr(acc_out), _ptr(workspace), ws_bytes, _stream()),
            "w4a8_gemm_asym")
     return (Y, acc_out) if want_acc else Y
+
+
+def w4a8_gemm_batched(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.Tensor,
+                      zero: torch.Tensor, batch: int, M: int, N: int, K: int, group_size: int = 0,
+                      zx=None, wsum=None, tsum=None, out_dtype=torch.float16, Y=None):
+    """`batch` decode products (M <= 16) of one shape in one launch; operands densely stacked:
+    Xq [batch*M, K], Wp tiled [batch*N*K/2], step/zero [batch*N, K/G], Y [batch*M, N]."""
+    if Y is None:
+        Y = torch.empty((batch * M, N), dtype=out_dtype, device=Xq.device)
+    _check(load_library().w4a8_gemm_batched(_ptr(Xq), _ptr(sx), _ptr(zx), M, _ptr(Wp), _ptr(step),
+                                            _ptr(zero), _ptr(wsum), _ptr(tsum), N, K,
+                                            int(group_size or 0), _ptr(Y), _DTYPES[Y.dtype],
+                                            Y.stride(0), batch, _stream()), "w4a8_gemm_batched")
+    return Y
+
+
+def quantize_value_dint4(V: torch.Tensor, group_size: int = 0):
+    """V [batch, T, D] (last dimension contiguous) -> (codes u8 [batch*D, T], step f32
+    [batch*D, T/G], zero u8 [batch*D, T/G]): channel-wise dINT4 along the tokens, stored as V^T."""
+    B, T, D = V.shape
+    if V.stride(2) != 1 and D > 1:
+        raise ValueError("the channel dimension of V must be contiguous")
+    G = T if not group_size else int(group_size)
+    ng = T // G if G > 0 and T % G == 0 else 1
+    codes = torch.empty((B * D, T), dtype=torch.uint8, device=V.device)
+    step = torch.empty((B * D, ng), dtype=torch.float32, device=V.device)
+    zero = torch.empty((B * D, ng), dtype=torch.uint8, device=V.device)
+    _check(load_library().quantize_value_dint4(_ptr(V), _DTYPES[V.dtype], B, T, D, V.stride(1),
+                                               V.stride(0), int(group_size or 0), _ptr(codes),
+                                               _ptr(step), _ptr(zero), _stream()),
+           "quantize_value_dint4")
+    return codes, step, zero

@@ -98,7 +98,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
             if (rc != W4A8_OK) return rc;
         }
         const int rc = launch_gemv(Xq, sx, zp, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
-                                   acc_out, (float *)(wsb + ws.part_off), st);
+                                   acc_out, (float *)(wsb + ws.part_off), 1, st);
         if (rc != W4A8_OK || !zx || !acc_out) return rc;
         return launch_acc_zero_point(acc_out, zx, wsum, M, N * (K / G), st);
     }
@@ -175,6 +175,21 @@ int quantize_weight_dint4(const void *W, int w_dtype, int64_t N, int64_t K, int6
                                (hipStream_t)stream);
 }
 
+int quantize_value_dint4(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D,
+                         int64_t ld_t, int64_t ld_b, int64_t group_size, uint8_t *codes,
+                         float *step, uint8_t *zero, void *stream)
+{
+    if (!valid_dtype(v_dtype)) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (batch < 0 || D < 0 || T < 1 || ld_t < D || !resolve_group(T, G)) return W4A8_ERR_SHAPE;
+    if (ld_b < 0) return W4A8_ERR_SHAPE;
+    if (batch > 65535 || T / G > 65535 || batch * D * T > 0x3fffffffffffLL) return W4A8_ERR_SHAPE;
+    if (batch == 0 || D == 0) return W4A8_OK;
+    if (!V || !codes || !step || !zero) return W4A8_ERR_NULL;
+    return launch_value_quant(V, v_dtype, batch, T, D, ld_t, ld_b, G, codes, step, zero,
+                              (hipStream_t)stream);
+}
+
 static int check_pack_shape(int64_t N, int64_t K, int layout)
 {
     if (!valid_layout(layout)) return W4A8_ERR_DTYPE;
@@ -235,6 +250,30 @@ int w4a8_gemm_asym(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t
     if (M > 0 && N > 0 && (!zx || !wsum || !tsum)) return W4A8_ERR_NULL;
     return gemm_common(Xq, sx, zx, M, Wp, layout, step, zero, wsum, tsum, N, K, group_size, Y,
                        y_dtype, ldy, acc_out, workspace, workspace_bytes, stream);
+}
+
+int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
+                      const uint8_t *Wp, const float *step, const uint8_t *zero,
+                      const int32_t *wsum, const int32_t *tsum,
+                      int64_t N, int64_t K, int64_t group_size,
+                      void *Y, int y_dtype, int64_t ldy, int64_t batch, void *stream)
+{
+    if (y_dtype != W4A8_F16 && y_dtype != W4A8_BF16) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (M < 0 || N < 0 || batch < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    // the decode kernel only, one K-range per workgroup, 32-bit offsets inside one problem
+    if (M > 16 || N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > 5120 || ldy < N ||
+        N * K / 2 > 0x7fffffffLL || batch > 65535)
+        return W4A8_ERR_SHAPE;
+    if (M == 0 || N == 0 || batch == 0) return W4A8_OK;
+    if (!Xq || !sx || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;
+    if (zx && (!wsum || !tsum)) return W4A8_ERR_NULL;
+    if ((uintptr_t)Xq % 16 != 0 || (M * K) % 16 != 0 || (uintptr_t)Wp % 16 != 0 ||
+        (uintptr_t)Y % 2 != 0)
+        return W4A8_ERR_SHAPE;
+    const ZeroPoint zp = {zx, zx ? wsum : nullptr, zx ? tsum : nullptr};
+    return launch_gemv(Xq, sx, zp, M, Wp, step, zero, N, K, G, Y, y_dtype, ldy, nullptr, nullptr,
+                       batch, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -89,8 +89,25 @@ struct GemvArgs {
 // output after the waves' int32 sums have been added (!GROUPED) -- never in floating point, where
 // the two large terms would cancel badly.
 template <bool GROUPED, int AT, int D, bool ACC_OUT, bool ASYM>
-__global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs a)
+__global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 {
+    // blockIdx.z: independent problems of one shape, densely stacked (batched launch)
+    GemvArgs a = args;
+    if (gridDim.z > 1) {
+        const int64_t b = blockIdx.z;
+        const int64_t rows_w = b * a.N, rows_x = b * a.M;
+        a.Xq += rows_x * a.K;
+        a.sx += rows_x;
+        a.Wt += rows_w * a.K / 2;
+        a.step += rows_w * a.ng;
+        a.zero += rows_w * a.ng;
+        a.Y += rows_x * a.ldy;
+        if (a.zx != nullptr) {
+            a.zx += rows_x;
+            a.wsum += rows_w * a.ng;
+            a.tsum += rows_w * (a.K >> 7);
+        }
+    }
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     float *red = reinterpret_cast<float *>(smem);                        // [2][GV_CW][256]
     v4u *rec = reinterpret_cast<v4u *>(smem + 2 * GV_CW * 256 * 4);      // [n-tile][channel][RS]
@@ -373,7 +390,7 @@ __global__ __launch_bounds__(256) void gemv_combine_kernel(const float *__restri
     Y[(int64_t)m * ldy + n] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
 }
 
-GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G)
+GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
 {
     GemvPlan pl;
     const int KT = (int)(K / TILE_K), NT = (int)(N / TILE_N);
@@ -385,7 +402,7 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G)
     const bool grouped = G != K;
     // about one workgroup per CU, n-tiles dealt out evenly (more, shorter-lived workgroups
     // measured slower: each one reloads its activation fragments)
-    int bps = 256 / pl.splits;
+    int bps = (int)(256 / (pl.splits * batch));   // batched: the 256 CUs are shared by all problems
     if (bps < 1) bps = 1;
     if (bps > NT) bps = NT;
     int q = (NT + bps - 1) / bps;   // most n-tiles any workgroup gets
@@ -408,9 +425,9 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G)
 }
 
 template <bool GROUPED, bool ACC_OUT, bool ASYM>
-static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, hipStream_t st)
+static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hipStream_t st)
 {
-    const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits);
+    const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits, (unsigned)batch);
 #define W4A8_GV_LAUNCH(AT_, D_)                                                                  \
     hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>), grid, dim3(GV_THREADS),  \
                        pl.lds_bytes, st, ga)
@@ -427,9 +444,11 @@ static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, hipStream_t s
 
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
-                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
+                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
+                hipStream_t st)
 {
-    const GemvPlan pl = plan_gemv(M, N, K, G);
+    const GemvPlan pl = plan_gemv(M, N, K, G, batch);
+    if (batch > 1 && (pl.splits > 1 || acc_out != nullptr)) return W4A8_ERR_SHAPE;
     const bool grouped = G != K;
     float *part = pl.splits > 1 ? partial : nullptr;
     GemvArgs ga;
@@ -443,19 +462,19 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     if (grouped) {
         // the per-tile zero-point term only exists in its own instances (asymmetric, grouped)
         if (asym) {
-            if (acc_out) launch_gemv_at<true, true, true>(pl, ga, st);
-            else launch_gemv_at<true, false, true>(pl, ga, st);
+            if (acc_out) launch_gemv_at<true, true, true>(pl, ga, (int)batch, st);
+            else launch_gemv_at<true, false, true>(pl, ga, (int)batch, st);
         } else {
-            if (acc_out) launch_gemv_at<true, true, false>(pl, ga, st);
-            else launch_gemv_at<true, false, false>(pl, ga, st);
+            if (acc_out) launch_gemv_at<true, true, false>(pl, ga, (int)batch, st);
+            else launch_gemv_at<true, false, false>(pl, ga, (int)batch, st);
         }
     } else {
         if (asym) {
-            if (acc_out) launch_gemv_at<false, true, true>(pl, ga, st);
-            else launch_gemv_at<false, false, true>(pl, ga, st);
+            if (acc_out) launch_gemv_at<false, true, true>(pl, ga, (int)batch, st);
+            else launch_gemv_at<false, false, true>(pl, ga, (int)batch, st);
         } else {
-            if (acc_out) launch_gemv_at<false, true, false>(pl, ga, st);
-            else launch_gemv_at<false, false, false>(pl, ga, st);
+            if (acc_out) launch_gemv_at<false, true, false>(pl, ga, (int)batch, st);
+            else launch_gemv_at<false, false, false>(pl, ga, (int)batch, st);
         }
     }
     int rc = hip_status(hipGetLastError());

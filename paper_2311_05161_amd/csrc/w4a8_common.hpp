@@ -149,6 +149,10 @@ int launch_acc_zero_point(int32_t *acc, const int32_t *zx, const int32_t *wsum, 
 int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
                         const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
                         uint8_t *zero, hipStream_t st);
+// Value cache: V [batch, T, D] (token stride ld_t, head stride ld_b) -> codes [batch * D, T]
+int launch_value_quant(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D, int64_t ld_t,
+                       int64_t ld_b, int64_t G, uint8_t *codes, float *step, uint8_t *zero,
+                       hipStream_t st);
 int launch_pack(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout,
                 hipStream_t st);
 int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout,
@@ -167,15 +171,18 @@ struct GemvPlan {
     int lds_bytes;
     size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1, else 0
 };
-GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G);
+GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch = 1);
 // Asymmetric activations: zx = token zero-points, wsum = weight sums per group [N, K/G],
 // tsum = weight sums per 128 columns [N, K/128]; all three null for the symmetric form.
 struct ZeroPoint {
     const int32_t *zx, *wsum, *tsum;
 };
+// batch > 1: `batch` problems of one shape, every operand densely stacked (Y: M * ldy apart);
+// needs a single K-range and no accumulator hook.
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
-                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st);
+                int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
+                hipStream_t st);
 // Y = cast(sx * sum over splits of partial).  int_step != null: the partials are int32
 // accumulators of a per-channel launch, scaled by int_step[n] / 8 after the exact zero-point term.
 int launch_gemv_combine(const float *partial, const float *sx, const float *int_step, ZeroPoint zp,

@@ -51,6 +51,25 @@ __device__ __forceinline__ uint32_t dint4_code(float w, float istep, int z)
     return (uint32_t)c;
 }
 
+// Min-max asymmetric parameters of a range that contains zero: step = (hi - lo) / 13,
+// z = clamp(rne(-lo / step), 0, 13); a degenerate range gives step 1, z 0.
+__device__ __forceinline__ void range_params(float lo, float hi, float &st, float &istep, int &z)
+{
+    if (hi == lo) {
+        st = 1.0f;
+        istep = 1.0f;
+        z = 0;
+    } else {
+        const float range = hi - lo;
+        st = range / 13.0f;
+        istep = 1.0f / st;
+        const float nlo = -lo;
+        float zf = __builtin_rintf(nlo * istep);
+        zf = fminf(fmaxf(zf, 0.0f), 13.0f);
+        z = (int)zf;
+    }
+}
+
 template <typename T, int V>
 __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
     const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
@@ -85,19 +104,7 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
         }
         lo = wave_min(lo);
         hi = wave_max(hi);
-        if (hi == lo) {
-            st = 1.0f;
-            istep = 1.0f;
-            z = 0;
-        } else {
-            const float range = hi - lo;
-            st = range / 13.0f;
-            istep = 1.0f / st;
-            const float nlo = -lo;
-            float zf = __builtin_rintf(nlo * istep);
-            zf = fminf(fmaxf(zf, 0.0f), 13.0f);
-            z = (int)zf;
-        }
+        range_params(lo, hi, st, istep, z);
         if (lane == 0) {
             step[seg] = st;
             zero[seg] = (uint8_t)z;
@@ -169,6 +176,96 @@ int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_
                                          zero, st);
         default: return W4A8_ERR_DTYPE;
     }
+}
+
+// ---- 4-bit Value cache (Sec. 5.1; App. A.1: channel-wise along the dimension the product with the
+// attention map accumulates over, i.e. the tokens) -------------------------------------------------
+// V [batch, T, D] is stored token-major, as a cache is appended to; the product wants V^T.  A
+// workgroup owns 64 channels of one (head, token group): lane = channel, so every load is 64
+// consecutive elements of one token; the four waves split the tokens, their ranges meet in LDS,
+// and the codes go through an LDS transpose so that each channel row is written 16 bytes at a time.
+template <typename T>
+__global__ __launch_bounds__(256) void value_quant_kernel(const T *__restrict__ V, int64_t Tn,
+                                                          int64_t D, int64_t ld_t, int64_t ld_b,
+                                                          int64_t G, uint8_t *__restrict__ codes,
+                                                          float *__restrict__ step,
+                                                          uint8_t *__restrict__ zero, int vec_ok)
+{
+    __shared__ float s_lo[4][64], s_hi[4][64];
+    __shared__ uint32_t s_codes[64][17];   // [channel][16 words of 4 tokens], odd stride
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t b = blockIdx.z, g = blockIdx.y;
+    const int64_t d = (int64_t)blockIdx.x * 64 + lane;
+    const bool live = d < D;
+    const T *v = V + b * ld_b + g * G * ld_t + (live ? d : 0);
+
+    float lo = 0.0f, hi = 0.0f;
+    if (live) {
+        for (int64_t t = wave; t < G; t += 4) {
+            const float x = to_f32(v[t * ld_t]);
+            lo = fminf(lo, x);
+            hi = fmaxf(hi, x);
+        }
+    }
+    s_lo[wave][lane] = lo;
+    s_hi[wave][lane] = hi;
+    __syncthreads();
+    lo = fminf(fminf(s_lo[0][lane], s_lo[1][lane]), fminf(s_lo[2][lane], s_lo[3][lane]));
+    hi = fmaxf(fmaxf(s_hi[0][lane], s_hi[1][lane]), fmaxf(s_hi[2][lane], s_hi[3][lane]));
+    float st, istep;
+    int z;
+    range_params(lo, hi, st, istep, z);
+    const int64_t ng = Tn / G;
+    if (wave == 0 && live) {
+        step[(b * D + d) * ng + g] = st;
+        zero[(b * D + d) * ng + g] = (uint8_t)z;
+    }
+
+    const int r = threadIdx.x >> 2, q = threadIdx.x & 3;   // write side: channel row, 16-token quarter
+    const int64_t dr = (int64_t)blockIdx.x * 64 + r;
+    for (int64_t c0 = 0; c0 < G; c0 += 64) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t t = c0 + wave * 16 + i4 * 4 + i;
+                if (live && t < G) word |= dint4_code(to_f32(v[t * ld_t]), istep, z) << (8 * i);
+            }
+            s_codes[lane][wave * 4 + i4] = word;
+        }
+        __syncthreads();
+        if (dr < D) {
+            const int64_t t0 = c0 + q * 16;
+            uint8_t *dst = codes + (b * D + dr) * Tn + g * G + t0;
+            const uint32_t *w = &s_codes[r][q * 4];
+            if (vec_ok && t0 + 16 <= G) {
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            } else {
+                for (int i = 0; i < 16 && t0 + i < G; ++i) dst[i] = (uint8_t)(w[i >> 2] >> (8 * (i & 3)));
+            }
+        }
+        __syncthreads();
+    }
+}
+
+int launch_value_quant(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D, int64_t ld_t,
+                       int64_t ld_b, int64_t G, uint8_t *codes, float *step, uint8_t *zero,
+                       hipStream_t st)
+{
+    const dim3 grid((unsigned)((D + 63) / 64), (unsigned)(T / G), (unsigned)batch);
+    const int vec_ok = (uintptr_t)codes % 16 == 0 && T % 16 == 0 && G % 16 == 0;
+#define W4A8_VQ_LAUNCH(T_)                                                                     \
+    hipLaunchKernelGGL((value_quant_kernel<T_>), grid, dim3(256), 0, st, (const T_ *)V, T, D, \
+                       ld_t, ld_b, G, codes, step, zero, vec_ok)
+    switch (v_dtype) {
+        case W4A8_F32: W4A8_VQ_LAUNCH(float); break;
+        case W4A8_F16: W4A8_VQ_LAUNCH(__half); break;
+        case W4A8_BF16: W4A8_VQ_LAUNCH(bf16_t); break;
+        default: return W4A8_ERR_DTYPE;
+    }
+#undef W4A8_VQ_LAUNCH
+    return hip_status(hipGetLastError());
 }
 
 // ---- sums of the quantized weights (needed to take a token zero-point out of the product) ------

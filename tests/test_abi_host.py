@@ -118,6 +118,32 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert gemm_asym(tsum=Z) == b.ERR_NULL
     assert gemm_asym(N=24) == b.ERR_SHAPE
 
+    # Value cache and the batched decode product
+    def vq(dt=b.F16, B=2, T=256, D=128, ld_t=128, ld_b=256 * 128, G=0, V=P, codes=P):
+        return c.quantize_value_dint4(V, dt, B, T, D, ld_t, ld_b, G, codes, P, P, Z)
+    assert vq(dt=4) == b.ERR_DTYPE
+    assert vq(ld_t=64) == b.ERR_SHAPE                # token stride below D
+    assert vq(ld_b=-1) == b.ERR_SHAPE
+    assert vq(G=100) == b.ERR_SHAPE                  # groups must divide T
+    assert vq(B=1 << 17) == b.ERR_SHAPE
+    assert vq(V=Z) == b.ERR_NULL
+    assert vq(codes=Z) == b.ERR_NULL
+    assert vq(B=0) == b.OK
+
+    def batched(M=4, N=128, K=256, G=0, ydt=b.F16, ldy=128, batch=8, zx=Z, wsum=Z, Xq=P):
+        return c.w4a8_gemm_batched(Xq, P, zx, M, P, P, P, wsum, wsum, N, K, G, P, ydt, ldy, batch, Z)
+    assert batched(M=17) == b.ERR_SHAPE              # decode shapes only
+    assert batched(K=5248) == b.ERR_SHAPE            # a single K-range per workgroup
+    assert batched(N=120) == b.ERR_SHAPE
+    assert batched(K=192) == b.ERR_SHAPE
+    assert batched(M=1, K=128, Xq=ctypes.c_void_p(0x1008)) == b.ERR_SHAPE
+    assert batched(batch=1 << 16) == b.ERR_SHAPE
+    assert batched(ldy=64) == b.ERR_SHAPE
+    assert batched(ydt=b.F32) == b.ERR_DTYPE
+    assert batched(Xq=Z) == b.ERR_NULL
+    assert batched(zx=P, wsum=Z) == b.ERR_NULL       # a zero-point needs the weight sums
+    assert batched(batch=0) == b.OK
+
 
 def test_product_path_has_no_cpu_fallback(lib, tmp_path):
     with pytest.raises(FileNotFoundError):

@@ -1,0 +1,127 @@
+"""GPU parity of the 4-bit Value-cache path (Sec. 5.1; App. A.1) against the CPU oracle:
+channel-wise dINT4 codes / steps / zero-points of V and the 8-bit probabilities bit-identical,
+the batched attention-times-Value product within 1e-3 relative (fp16) of the oracle's float64
+evaluation, and its integer accumulators bit-identical through the single-problem entry point."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as syn
+from gpu_util import assert_y_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2311_05161_amd as w
+    w.load_library()
+    assert torch.cuda.is_available()
+    return w
+
+
+VQ_CASES = [
+    # name, heads, tokens, channels, dtype, group, layout of the cache
+    ("llama_heads", 4, 512, 128, "f16", 0, "dense"),
+    ("token_groups", 3, 384, 64, "f16", 128, "dense"),
+    ("ragged_f32", 2, 200, 80, "f32", 0, "dense"),
+    ("ragged_groups", 2, 96, 48, "f16", 24, "dense"),
+    ("bf16_groups", 2, 256, 128, "bf16", 128, "dense"),
+    ("interleaved_heads", 5, 320, 64, "f16", 0, "thd"),
+    ("one_token_groups", 1, 8, 16, "f32", 1, "dense"),
+    ("long", 2, 5120, 128, "f16", 0, "dense"),
+]
+
+
+@pytest.mark.parametrize("case", VQ_CASES, ids=[c[0] for c in VQ_CASES])
+def test_value_quant_bit_exact(lib, oracle, case):
+    name, B, T, D, dtype, G, layout = case
+    _, V = syn.attention_value(sum(name.encode()) % 997, B, 1, T, D, v_dtype="f32")
+    if T >= 8:
+        V[0, :, 0] = 0.0                       # a channel that is zero for every token
+        V[0, :, 1] = np.abs(V[0, :, 1])        # an all-positive channel: zero-point 0
+        V[0, 3, 2] = 1e-3 * V[0, 3, 2]         # a value inside the band around zero
+    Vt = torch.from_numpy(V).to(TORCH_DT[dtype])
+    Vh = Vt.float().numpy() if dtype == "bf16" else Vt.numpy()
+    if layout == "thd":                        # cache stored [T, heads, D]; heads are a strided view
+        Vd = Vt.permute(1, 0, 2).contiguous().cuda().permute(1, 0, 2)
+        assert Vd.stride(0) == D and Vd.stride(1) == B * D
+    else:
+        Vd = Vt.cuda()
+    codes, step, zero = lib.quantize_value_dint4(Vd, G)
+    rc, rs, rz = oracle.quantize_value_dint4(Vh, G)
+    np.testing.assert_array_equal(host(step).reshape(rs.shape), rs)
+    np.testing.assert_array_equal(host(zero).reshape(rz.shape), rz)
+    np.testing.assert_array_equal(host(codes).reshape(rc.shape), rc)
+
+
+AV_CASES = [
+    # name, heads(batch), query tokens, cached tokens, channels, group, asymmetric probabilities
+    ("decode_32_heads", 32, 1, 1024, 128, 0, False),
+    ("gqa_8_queries", 8, 8, 4096, 128, 0, False),
+    ("more_heads_than_cus", 300, 4, 256, 64, 0, False),
+    ("max_tokens_16_queries", 2, 16, 5120, 128, 0, False),
+    ("token_groups", 16, 1, 2048, 128, 128, False),
+    ("asym_decode", 32, 1, 1024, 128, 0, True),
+    ("asym_token_groups", 6, 3, 1536, 64, 128, True),
+    ("one_head", 1, 2, 128, 16, 0, True),
+]
+
+
+@pytest.mark.parametrize("case", AV_CASES, ids=[c[0] for c in AV_CASES])
+def test_attention_value_matches_oracle(lib, oracle, case):
+    name, B, M, T, D, G, asym = case
+    P, V = syn.attention_value(sum(name.encode()) % 991, B, M, T, D)
+    ref = oracle.attention_value_w4a8(P, V, G, asym)
+
+    Pd = dev(P.reshape(B * M, T))
+    codes, step, zero = lib.quantize_value_dint4(dev(V), G)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    if asym:
+        Xq, sx, zx = lib.quantize_act_int8_asym(Pd, None)
+        wsum, tsum = lib.dint4_weight_sums(codes, zero, G)
+        np.testing.assert_array_equal(host(Xq).astype(np.int32) + 128, ref["Q"].reshape(B * M, T))
+        np.testing.assert_array_equal(host(zx) + 128, ref["zx"].reshape(-1))
+    else:
+        Xq, sx = lib.quantize_act_int8(Pd, None)
+        zx = wsum = tsum = None
+        np.testing.assert_array_equal(host(Xq), ref["Q"].reshape(B * M, T))
+    np.testing.assert_array_equal(host(sx), ref["sx"].reshape(-1))
+    np.testing.assert_array_equal(host(codes).reshape(ref["codes"].shape), ref["codes"])
+    np.testing.assert_array_equal(host(step).reshape(ref["step"].shape), ref["step"])
+    np.testing.assert_array_equal(host(zero).reshape(ref["zero"].shape), ref["zero"])
+
+    Y = lib.w4a8_gemm_batched(Xq, sx, Wp, step, zero, B, M, D, T, G, zx=zx, wsum=wsum, tsum=tsum)
+    y = host(Y).astype(np.float64)
+    assert_y_close(y, ref["Y64"].reshape(B * M, D), "f16")
+
+    # the same products one head at a time through the single-problem entry point, whose hook
+    # returns the int32 accumulators: bit-identical to the oracle's, and the same Y bits
+    ng = step.shape[1]
+    for b in sorted({0, B // 2, B - 1}):
+        xs = slice(b * M, (b + 1) * M)
+        ws = slice(b * D, (b + 1) * D)
+        Wb = Wp[b * D * T // 2:(b + 1) * D * T // 2]
+        if asym:
+            Yb, acc = lib.w4a8_gemm_asym(Xq[xs], sx[xs], zx[xs], Wb, step[ws], zero[ws], wsum[ws],
+                                         tsum[ws], D, T, G, want_acc=True)
+        else:
+            Yb, acc = lib.w4a8_gemm(Xq[xs], sx[xs], Wb, step[ws], zero[ws], D, T, G, want_acc=True)
+        np.testing.assert_array_equal(host(acc).reshape(M, D, ng), ref["acc"][b])
+        np.testing.assert_array_equal(host(Yb).view(np.uint16), host(Y[xs]).view(np.uint16))
+
+
+def test_batched_output_stride_and_bf16(lib, oracle):
+    B, M, T, D = 4, 2, 512, 64
+    P, V = syn.attention_value(77, B, M, T, D)
+    ref = oracle.attention_value_w4a8(P, V, 0, False)
+    Xq, sx = lib.quantize_act_int8(dev(P.reshape(B * M, T)), None)
+    codes, step, zero = lib.quantize_value_dint4(dev(V), 0)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    buf = torch.full((B * M, D + 32), 7.0, dtype=torch.bfloat16, device="cuda")
+    lib.w4a8_gemm_batched(Xq, sx, Wp, step, zero, B, M, D, T, 0, Y=buf[:, :D])
+    out = host(buf)
+    assert_y_close(out[:, :D].astype(np.float64), ref["Y64"].reshape(B * M, D), "bf16")
+    assert np.all(out[:, D:] == 7.0)           # nothing written beyond the N columns of a row
