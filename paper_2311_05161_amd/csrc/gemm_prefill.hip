@@ -31,6 +31,48 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int GM_BN = 256;  // output channels per workgroup
 constexpr int GM_OOB = 0x7fff0000;
+constexpr int GM_RING = 4;  // activation tiles in LDS
+
+// Pins the program order of memory instructions and of everything scheduled around them, at every
+// level of the compiler (emits no instruction).
+__device__ __forceinline__ void gm_order_fence()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Global -> LDS copy that bypasses the registers: lane l of the wave writes its 16 bytes to
+// lds_addr + 16 l (lds_addr: byte address in LDS, wave-uniform); addresses beyond the buffer
+// write zeros.  Completion is counted by vmcnt like any buffer load, but the compiler does not
+// know that this one writes LDS: whoever reads the bytes waits for vmcnt and a barrier first.
+__device__ __forceinline__ void dma_b128(v4i rsrc, int voff, int soff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
+                 :: "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_addr) : "memory");
+}
+
+// Copies issued by dma_b128 are invisible to the compiler's own wait insertion: wait_copies<Y>()
+// returns once at most Y accesses issued after the copies in question are outstanding (vmcnt
+// retires in issue order), and must be followed by a barrier before other waves read the tile.
+template <int YOUNGER>
+__device__ __forceinline__ void wait_copies()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(YOUNGER) : "memory");
+}
+// A use of every register of p (emits nothing): the compiler completes all the loads into p here,
+// with one wait, instead of piecemeal in front of later uses -- a later wait of its own could only
+// allow fewer accesses in flight, and it does not know of the LDS copies issued in between.
+// (In / out operands: what is computed from p afterwards depends on this statement and stays behind it.)
+__device__ __forceinline__ void use_all(v4u (&p)[2][2])
+{
+    asm volatile("" : "+v"(p[0][0]), "+v"(p[0][1]), "+v"(p[1][0]), "+v"(p[1][1]));
+}
+__device__ __forceinline__ void use_all(v4u (&p)[1][2])
+{
+    asm volatile("" : "+v"(p[0][0]), "+v"(p[0][1]));
+}
+// keeps the computation of v in front of this point (emits nothing)
+__device__ __forceinline__ void pin_value(v4i &v) { asm volatile("" : "+v"(v)); }
 
 // ---- per-token row-sums of Xq over each K-range (bias removal of the per-channel path) ----------
 __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ Xq, int64_t M, int K,
@@ -82,9 +124,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int GM_NS = GM_BN / (WN * 32);       // 32-channel sub-tiles per wave
     constexpr int WROWS = BM / WM;                 // token rows per wave
     constexpr int MS = WROWS / 32;                 // 32-token sub-tiles per wave
+    constexpr int NW = WM * WN;                    // waves
     constexpr int LD_ITERS = BM * 8 / GM_THREADS;  // 16-byte chunks of the A tile per thread
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    uint8_t(*lds)[BM * TILE_K] = reinterpret_cast<uint8_t(*)[BM * TILE_K]>(lds_raw);   // [3][BM * 128]
+    uint8_t(*lds)[BM * TILE_K] = reinterpret_cast<uint8_t(*)[BM * TILE_K]>(lds_raw);   // [GM_RING][BM * 128]
     // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, a ring of four groups
     __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 4 : 1][GROUPED ? GM_BN : 4];
     __shared__ int s_gz[GROUPED ? 4 : 1][GROUPED ? GM_BN : 4];
@@ -119,8 +162,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 
     __amdgpu_buffer_rsrc_t rw =
         __builtin_amdgcn_make_buffer_rsrc((void *)Wt, 0, (int)((int64_t)N * K / 2), 0x00020000);
-    __amdgpu_buffer_rsrc_t rx =
-        __builtin_amdgcn_make_buffer_rsrc((void *)Xq, 0, (int)((int64_t)M * K), 0x00020000);
+    // the LDS copies take the descriptor of Xq as plain words (base, high bits with stride 0, bytes, flags)
+    const uint64_t xq_addr = (uint64_t)Xq;
+    const v4i rx = {(int)(uint32_t)xq_addr, (int)((xq_addr >> 32) & 0xffffu), (int)((int64_t)M * K),
+                    0x00020000};
 
     // Weight operand of k-step s = 2 sp + h of a k-tile: MFMA lane (r32, kh) takes half h of the 16
     // bytes that lane (r32 % 16) + 16 (2 sp + kh) of tile (n / 16, kt) holds (w4a8.h), i.e. input
@@ -155,27 +200,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             for (int r = 0; r < 16; ++r) y[ms][ns][r] = 0.f;
 
     // A-tile staging: chunk c (16 bytes) of row r lives at r*128 + ((c ^ ((r >> 1) & 7)) * 16): with 64
-    // LDS banks (256 B per clock) 16 consecutive rows x one chunk index cover all banks exactly once
-    v4u areg[LD_ITERS];
-    auto load_a = [&](int kt) {
+    // LDS banks (256 B per clock) 16 consecutive rows x one chunk index cover all banks exactly once.
+    // The tile goes global -> LDS directly: copy i of wave w fills the 1 KB block q = i * NW + w
+    // (rows 8q .. 8q+7) in lane order, so lane l fetches, for row 8q + l/8 and physical chunk l%8,
+    // the logical chunk that the swizzle puts there.  Rows >= M lie beyond the buffer: zeros.
+    int avoff[LD_ITERS];
 #pragma unroll
-        for (int i = 0; i < LD_ITERS; ++i) {
-            const int idx = tid + i * GM_THREADS;
-            const int row = idx >> 3, ch = idx & 7;
-            // rows >= M lie beyond the buffer and read as zero
-            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (m0 + row) * K + ch * 16, (kt0 + kt) * TILE_K, 0);
-        }
-    };
-    auto store_a = [&](int buf) {
+    for (int i = 0; i < LD_ITERS; ++i) {
+        const int row = (i * NW + wave) * 8 + (lane >> 3);
+        avoff[i] = (m0 + row) * K + (((lane & 7) ^ ((row >> 1) & 7)) << 4);
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw;
+    auto dma_a = [&](int kt, int buf) {
 #pragma unroll
-        for (int i = 0; i < LD_ITERS; ++i) {
-            const int idx = tid + i * GM_THREADS;
-            const int row = idx >> 3, ch = idx & 7;
-            *reinterpret_cast<v4u *>(&lds[buf][row * TILE_K + ((ch ^ ((row >> 1) & 7)) << 4)]) = areg[i];
-        }
+        for (int i = 0; i < LD_ITERS; ++i)
+            dma_b128(rx, avoff[i], (kt0 + kt) * TILE_K,
+                     lds_base + (uint32_t)(buf * (BM * TILE_K) + (i * NW + wave) * 1024));
     };
 
-    v4u p[GM_NS][2], pn[GM_NS][2];
+    v4u pa[GM_NS][2], pb[GM_NS][2];   // packed weights of two consecutive k-tiles (ping-pong)
     auto load_b = [&](int kt, v4u(&dst)[GM_NS][2]) {
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns)
@@ -281,16 +324,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     };
 
     // ---- pipeline ------------------------------------------------------------------------------
-    // LDS holds three activation tiles: kt (being consumed), kt + 1 (published by the previous
-    // barrier, so its first fragments can be fetched before this iteration's barrier) and kt + 2
-    // (being written).  Global loads run three tiles ahead of the MFMAs; tile indices past the end
-    // are clamped to the last tile (a redundant but in-bounds reload).
+    // LDS holds four activation tiles: kt (being consumed), kt + 1 (its first fragments are fetched
+    // before this iteration's barrier), kt + 2 (landing, published by this iteration's barrier) and
+    // kt + 3 (copy issued right before that barrier).  The packed weights of tile kt + 2 are loaded
+    // at the start of iteration kt's last k-step into the registers that tile kt has just been
+    // decoded from (ordinary loads: the compiler places their waits), one whole iteration before
+    // their first decode.  The LDS copies are waited for explicitly at the end of the next
+    // iteration, one barrier before anyone reads the tile: the only accesses issued after them by
+    // then are that iteration's NB weight loads (vmcnt retires in issue order), and every access
+    // of the loop is unconditional (tiles past the end are clamped), which keeps that count exact.
+    // The k-tile loop is unrolled by two so that the two weight register sets swap roles without
+    // copies.
+    constexpr int NB = GM_NS * 2;   // weight loads per k-tile and lane
     const int ktl = KTl - 1;
     const int g0 = GROUPED ? kt0 / tiles_per_group : 0;            // groups [g0, g_end) of this split
     const int g_end = GROUPED ? g0 + KTl / tiles_per_group : 1;
-    load_a(0);
-    load_b(0, p);
-    load_b(min(1, ktl), pn);
+    dma_a(0, 0);
+    dma_a(min(1, ktl), 1);
+    dma_a(min(2, ktl), 2);
+    load_b(0, pa);
+    load_b(min(1, ktl), pb);
     if (GROUPED) {
         fetch_group(g0);
         publish_group(g0);
@@ -302,86 +355,105 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     } else {
         load_luts(0);
     }
-    store_a(0);
-    load_a(min(1, ktl));
-    store_a(1);
-    load_a(min(2, ktl));
+    use_all(pa);
+    use_all(pb);
+    wait_copies<0>();
     __syncthreads();
     if (GROUPED) load_luts(g0);
 
     v4i af[2][MS], w[2][GM_NS];
     read_a(0, 0, af[0]);
-    decode_step(p, 0, w[0]);
+    decode_step(pa, 0, w[0]);
 
-    // Outer loop over the quantization groups of this K-range (one "group" spanning all of it for
-    // per-channel weights), inner loop over a group's k-tiles; the group is rescaled into the
-    // fp32 sums behind its last k-tile.  Ring of group parameters: group g + 2 is published while
-    // group g starts (its slot was last read for group g - 2, at least one barrier ago) and read
-    // from the end of group g + 1 on (at least one barrier later).
-    int cur = 0;   // kt % 3
-    int kt = 0;
+    // One k-tile: P holds its packed weights, PN those of the next tile.  For group-wise weights
+    // the group is rescaled into the fp32 sums behind its last k-tile.  Ring of group parameters:
+    // group g + 2 is published before the barrier of group g's first tile (its slot was last read
+    // for group g - 2, at least one barrier ago) and read from the end of group g + 1 on (at least
+    // one barrier later).
     const int tiles_in_group = GROUPED ? tiles_per_group : KTl;
-    for (int g = g0; g < g_end; ++g) {
-        if (GROUPED) {
-            if (g + 2 < g_end) publish_group(g + 2);
-            if (g + 3 < g_end) fetch_group(g + 3);
-        }
-        for (int t = 0; t < tiles_in_group; ++t, ++kt) {
-            const int nxt = cur == 2 ? 0 : cur + 1;
-            const int nx2 = nxt == 2 ? 0 : nxt + 1;
-            store_a(nx2);                     // tile kt + 2 (loaded one iteration ago)
-            load_a(min(kt + 3, ktl));
-
-            // Software pipeline over the four 32-column k-steps: fragments and decoded weights of
-            // the next step (for the last step: of the next tile's first step) are produced while
-            // the MFMAs of the current step run.
+    auto k_tile = [&](v4u(&P)[GM_NS][2], v4u(&PN)[GM_NS][2], int kt, int t, int g)
+                      __attribute__((always_inline)) {
+        const int cur = kt & (GM_RING - 1), nxt = (kt + 1) & (GM_RING - 1);
+        // Software pipeline over the four 32-column k-steps: fragments and decoded weights of
+        // the next step (for the last step: of the next tile's first step) are produced while
+        // the MFMAs of the current step run.
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                if (s < 3) {
-                    read_a(cur, s + 1, af[(s + 1) & 1]);
-                    decode_step(p, s + 1, w[(s + 1) & 1]);
-                } else {
-                    if (GROUPED && t == tiles_in_group - 1 && g + 1 < g_end) load_luts(g + 1);
-                    read_a(nxt, 0, af[0]);
-                    decode_step(pn, 0, w[0]);
-                }
-                // D[i][j]: rows i = output channels (weights operand), columns j = tokens.  The
-                // first k-step of a group starts from a zero operand instead of cleared accumulators.
-                if (GROUPED && s == 0 && t == 0) {
-                    const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                        for (int ns = 0; ns < GM_NS; ++ns)
-                            acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
-                                                                                z16, 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                        for (int ns = 0; ns < GM_NS; ++ns)
-                            acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
-                                                                                acc[ms][ns], 0, 0, 0);
-                }
-                // issue order for this step: the LDS reads of the next step first, then the decode
-                // arithmetic spread evenly between the MFMAs
-                __builtin_amdgcn_sched_group_barrier(0x100, MS, 0);
-#pragma unroll
-                for (int i = 0; i < MS * GM_NS; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, GROUPED ? 6 : 4, 0);
-                }
+        for (int s = 0; s < 4; ++s) {
+            if (s < 3) {
+                read_a(cur, s + 1, af[(s + 1) & 1]);
+                decode_step(P, s + 1, w[(s + 1) & 1]);
+            } else {
+                gm_order_fence();
+                load_b(min(kt + 2, ktl), P);   // P: last read by the decode during the previous k-step
+                gm_order_fence();
+                if (GROUPED && t == tiles_in_group - 1 && g + 1 < g_end) load_luts(g + 1);
+                read_a(nxt, 0, af[0]);
+                use_all(PN);
+                decode_step(PN, 0, w[0]);
             }
+            // D[i][j]: rows i = output channels (weights operand), columns j = tokens.  The
+            // first k-step of a group starts from a zero operand instead of cleared accumulators.
+            if (GROUPED && s == 0 && t == 0) {
+                const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int ns = 0; ns < GM_NS; ++ns)
+                for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                for (int sp = 0; sp < 2; ++sp) p[ns][sp] = pn[ns][sp];
-            load_b(min(kt + 2, ktl), pn);
-            cur = nxt;
-            __syncthreads();
+                    for (int ns = 0; ns < GM_NS; ++ns)
+                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                            z16, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                    for (int ns = 0; ns < GM_NS; ++ns)
+                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                                                                            acc[ms][ns], 0, 0, 0);
+            }
+            // issue order for this step: the LDS reads of the next step first, then the decode
+            // arithmetic spread evenly between the MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, MS, 0);
+#pragma unroll
+            for (int i = 0; i < MS * GM_NS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, GROUPED ? 6 : 4, 0);
+            }
         }
-        if (GROUPED) flush_group(g);
+#pragma unroll
+        for (int ns = 0; ns < GM_NS; ++ns) pin_value(w[0][ns]);
+        gm_order_fence();
+        // group parameters: the values fetched an iteration (or more) ago go to LDS, the next
+        // fetch joins this iteration's loads as the youngest
+        // tile kt + 2 has landed, and so have the group parameters fetched a group ago (younger:
+        // the loads into P)
+        if (GROUPED && t == 0 && g + 2 < g_end) publish_group(g + 2);
+        wait_copies<NB>();
+        dma_a(min(kt + 3, ktl), (kt + 3) & (GM_RING - 1));
+        if (GROUPED && t == 0 && g + 3 < g_end) fetch_group(g + 3);
+        gm_order_fence();
+        __syncthreads();
+        if (GROUPED && t == tiles_in_group - 1) flush_group(g);
+    };
+
+    {
+        int kt = 0, t = 0, g = g0;
+        auto advance = [&]() {
+            ++kt;
+            if (GROUPED && ++t == tiles_in_group) {
+                t = 0;
+                ++g;
+            }
+        };
+        while (kt + 2 <= KTl) {
+            k_tile(pa, pb, kt, t, g);
+            advance();
+            k_tile(pb, pa, kt, t, g);
+            advance();
+        }
+        if (kt < KTl) k_tile(pa, pb, kt, t, g);
     }
+    // the staging buffers are reused below: no copy may still be on its way
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 
     // epilogue parameters of the workgroup's 256 channels, in the (now free) staging buffer
     float *s_es = reinterpret_cast<float *>(&lds[0][0]);          // step / 8
@@ -476,7 +548,7 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
     const int vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
-    constexpr int lds_bytes = 3 * BM * TILE_K;
+    constexpr int lds_bytes = GM_RING * BM * TILE_K;
     static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
     if (!attr_set) {
         if (lds_bytes > 48 * 1024 &&

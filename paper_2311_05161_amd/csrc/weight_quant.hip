@@ -201,10 +201,16 @@ __global__ __launch_bounds__(256) void value_quant_kernel(const T *__restrict__ 
 
     float lo = 0.0f, hi = 0.0f;
     if (live) {
-        for (int64_t t = wave; t < G; t += 4) {
-            const float x = to_f32(v[t * ld_t]);
-            lo = fminf(lo, x);
-            hi = fmaxf(hi, x);
+        // eight loads in flight per lane; tokens past the group re-read its first token
+        for (int64_t t = wave; t < G; t += 32) {
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = to_f32(v[(t + 4 * i < G ? t + 4 * i : 0) * ld_t]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                lo = fminf(lo, x[i]);
+                hi = fmaxf(hi, x[i]);
+            }
         }
     }
     s_lo[wave][lane] = lo;
@@ -224,13 +230,19 @@ __global__ __launch_bounds__(256) void value_quant_kernel(const T *__restrict__ 
     const int r = threadIdx.x >> 2, q = threadIdx.x & 3;   // write side: channel row, 16-token quarter
     const int64_t dr = (int64_t)blockIdx.x * 64 + r;
     for (int64_t c0 = 0; c0 < G; c0 += 64) {
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t t = c0 + wave * 16 + i;
+            x[i] = to_f32(v[(t < G ? t : 0) * ld_t]);   // all sixteen loads issued before any is used
+        }
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
             uint32_t word = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int64_t t = c0 + wave * 16 + i4 * 4 + i;
-                if (live && t < G) word |= dint4_code(to_f32(v[t * ld_t]), istep, z) << (8 * i);
+                if (live && t < G) word |= dint4_code(x[i4 * 4 + i], istep, z) << (8 * i);
             }
             s_codes[lane][wave * 4 + i4] = word;
         }
