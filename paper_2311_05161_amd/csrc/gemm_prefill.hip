@@ -32,6 +32,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int GM_BN = 256;  // output channels per workgroup
 constexpr int GM_OOB = 0x7fff0000;
 constexpr int GM_RING = 4;  // activation tiles in LDS
+constexpr int GM_PANEL = 4; // token tiles per panel of the tile numbering
 
 // Pins the program order of memory instructions and of everything scheduled around them, at every
 // level of the compiler (emits no instruction).
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const int KT = K / TILE_K;
 
     // Workgroups are handed to the 8 XCDs round-robin; renumber so that each XCD works on a
-    // contiguous range of tiles (token tiles fastest) and its private L2 sees the reuse.
+    // contiguous range of tiles and its private L2 sees the reuse.
     // With few output tiles K is also split over workgroups (each writes an fp32 partial).
     const int tiles = grid_m * grid_n;
     const int split = blockIdx.x / tiles;
@@ -152,8 +153,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         const int per = tiles / 8;
         if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
     }
-    const int bm = bid % grid_m;
-    const int bn = bid / grid_m;
+    // tiles are numbered down panels of GM_PANEL token tiles, channel tiles next: the 32 tiles an
+    // XCD works on at a time then share their activations 8 ways and their weights 4 ways
+    const int panel = bid / (GM_PANEL * grid_n);
+    const int pr = bid - panel * (GM_PANEL * grid_n);
+    const int ph = min(GM_PANEL, grid_m - panel * GM_PANEL);   // rows of this (possibly last, lower) panel
+    const int bn = pr / ph;
+    const int bm = panel * GM_PANEL + pr - bn * ph;
     const int m0 = bm * BM;
     const int nb0 = bn * GM_BN;                        // first output channel of the workgroup
     const int wn = wave % WN;                          // wave column
