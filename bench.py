@@ -28,8 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 # HBM bytes per gemv_kernel launch on this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script, scaled by a 256 MiB copy (profiles/gemv_kernel_C2_decode_hbm_traffic.md): 9,694,208 read + 131,072 written
-GEMV_C2_TRAFFIC_BYTES = 9830400
+# script, scaled by a 256 MiB copy (profiles/gemv_kernel_C2_decode_hbm_traffic.md): 9,710,592 read + 131,072 written
+GEMV_C2_TRAFFIC_BYTES = 9841664
 METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
 
 
@@ -214,10 +214,25 @@ def main():
         reps_ms.append(e0.elapsed_time(e1) / L)
     kern_ms = float(np.median(reps_ms))
     achieved = per_copy / (kern_ms * 1e-3) / 1e9
+    # context: the same loop over the smallest kernel of the library (packing one 16 x 128 tile) -- what a
+    # launch costs on this stream when the kernel itself does next to nothing
+    tiny_codes = torch.zeros((16, 128), dtype=torch.uint8, device=dev)
+    tiny_out = torch.empty((16 * 64,), dtype=torch.uint8, device=dev)
+    tiny_args = (P(tiny_codes), 16, 128, P(tiny_out), w.LAYOUT_TILED, st)
+    for i in range(64):
+        lib.pack_dint4(*tiny_args)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(L):
+        lib.pack_dint4(*tiny_args)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    floor_us = e0.elapsed_time(e1) / L * 1e3
     roofline = {"bound": "hbm", "kernel": "gemv_kernel (w4a8_gemm, M<=16)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": GEMV_C2_TRAFFIC_BYTES,
-                "bytes_per_launch": per_copy, "avg_launch_us": round(kern_ms * 1e3, 3)}
+                "bytes_per_launch": per_copy, "avg_launch_us": round(kern_ms * 1e3, 3),
+                "launch_floor_us": round(floor_us, 3)}
 
     # ------------------------------------------------------------------ larger decode shapes (side figures)
     def time_gemm(Mq, Nq, Kq, Gq, reps, ring_bytes=600 << 20, asym=False):
