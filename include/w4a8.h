@@ -194,7 +194,7 @@ int quantize_value_dint4(const void *V, int v_dtype, int64_t batch, int64_t T, i
  *     Xq + b*M*K, sx + b*M, zx + b*M, Wp + b*N*K/2, step/zero/wsum + b*N*(K/G), tsum + b*N*(K/128),
  *     Y + b*M*ldy
  * with the meaning of w4a8_gemm_asym (zx == NULL: of w4a8_gemm; wsum, tsum then unused).
- * Wp in the tiled layout only.  Requires M <= 16 (M*K a multiple of 16), K <= 5120, N % 16 == 0,
+ * Wp in the tiled layout only.  Requires M <= 16 (M*K a multiple of 16), K <= 9216 (5120 with groups), N % 16 == 0,
  * K % 128 == 0, batch <= 65535; needs no workspace and has no accumulator hook. */
 int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
                       const uint8_t *Wp, const float *step, const uint8_t *zero,

@@ -262,7 +262,7 @@ int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int6
     int64_t G = group_size;
     if (M < 0 || N < 0 || batch < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
     // the decode kernel only, one K-range per workgroup, 32-bit offsets inside one problem
-    if (M > 16 || N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > 5120 || ldy < N ||
+    if (M > 16 || N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > (G == K ? 9216 : 5120) || ldy < N ||
         N * K / 2 > 0x7fffffffLL || batch > 65535)
         return W4A8_ERR_SHAPE;
     if (M == 0 || N == 0 || batch == 0) return W4A8_OK;

@@ -31,7 +31,7 @@ namespace w4a8 {
 
 constexpr int GV_CW = 8;                          // compute waves per workgroup
 constexpr int GV_THREADS = (GV_CW + 1) * WAVE;    // + 1 helper wave
-constexpr int GV_MAX_AT = 5;                      // k-tiles per compute wave -> K per split <= 5120
+constexpr int GV_MAX_AT = 9;                      // k-tiles per compute wave -> K per split <= 9216 (5120 group-wise)
 constexpr int GV_STAGE = 6;                       // decode records staged per thread (grouped mode)
 constexpr int GV_LDS_BUDGET = 48 * 1024;          // bytes of decode records per workgroup
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
@@ -394,7 +394,10 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
 {
     GemvPlan pl;
     const int KT = (int)(K / TILE_K), NT = (int)(N / TILE_N);
-    pl.splits = (KT + GV_CW * GV_MAX_AT - 1) / (GV_CW * GV_MAX_AT);
+    // group-wise weights keep at most 5 k-tiles per wave: their decode records (one per channel and
+    // k-tile) would otherwise leave room for too few n-tiles per workgroup in LDS
+    const int max_at = (G != K) ? 5 : GV_MAX_AT;
+    pl.splits = (KT + GV_CW * max_at - 1) / (GV_CW * max_at);
     pl.kt_per_split = (KT + pl.splits - 1) / pl.splits;
     pl.splits = (KT + pl.kt_per_split - 1) / pl.kt_per_split;
     const int tpw = (pl.kt_per_split + GV_CW - 1) / GV_CW;
@@ -437,7 +440,11 @@ static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hi
         case 2: W4A8_GV_LAUNCH(2, 4); break;
         case 3: W4A8_GV_LAUNCH(3, 3); break;
         case 4: W4A8_GV_LAUNCH(4, 2); break;
-        default: W4A8_GV_LAUNCH(5, 2); break;
+        case 5: W4A8_GV_LAUNCH(5, 2); break;
+        case 6: W4A8_GV_LAUNCH(6, 1); break;
+        case 7: W4A8_GV_LAUNCH(7, 1); break;
+        case 8: W4A8_GV_LAUNCH(8, 1); break;
+        default: W4A8_GV_LAUNCH(9, 1); break;
     }
 #undef W4A8_GV_LAUNCH
 }

@@ -52,6 +52,9 @@ def test_workspace_sizes(lib):
     # K > 5120 at decode is split over workgroups: fp32 partial sums [splits][M][N]
     assert lib.gemm_workspace_bytes(16, 5120, 13824, 128, lib.LAYOUT_TILED) == 3 * 16 * 5120 * 4
     assert lib.gemm_workspace_bytes(16, 13824, 5120, 128, lib.LAYOUT_TILED) == 0
+    # per-channel weights: a workgroup covers up to 9216 columns, no split below that
+    assert lib.gemm_workspace_bytes(16, 36864, 9216, 0, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(16, 4096, 11008, 0, lib.LAYOUT_TILED) == 2 * 16 * 4096 * 4
     # mid-size M with few output tiles: K is split as well (here 10 ranges of 4 k-tiles), and the
     # per-channel variant adds one row-sum per (range, token), 256-byte aligned before the partials
     part = 10 * 128 * 5120 * 4
@@ -133,7 +136,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     def batched(M=4, N=128, K=256, G=0, ydt=b.F16, ldy=128, batch=8, zx=Z, wsum=Z, Xq=P):
         return c.w4a8_gemm_batched(Xq, P, zx, M, P, P, P, wsum, wsum, N, K, G, P, ydt, ldy, batch, Z)
     assert batched(M=17) == b.ERR_SHAPE              # decode shapes only
-    assert batched(K=5248) == b.ERR_SHAPE            # a single K-range per workgroup
+    assert batched(K=9344) == b.ERR_SHAPE            # a single K-range per workgroup
+    assert batched(K=5248, G=128) == b.ERR_SHAPE     # (5120 columns with token groups)
     assert batched(N=120) == b.ERR_SHAPE
     assert batched(K=192) == b.ERR_SHAPE
     assert batched(M=1, K=128, Xq=ctypes.c_void_p(0x1008)) == b.ERR_SHAPE

@@ -160,6 +160,11 @@ DECODE_CASES = [
     ("k_split_2_g128", 16, 9216, 48, 128),        # K > 8192: two K-ranges + deterministic combine
     ("k_split_2_per_channel", 5, 11008, 32, 0),
     ("k_split_3_ragged", 9, 16512, 16, 384),
+    ("per_channel_6_tiles_per_wave", 16, 6144, 272, 0),   # K <= 9216 per channel: one K-range, 6..9 k-tiles per wave
+    ("per_channel_7_tiles_ragged", 3, 6784, 48, 0),
+    ("per_channel_8_tiles_per_wave", 16, 8192, 528, 0),
+    ("per_channel_9_tiles_per_wave", 9, 9216, 1040, 0),
+    ("per_channel_9_tiles_ragged", 16, 8576, 32, 0),
     ("many_n_tiles_per_block", 16, 512, 9232, 128),  # 577 n-tiles: several per workgroup, ragged
     ("many_n_tiles_per_channel", 2, 1024, 4640, 0),
 ]

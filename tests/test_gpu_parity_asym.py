@@ -103,6 +103,8 @@ GEMM_CASES = [
     ("decode_per_channel_tail", 7, 1152, 272, 0),
     ("decode_k_split_g128", 16, 9216, 48, 128),
     ("decode_k_split_per_channel", 5, 11008, 32, 0),
+    ("decode_per_channel_9_tiles_per_wave", 16, 9216, 272, 0),
+    ("decode_per_channel_7_tiles_ragged", 5, 6784, 48, 0),
     ("decode_many_n_tiles", 16, 512, 9232, 128),
     ("prefill_m17", 17, 384, 272, 0),
     ("prefill_m64_g128", 64, 512, 256, 128),

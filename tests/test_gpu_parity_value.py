@@ -63,6 +63,8 @@ AV_CASES = [
     ("gqa_8_queries", 8, 8, 4096, 128, 0, False),
     ("more_heads_than_cus", 300, 4, 256, 64, 0, False),
     ("max_tokens_16_queries", 2, 16, 5120, 128, 0, False),
+    ("long_context_9216_tokens", 3, 2, 9216, 128, 0, False),
+    ("long_context_asym", 2, 1, 7168, 64, 0, True),
     ("token_groups", 16, 1, 2048, 128, 128, False),
     ("asym_decode", 32, 1, 1024, 128, 0, True),
     ("asym_token_groups", 6, 3, 1536, 64, 128, True),
