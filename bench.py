@@ -355,6 +355,32 @@ def main():
                       "quantize_value_GBps": round(Bv * Tv * Dv * 3 / vq_ms / 1e6, 1)}
         del Vv, Pv, wps_v
 
+    # ------------------------------------------------------------------ AQAS scale search (side, offline)
+    search_side = None
+    if not args.no_prefill:
+        Ms = 512   # calibration tokens
+        Xc, _, _, _ = syn.make_layer("C2", M=Ms, variant=1)
+        Xc_d = torch.from_numpy(Xc).to(dev)
+        w.aqas_search(Xc_d, Wd, G)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        s_best, j_best, losses_s = w.aqas_search(Xc_d, Wd, G)
+        torch.cuda.synchronize()
+        search_ms = (time.perf_counter() - t0) * 1e3
+        t0 = time.perf_counter()
+        clip_idx, _, _ = w.aqas_clip_search(Xc_d, Wd, s_best, G)
+        torch.cuda.synchronize()
+        clip_ms = (time.perf_counter() - t0) * 1e3
+        ls = losses_s.cpu().numpy()
+        search_side = {"what": "aqas_search (17 grid points, each a full pass of the quantized layer on the GPU) and "
+                               "aqas_clip_search (11 range factors per output channel) on the C2 layer",
+                       "workload": f"calibration_tokens={Ms} K={K} N={N} G={G}",
+                       "search_ms": round(search_ms, 3), "clip_ms": round(clip_ms, 3),
+                       "best_alpha": int(j_best.item()) / 16.0,
+                       "loss_at_best_over_loss_at_alpha_0_and_1": [round(float(ls.min() / ls[0]), 4),
+                                                                   round(float(ls.min() / ls[16]), 4)],
+                       "channels_clipped": int((clip_idx > 0).sum().item())}
+
     out = {
         "metric": METRIC, "value": round(weight_gbs, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
@@ -372,7 +398,7 @@ def main():
         "asymmetric_activations": {"what": "w4a8_gemm_asym (token zero-point taken out of the int32 "
                                            "accumulators), same shapes and protocol as the lists above",
                                    "shapes": asym_side},
-        "value_cache": value_side,
+        "value_cache": value_side, "aqas_search": search_side,
     }
     print(json.dumps(out), flush=True)
 

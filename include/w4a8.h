@@ -202,6 +202,49 @@ int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int6
                       int64_t N, int64_t K, int64_t group_size,
                       void *Y, int y_dtype, int64_t ldy, int64_t batch, void *stream);
 
+/* ---- AQAS scale search (Sec. 3.2, Eq. 1; App. A.4).  Offline calibration: on calibration activations
+ * X [M, K] and the layer's weights W [N, K] it looks for the per-input-channel scale s that minimizes
+ *     loss(s) = sum_{m,n} ( Yq[m,n] - sum_k X[m,k] W[n,k] )^2,    Yq = the fp16 output of the quantized
+ * layer computed by this library's own kernels (quantize_act_int8, quantize_weight_dint4, pack_dint4,
+ * w4a8_gemm) with that s.  Representatives are the maximum magnitudes per input channel (App. A.4):
+ *     ax[k] = max_m |X[m,k]|,   aw[k] = max_n |W[n,k]|,
+ * and the candidates are the 17 grid points j = 0..16 of
+ *     s_k(j) = ax[k]^(j/16) / aw[k]^(1 - j/16)        (1 where ax[k] or aw[k] is 0; clamped to [1e-4, 1e4]),
+ * a sixteenth power being the product, in the order 1/2, 1/4, 1/8, 1/16, of the correctly rounded
+ * binary32 square-root chain of x selected by the bits of j (x for j = 16, 1 for j = 0): a fixed
+ * sequence of IEEE operations.  The first grid point with the smallest loss wins; it is chosen on the
+ * device, nothing synchronizes.
+ *   X, W     in   one element type `dtype` for both (F32, F16, BF16); rows ldx / ldw elements apart;
+ *                 F16: 16-byte aligned rows (pointer % 16 == 0, ld % 8 == 0)
+ *   s_out    out  [K] float: s at the chosen grid point      best_j  out  int32 (device)
+ *   losses   out  [17] double (device): loss of every grid point
+ *   workspace     device scratch of aqas_search_workspace_bytes(M, N, K, group_size) bytes, 256-byte aligned
+ * Shape limits as for w4a8_gemm (N % 16 == 0, K % 128 == 0, groups multiples of 128). */
+size_t aqas_search_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size);
+int aqas_channel_absmax(const void *A, int dtype, int64_t R, int64_t K, int64_t lda, float *out,
+                        void *stream);                         /* out[k] = max_r |A[r,k]|, exact */
+int aqas_scale(const float *ax, const float *aw, int64_t K, int j, float *s, void *stream);
+int aqas_search(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K, int64_t ldx,
+                int64_t ldw, int64_t group_size, float *s_out, int32_t *best_j, double *losses,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Weight clipping after the scale search (App. A.4).  The (zero-containing) min / max of every group of
+ * W diag(s) is shrunk by rho_i = 1 - 0.05 i, i = 0..10 (one binary32 multiply per end), step and
+ * zero-point follow from the shrunk range by the rule of quantize_weight_dint4, and the codes come from
+ * that function with use_given_params (values beyond the range saturate).
+ *   dint4_clipped_params: index [N] int32 (device) gives i per output channel, or NULL: uniform_index for all.
+ *   aqas_clip_search: tries every i for all channels, measures each output channel's own error
+ *     sum_m (Yq[m,n] - Y[m,n])^2 with the layer's kernels as in aqas_search, and keeps per channel the
+ *     first i with the smallest error.  index_out [N] int32, step_out / zero_out [N, K/G] the chosen
+ *     parameters, err_table NULL or [11, N] double (every candidate's errors).  Workspace as aqas_search. */
+int dint4_clipped_params(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                         int64_t group_size, const int32_t *index, int uniform_index, float *step,
+                         uint8_t *zero, void *stream);
+int aqas_clip_search(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K,
+                     int64_t ldx, int64_t ldw, const float *s, int64_t group_size, int32_t *index_out,
+                     float *step_out, uint8_t *zero_out, double *err_table, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *w4a8_status_string(int status);
 

@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     status_string, unpack_dint4, w4a8_gemm,
     dint4_weight_sums, quantize_act_int8_asym, w4a8_gemm_asym, w4a8_gemm_batched,
     quantize_value_dint4,
+    aqas_channel_absmax, aqas_scale, aqas_search, dint4_clipped_params, aqas_clip_search,
 )

@@ -25,6 +25,8 @@ EXPORTS = (
     "w4a8_gemm_workspace_bytes", "w4a8_gemm", "w4a8_status_string",
     "quantize_act_int8_asym", "dint4_weight_sums", "w4a8_gemm_asym", "w4a8_gemm_batched",
     "quantize_value_dint4",
+    "aqas_search_workspace_bytes", "aqas_channel_absmax", "aqas_scale", "aqas_search",
+    "dint4_clipped_params", "aqas_clip_search",
 )
 
 _lib = None
@@ -71,6 +73,19 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.w4a8_gemm_batched.restype = ci
     lib.quantize_value_dint4.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.quantize_value_dint4.restype = ci
+    lib.aqas_search_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.aqas_search_workspace_bytes.restype = sz
+    lib.aqas_channel_absmax.argtypes = [vp, ci, i64, i64, i64, vp, vp]
+    lib.aqas_channel_absmax.restype = ci
+    lib.aqas_scale.argtypes = [vp, vp, i64, ci, vp, vp]
+    lib.aqas_scale.restype = ci
+    lib.aqas_search.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, i64, vp, vp, vp, vp, sz, vp]
+    lib.aqas_search.restype = ci
+    lib.dint4_clipped_params.argtypes = [vp, ci, i64, i64, i64, vp, i64, vp, ci, vp, vp, vp]
+    lib.dint4_clipped_params.restype = ci
+    lib.aqas_clip_search.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp,
+                                     sz, vp]
+    lib.aqas_clip_search.restype = ci
     lib.w4a8_status_string.argtypes = [ci]
     lib.w4a8_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -260,3 +275,69 @@ def quantize_value_dint4(V: torch.Tensor, group_size: int = 0):
                                                _ptr(step), _ptr(zero), _stream()),
            "quantize_value_dint4")
     return codes, step, zero
+
+
+# ---- AQAS scale search and weight clipping (offline calibration) ---------------------------------
+def aqas_channel_absmax(A: torch.Tensor) -> torch.Tensor:
+    R, K, lda = _rows(A, "A")
+    out = torch.empty((K,), dtype=torch.float32, device=A.device)
+    _check(load_library().aqas_channel_absmax(_ptr(A), _DTYPES[A.dtype], R, K, lda, _ptr(out), _stream()),
+           "aqas_channel_absmax")
+    return out
+
+
+def aqas_scale(ax: torch.Tensor, aw: torch.Tensor, j: int) -> torch.Tensor:
+    s = torch.empty_like(ax)
+    _check(load_library().aqas_scale(_ptr(ax), _ptr(aw), ax.numel(), int(j), _ptr(s), _stream()),
+           "aqas_scale")
+    return s
+
+
+def _aqas_ws(M, N, K, group_size, device):
+    need = int(load_library().aqas_search_workspace_bytes(M, N, K, int(group_size or 0)))
+    return torch.empty((max(need, 1),), dtype=torch.uint8, device=device), need
+
+
+def aqas_search(X: torch.Tensor, W: torch.Tensor, group_size: int = 0):
+    """Grid search of the AQAS scale on calibration activations X [M,K] for weights W [N,K].
+    Returns (s float32 [K], best_j int32 [1], losses float64 [17]), all on the device."""
+    M, K, ldx = _rows(X, "X")
+    N, _, ldw = _rows(W, "W")
+    ws, need = _aqas_ws(M, N, K, group_size, X.device)
+    s = torch.empty((K,), dtype=torch.float32, device=X.device)
+    best = torch.empty((1,), dtype=torch.int32, device=X.device)
+    losses = torch.empty((17,), dtype=torch.float64, device=X.device)
+    _check(load_library().aqas_search(_ptr(X), _ptr(W), _DTYPES[X.dtype], M, N, K, ldx, ldw,
+                                      int(group_size or 0), _ptr(s), _ptr(best), _ptr(losses),
+                                      _ptr(ws), need, _stream()), "aqas_search")
+    return s, best, losses
+
+
+def dint4_clipped_params(W: torch.Tensor, s, group_size: int = 0, index=None, uniform_index: int = 0):
+    N, K, ldw = _rows(W, "W")
+    G = K if not group_size else int(group_size)
+    ng = K // G if G > 0 and K % G == 0 else 1
+    step = torch.empty((N, ng), dtype=torch.float32, device=W.device)
+    zero = torch.empty((N, ng), dtype=torch.uint8, device=W.device)
+    _check(load_library().dint4_clipped_params(_ptr(W), _DTYPES[W.dtype], N, K, ldw, _ptr(s),
+                                               int(group_size or 0), _ptr(index), int(uniform_index),
+                                               _ptr(step), _ptr(zero), _stream()), "dint4_clipped_params")
+    return step, zero
+
+
+def aqas_clip_search(X: torch.Tensor, W: torch.Tensor, s: torch.Tensor, group_size: int = 0,
+                     want_table: bool = False):
+    """Per-output-channel range factor by output error.  Returns (index int32 [N], step, zero[, err])."""
+    M, K, ldx = _rows(X, "X")
+    N, _, ldw = _rows(W, "W")
+    G = K if not group_size else int(group_size)
+    ng = K // G if G > 0 and K % G == 0 else 1
+    ws, need = _aqas_ws(M, N, K, group_size, X.device)
+    idx = torch.empty((N,), dtype=torch.int32, device=X.device)
+    step = torch.empty((N, ng), dtype=torch.float32, device=X.device)
+    zero = torch.empty((N, ng), dtype=torch.uint8, device=X.device)
+    table = torch.empty((11, N), dtype=torch.float64, device=X.device) if want_table else None
+    _check(load_library().aqas_clip_search(_ptr(X), _ptr(W), _DTYPES[X.dtype], M, N, K, ldx, ldw, _ptr(s),
+                                           int(group_size or 0), _ptr(idx), _ptr(step), _ptr(zero),
+                                           _ptr(table), _ptr(ws), need, _stream()), "aqas_clip_search")
+    return (idx, step, zero, table) if want_table else (idx, step, zero)

@@ -24,6 +24,7 @@ SOURCES = {
     "pack.hip": [],
     "gemm_decode.hip": [],
     "gemm_prefill.hip": [],
+    "aqas_search.hip": ["-ffp-contract=off"],
 }
 
 COMMON = [
@@ -64,7 +65,7 @@ def _compile(name: str, extra, verbose: bool) -> str:
 def build(verbose: bool = False, extra_flags=()) -> str:
     """Compile every HIP source for gfx950 and link the shared library.  Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as pool:
+    with ThreadPoolExecutor(max_workers=7) as pool:
         objs = list(pool.map(lambda kv: _compile(kv[0], [*kv[1], *extra_flags], verbose),
                              SOURCES.items()))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]

@@ -277,3 +277,176 @@ int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int6
 }
 
 }  // extern "C"
+
+// ---- AQAS scale search and weight clipping (Sec. 3.2, Eq. 1; App. A.4) ---------------------------
+namespace {
+
+constexpr int AQ_GRID = 16, AQ_CLIP_STEPS = 11;
+
+struct AqasWs {
+    size_t ax, aw, s, Xq, sx, codes, step, zero, Wp, Y, Yref, err, best_err, gemm, gemm_bytes, total;
+};
+
+AqasWs plan_aqas(int64_t M, int64_t N, int64_t K, int64_t G)
+{
+    AqasWs w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    const size_t ng = (size_t)(K / G);
+    w.ax = take((size_t)K * 4);
+    w.aw = take((size_t)K * 4);
+    w.s = take((size_t)K * 4);
+    w.Xq = take((size_t)M * K);
+    w.sx = take((size_t)M * 4);
+    w.codes = take((size_t)N * K);
+    w.step = take((size_t)N * ng * 4);
+    w.zero = take((size_t)N * ng);
+    w.Wp = take((size_t)N * K / 2);
+    w.Y = take((size_t)M * N * 2);
+    w.Yref = take((size_t)M * N * 4);
+    w.err = take((size_t)N * 8);
+    w.best_err = take((size_t)N * 8);
+    w.gemm_bytes = plan_workspace(M, N, K, G, W4A8_LAYOUT_TILED).total;
+    w.gemm = take(w.gemm_bytes);
+    w.total = off;
+    return w;
+}
+
+int aqas_check(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K, int64_t ldx,
+               int64_t ldw, int64_t &G, const void *workspace, size_t workspace_bytes)
+{
+    if (!valid_dtype(dtype)) return W4A8_ERR_DTYPE;
+    if (M < 1 || N < 1 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K || ldx < K || ldw < K ||
+        M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL || M * K > 0x7fffffffLL)
+        return W4A8_ERR_SHAPE;
+    if (!X || !W) return W4A8_ERR_NULL;
+    // the reference product fetches 16 bytes per lane from fp16 rows
+    if (dtype == W4A8_F16 && ((uintptr_t)X % 16 != 0 || (uintptr_t)W % 16 != 0 || ldx % 8 != 0 || ldw % 8 != 0))
+        return W4A8_ERR_SHAPE;
+    if (!workspace || (uintptr_t)workspace % WS_ALIGN != 0 || workspace_bytes < plan_aqas(M, N, K, G).total)
+        return W4A8_ERR_WORKSPACE;
+    return W4A8_OK;
+}
+
+// One evaluation of the layer with scale s: err[n] = sum_m (Yq[m,n] - Yref[m,n])^2.
+// clip_uniform >= 0: the weight ranges are shrunk by that clipping index first.
+int aqas_evaluate(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K, int64_t ldx,
+                  int64_t ldw, int64_t G, const float *s, int clip_uniform, uint8_t *ws, const AqasWs &w,
+                  void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    int8_t *Xq = (int8_t *)(ws + w.Xq);
+    float *sx = (float *)(ws + w.sx), *step = (float *)(ws + w.step);
+    uint8_t *codes = ws + w.codes, *zero = ws + w.zero, *Wp = ws + w.Wp;
+    int rc = quantize_act_int8(X, dtype, M, K, ldx, s, Xq, sx, stream);
+    if (rc != W4A8_OK) return rc;
+    if (clip_uniform >= 0) {
+        rc = launch_clip_params(W, dtype, N, K, ldw, s, G, nullptr, clip_uniform, step, zero, st);
+        if (rc != W4A8_OK) return rc;
+    }
+    rc = quantize_weight_dint4(W, dtype, N, K, ldw, s, G, clip_uniform >= 0 ? 1 : 0, codes, step, zero, stream);
+    if (rc != W4A8_OK) return rc;
+    rc = pack_dint4(codes, N, K, Wp, W4A8_LAYOUT_TILED, stream);
+    if (rc != W4A8_OK) return rc;
+    rc = w4a8_gemm(Xq, sx, M, Wp, W4A8_LAYOUT_TILED, step, zero, N, K, G, ws + w.Y, W4A8_F16, N, nullptr,
+                   w.gemm_bytes ? ws + w.gemm : nullptr, w.gemm_bytes, stream);
+    if (rc != W4A8_OK) return rc;
+    return launch_output_sq_error(ws + w.Y, W4A8_F16, N, (const float *)(ws + w.Yref), M, N,
+                                  (double *)(ws + w.err), st);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t aqas_search_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size)
+{
+    int64_t G = group_size;
+    if (M < 1 || N < 1 || !resolve_group(K, G) || K % TILE_K != 0 || G % TILE_K != 0 || N % TILE_N != 0)
+        return 0;
+    return plan_aqas(M, N, K, G).total;
+}
+
+int aqas_channel_absmax(const void *A, int dtype, int64_t R, int64_t K, int64_t lda, float *out,
+                        void *stream)
+{
+    if (!valid_dtype(dtype)) return W4A8_ERR_DTYPE;
+    if (R < 0 || K < 1 || lda < K || (R + 255) / 256 > 65535) return W4A8_ERR_SHAPE;
+    if (!out || (R > 0 && !A)) return W4A8_ERR_NULL;
+    return launch_channel_absmax(A, dtype, R, K, lda, out, (hipStream_t)stream);
+}
+
+int aqas_scale(const float *ax, const float *aw, int64_t K, int j, float *s, void *stream)
+{
+    if (K < 1 || j < 0 || j > AQ_GRID) return W4A8_ERR_SHAPE;
+    if (!ax || !aw || !s) return W4A8_ERR_NULL;
+    return launch_aqas_scale(ax, aw, K, j, nullptr, s, (hipStream_t)stream);
+}
+
+int aqas_search(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K, int64_t ldx,
+                int64_t ldw, int64_t group_size, float *s_out, int32_t *best_j, double *losses,
+                void *workspace, size_t workspace_bytes, void *stream)
+{
+    int64_t G = group_size;
+    int rc = aqas_check(X, W, dtype, M, N, K, ldx, ldw, G, workspace, workspace_bytes);
+    if (rc != W4A8_OK) return rc;
+    if (!s_out || !best_j || !losses) return W4A8_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    const AqasWs w = plan_aqas(M, N, K, G);
+    float *ax = (float *)(ws + w.ax), *aw = (float *)(ws + w.aw), *s = (float *)(ws + w.s);
+    if ((rc = launch_channel_absmax(X, dtype, M, K, ldx, ax, st)) != W4A8_OK) return rc;
+    if ((rc = launch_channel_absmax(W, dtype, N, K, ldw, aw, st)) != W4A8_OK) return rc;
+    if ((rc = launch_ref_gemm(X, W, dtype, M, N, K, ldx, ldw, (float *)(ws + w.Yref), st)) != W4A8_OK) return rc;
+    for (int j = 0; j <= AQ_GRID; ++j) {
+        if ((rc = launch_aqas_scale(ax, aw, K, j, nullptr, s, st)) != W4A8_OK) return rc;
+        if ((rc = aqas_evaluate(X, W, dtype, M, N, K, ldx, ldw, G, s, -1, ws, w, stream)) != W4A8_OK) return rc;
+        if ((rc = launch_loss_sum((const double *)(ws + w.err), N, losses, j, st)) != W4A8_OK) return rc;
+    }
+    if ((rc = launch_argmin(losses, AQ_GRID + 1, best_j, st)) != W4A8_OK) return rc;
+    return launch_aqas_scale(ax, aw, K, 0, best_j, s_out, st);
+}
+
+int dint4_clipped_params(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                         int64_t group_size, const int32_t *index, int uniform_index, float *step,
+                         uint8_t *zero, void *stream)
+{
+    if (!valid_dtype(w_dtype)) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (N < 0 || K < 1 || ldw < K || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (!index && (uniform_index < 0 || uniform_index >= AQ_CLIP_STEPS)) return W4A8_ERR_SHAPE;
+    if (N == 0) return W4A8_OK;
+    if (!W || !step || !zero) return W4A8_ERR_NULL;
+    return launch_clip_params(W, w_dtype, N, K, ldw, s, G, index, uniform_index, step, zero,
+                              (hipStream_t)stream);
+}
+
+int aqas_clip_search(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K,
+                     int64_t ldx, int64_t ldw, const float *s, int64_t group_size, int32_t *index_out,
+                     float *step_out, uint8_t *zero_out, double *err_table, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    int64_t G = group_size;
+    int rc = aqas_check(X, W, dtype, M, N, K, ldx, ldw, G, workspace, workspace_bytes);
+    if (rc != W4A8_OK) return rc;
+    if (!index_out || !step_out || !zero_out) return W4A8_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    const AqasWs w = plan_aqas(M, N, K, G);
+    if ((rc = launch_ref_gemm(X, W, dtype, M, N, K, ldx, ldw, (float *)(ws + w.Yref), st)) != W4A8_OK) return rc;
+    for (int i = 0; i < AQ_CLIP_STEPS; ++i) {
+        if ((rc = aqas_evaluate(X, W, dtype, M, N, K, ldx, ldw, G, s, i, ws, w, stream)) != W4A8_OK) return rc;
+        if ((rc = launch_clip_select((const double *)(ws + w.err), N, i, (double *)(ws + w.best_err),
+                                     index_out, err_table, st)) != W4A8_OK)
+            return rc;
+    }
+    return launch_clip_params(W, dtype, N, K, ldw, s, G, index_out, 0, step_out, zero_out, st);
+}
+
+}  // extern "C"
+

@@ -149,6 +149,23 @@ int launch_acc_zero_point(int32_t *acc, const int32_t *zx, const int32_t *wsum, 
 int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
                         const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
                         uint8_t *zero, hipStream_t st);
+// step / zero of the ranges shrunk by rho = 1 - 0.05 i, i = idx[n] (or `uniform` when idx is null)
+int launch_clip_params(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                       int64_t G, const int32_t *idx, int uniform, float *step, uint8_t *zero,
+                       hipStream_t st);
+// AQAS scale search helpers (aqas_search.hip)
+int launch_channel_absmax(const void *A, int dtype, int64_t R, int64_t K, int64_t lda, float *out,
+                          hipStream_t st);
+int launch_aqas_scale(const float *ax, const float *aw, int64_t K, int j, const int32_t *j_dev,
+                      float *s, hipStream_t st);
+int launch_ref_gemm(const void *X, const void *W, int dtype, int64_t M, int64_t N, int64_t K,
+                    int64_t ldx, int64_t ldw, float *Y, hipStream_t st);
+int launch_output_sq_error(const void *Y, int y_dtype, int64_t ldy, const float *Yref, int64_t M,
+                           int64_t N, double *err, hipStream_t st);
+int launch_loss_sum(const double *err, int64_t N, double *losses, int slot, hipStream_t st);
+int launch_argmin(const double *losses, int count, int32_t *best, hipStream_t st);
+int launch_clip_select(const double *err, int64_t N, int i, double *best_err, int32_t *best_idx,
+                       double *err_table, hipStream_t st);
 // Value cache: V [batch, T, D] (token stride ld_t, head stride ld_b) -> codes [batch * D, T]
 int launch_value_quant(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D, int64_t ld_t,
                        int64_t ld_b, int64_t G, uint8_t *codes, float *step, uint8_t *zero,

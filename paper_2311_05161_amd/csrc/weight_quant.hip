@@ -178,6 +178,64 @@ int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_
     }
 }
 
+// ---- clipped ranges (App. A.4: after the scale search the weights are additionally clipped) ------
+// step / zero of the (zero-containing) min-max range of each (row, group) of W diag(s), shrunk by
+// rho = 1 - 0.05 i: i = idx[n] per output row, or the same `uniform` index for all rows.  The codes
+// then come from quantize_weight_dint4 with these parameters given (values beyond the shrunk range
+// saturate at its end levels).  One wave per (row, group).
+template <typename T>
+__global__ __launch_bounds__(WQ_THREADS) void clip_params_kernel(
+    const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s, int64_t G,
+    const int32_t *__restrict__ idx, int uniform, float *__restrict__ step, uint8_t *__restrict__ zero)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t ng = K / G;
+    const int64_t seg = (int64_t)blockIdx.x * (WQ_THREADS / WAVE) + (threadIdx.x >> 6);
+    if (seg >= N * ng) return;
+    const int64_t n = seg / ng, g = seg % ng;
+    const T *w = W + n * ldw + g * G;
+    const float *sg = s ? s + g * G : nullptr;
+    float lo = 0.0f, hi = 0.0f;
+    for (int64_t k = lane; k < G; k += WAVE) {
+        const float v = to_f32(w[k]);
+        const float x = sg ? v * sg[k] : v;
+        lo = fminf(lo, x);
+        hi = fmaxf(hi, x);
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+    const float rho = 1.0f - 0.05f * (float)(idx ? idx[n] : uniform);
+    lo = lo * rho;
+    hi = hi * rho;
+    float st, istep;
+    int z;
+    range_params(lo, hi, st, istep, z);
+    if (lane == 0) {
+        step[seg] = st;
+        zero[seg] = (uint8_t)z;
+    }
+}
+
+int launch_clip_params(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                       int64_t G, const int32_t *idx, int uniform, float *step, uint8_t *zero,
+                       hipStream_t st)
+{
+    const int64_t segs = N * (K / G);
+    if (segs == 0) return W4A8_OK;
+    const dim3 grid((unsigned)((segs + (WQ_THREADS / WAVE) - 1) / (WQ_THREADS / WAVE)));
+#define W4A8_CP_LAUNCH(T_)                                                                        \
+    hipLaunchKernelGGL((clip_params_kernel<T_>), grid, dim3(WQ_THREADS), 0, st, (const T_ *)W, N, K, \
+                       ldw, s, G, idx, uniform, step, zero)
+    switch (w_dtype) {
+        case W4A8_F32: W4A8_CP_LAUNCH(float); break;
+        case W4A8_F16: W4A8_CP_LAUNCH(__half); break;
+        case W4A8_BF16: W4A8_CP_LAUNCH(bf16_t); break;
+        default: return W4A8_ERR_DTYPE;
+    }
+#undef W4A8_CP_LAUNCH
+    return hip_status(hipGetLastError());
+}
+
 // ---- 4-bit Value cache (Sec. 5.1; App. A.1: channel-wise along the dimension the product with the
 // attention map accumulates over, i.e. the tokens) -------------------------------------------------
 // V [batch, T, D] is stored token-major, as a cache is appended to; the product wants V^T.  A

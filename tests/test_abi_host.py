@@ -148,6 +148,36 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert batched(zx=P, wsum=Z) == b.ERR_NULL       # a zero-point needs the weight sums
     assert batched(batch=0) == b.OK
 
+    # AQAS scale search and clipping
+    assert c.aqas_channel_absmax(P, 9, 4, 128, 128, P, Z) == b.ERR_DTYPE
+    assert c.aqas_channel_absmax(P, b.F16, 4, 128, 64, P, Z) == b.ERR_SHAPE
+    assert c.aqas_channel_absmax(P, b.F16, 4, 128, 128, Z, Z) == b.ERR_NULL
+    assert c.aqas_scale(P, P, 128, 17, P, Z) == b.ERR_SHAPE          # grid points 0..16
+    assert c.aqas_scale(P, Z, 128, 3, P, Z) == b.ERR_NULL
+    need = lib.load_library().aqas_search_workspace_bytes(32, 64, 256, 0)
+    assert need > 32 * 256 + 64 * 256 + 64 * 128 + 32 * 64 * 6
+    assert lib.load_library().aqas_search_workspace_bytes(32, 60, 256, 0) == 0   # N % 16
+
+    def search(dt=b.F16, M=32, N=64, K=256, ldx=256, G=0, X=P, ws=ctypes.c_void_p(0x10000), wsb=1 << 30,
+               s_out=P):
+        return c.aqas_search(X, P, dt, M, N, K, ldx, 256, G, s_out, P, P, ws, wsb, Z)
+    assert search(dt=7) == b.ERR_DTYPE
+    assert search(N=60) == b.ERR_SHAPE
+    assert search(K=200) == b.ERR_SHAPE
+    assert search(ldx=100) == b.ERR_SHAPE
+    assert search(ldx=260) == b.ERR_SHAPE                            # fp16 rows must stay 16-byte aligned
+    assert search(M=0) == b.ERR_SHAPE
+    assert search(X=Z) == b.ERR_NULL
+    assert search(ws=Z) == b.ERR_WORKSPACE
+    assert search(wsb=1000) == b.ERR_WORKSPACE
+    assert search(s_out=Z) == b.ERR_NULL
+    assert c.dint4_clipped_params(P, b.F16, 16, 128, 128, Z, 0, Z, 11, P, P, Z) == b.ERR_SHAPE   # i = 0..10
+    assert c.dint4_clipped_params(P, b.F16, 16, 128, 128, Z, 48, Z, 0, P, P, Z) == b.ERR_SHAPE
+    assert c.dint4_clipped_params(P, b.F16, 16, 128, 128, Z, 0, Z, 0, Z, P, Z) == b.ERR_NULL
+    assert c.aqas_clip_search(P, P, b.F16, 32, 64, 256, 256, 256, P, 0, Z, P, P, Z,
+                              ctypes.c_void_p(0x10000), 1 << 30, Z) == b.ERR_NULL
+    assert c.aqas_clip_search(P, P, b.F16, 32, 64, 256, 256, 256, P, 0, P, P, P, Z, Z, 0, Z) == b.ERR_WORKSPACE
+
 
 def test_product_path_has_no_cpu_fallback(lib, tmp_path):
     with pytest.raises(FileNotFoundError):
