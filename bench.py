@@ -292,6 +292,83 @@ def main():
             prefill.append({"workload": f"{name} M={Mp} K={Kp} N={Np} G={Gp or Kp}", "ms": round(ms, 4),
                             "TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
 
+    # ------------------------------------------------------------------ quantizer kernels and C5 end to end (side)
+    quant_side = None
+    if not args.no_prefill:
+        g = torch.Generator(device=dev)
+        g.manual_seed(20231107)
+        Mq, Kq, Nq = 4096, 9216, 36864                      # C5
+        Xb = torch.randn((Mq, Kq), device=dev, generator=g).to(torch.float16)
+        sb = torch.rand((Kq,), device=dev, generator=g) * 1.5 + 0.5
+        Xqb = torch.empty((Mq, Kq), dtype=torch.int8, device=dev)
+        sxb = torch.empty((Mq,), dtype=torch.float32, device=dev)
+        aq_b = (P(Xb), w.F16, Mq, Kq, Kq, P(sb), P(Xqb), P(sxb), st)
+        for _ in range(3):
+            lib.quantize_act_int8(*aq_b)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(20):
+            lib.quantize_act_int8(*aq_b)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        aq_ms = e0.elapsed_time(e1) / 20
+        aq_bytes = Mq * Kq * 3 + 4 * Kq + 4 * Mq
+        # end to end on C5: activation quantization + GEMM back to back on one stream
+        wpb = torch.randint(0, 256, (Nq * Kq // 2,), dtype=torch.uint8, device=dev, generator=g)
+        stb = torch.rand((Nq, 1), device=dev, generator=g) * 0.01 + 0.001
+        zb = torch.randint(0, 14, (Nq, 1), dtype=torch.uint8, device=dev, generator=g)
+        yb = torch.empty((Mq, Nq), dtype=torch.float16, device=dev)
+        wsb_n = w.gemm_workspace_bytes(Mq, Nq, Kq, 0)
+        wsb = torch.empty((max(1, wsb_n),), dtype=torch.uint8, device=dev)
+        gm_b = (P(Xqb), P(sxb), Mq, P(wpb), w.LAYOUT_TILED, P(stb), P(zb), Nq, Kq, 0, P(yb), w.F16, Nq, None,
+                P(wsb), wsb_n, st)
+        for _ in range(2):
+            assert lib.quantize_act_int8(*aq_b) == 0 and lib.w4a8_gemm(*gm_b) == 0
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(10):
+            lib.quantize_act_int8(*aq_b)
+            lib.w4a8_gemm(*gm_b)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        e2e_ms = e0.elapsed_time(e1) / 10
+        del Xb, Xqb, wpb, yb
+        # weight quantization + packing of a C4 up-projection matrix (offline)
+        Nw, Kw = 13824, 5120
+        Wb = (torch.randn((Nw, Kw), device=dev, generator=g) * 0.02).to(torch.float16)
+        sw = torch.rand((Kw,), device=dev, generator=g) * 1.5 + 0.5
+        for _ in range(2):
+            cb, _, _ = w.quantize_weight_dint4(Wb, sw, 128)
+            w.pack_dint4(cb, w.LAYOUT_TILED)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(10):
+            cb, _, _ = w.quantize_weight_dint4(Wb, sw, 128)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wq_ms = e0.elapsed_time(e1) / 10
+        e0.record(stream)
+        for _ in range(10):
+            w.pack_dint4(cb, w.LAYOUT_TILED)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        pk_ms = e0.elapsed_time(e1) / 10
+        wq_bytes = Nw * Kw * 3 + 5 * Nw * Kw // 128 + 4 * Kw
+        quant_side = {"what": "the quantizer kernels against the HBM roofline (bytes: input read + output written), "
+                              "and the C5 layer end to end (quantize_act_int8 + w4a8_gemm on one stream)",
+                      "act_quant_C5": {"workload": f"M={Mq} K={Kq} fp16", "ms": round(aq_ms, 4),
+                                       "GBps": round(aq_bytes / aq_ms / 1e6, 1),
+                                       "frac_of_hbm_peak": round(aq_bytes / aq_ms / 1e6 / HBM_PEAK_GBS, 4)},
+                      "weight_quant_C4": {"workload": f"N={Nw} K={Kw} fp16 G=128", "ms": round(wq_ms, 4),
+                                          "GBps": round(wq_bytes / wq_ms / 1e6, 1),
+                                          "frac_of_hbm_peak": round(wq_bytes / wq_ms / 1e6 / HBM_PEAK_GBS, 4)},
+                      "pack_tiled_C4": {"ms": round(pk_ms, 4), "GBps": round(Nw * Kw * 1.5 / pk_ms / 1e6, 1)},
+                      "C5_end_to_end": {"workload": f"M={Mq} K={Kq} N={Nq} per-channel", "ms": round(e2e_ms, 4),
+                                        "TOPS": round(2.0 * Mq * Nq * Kq / (e2e_ms * 1e-3) / 1e12, 1),
+                                        "frac_of_int8_peak": round(2.0 * Mq * Nq * Kq / (e2e_ms * 1e-3) / 1e12
+                                                                   / INT8_PEAK_TOPS, 4)}}
+        del Wb, cb
+
     # ------------------------------------------------------------------ asymmetric activations (side)
     asym_side = []
     if not args.no_prefill:
@@ -398,7 +475,7 @@ def main():
         "asymmetric_activations": {"what": "w4a8_gemm_asym (token zero-point taken out of the int32 "
                                            "accumulators), same shapes and protocol as the lists above",
                                    "shapes": asym_side},
-        "value_cache": value_side, "aqas_search": search_side,
+        "quantizers": quant_side, "value_cache": value_side, "aqas_search": search_side,
     }
     print(json.dumps(out), flush=True)
 

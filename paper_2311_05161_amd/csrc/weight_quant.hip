@@ -133,6 +133,58 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
     }
 }
 
+// Groups of 128 or 256 columns: a wave takes 512 consecutive columns of a row (8 per lane, one
+// 16-byte load), i.e. 4 or 2 whole groups, each reduced over its own LANES = G / 8 lanes; the
+// elements stay in registers between the range and the codes, so W is read once.
+template <typename T, int LANES>
+__global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
+    const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
+    int use_given, uint8_t *__restrict__ codes, float *__restrict__ step, uint8_t *__restrict__ zero)
+{
+    constexpr int G = LANES * 8;
+    const int lane = threadIdx.x & 63;
+    const int64_t chunks = (K + 511) / 512;
+    const int64_t seg = (int64_t)blockIdx.x * (WQ_THREADS / WAVE) + (threadIdx.x >> 6);   // (row, chunk)
+    if (seg >= N * chunks) return;
+    const int64_t n = seg / chunks, c = seg - n * chunks;
+    const int64_t k = c * 512 + lane * 8;
+    if (k >= K) return;   // whole groups of LANES lanes leave together (K % G == 0)
+    float v[8], x[8];
+    loadv<T, 8>(W + n * ldw + k, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = s ? v[j] * s[k + j] : v[j];
+    const int64_t pidx = n * (K / G) + k / G;
+    float st, istep;
+    int z;
+    if (use_given) {
+        st = step[pidx];
+        z = zero[pidx];
+        istep = 1.0f / st;
+    } else {
+        float lo = 0.0f, hi = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            lo = fminf(lo, x[j]);
+            hi = fmaxf(hi, x[j]);
+        }
+#pragma unroll
+        for (int off = LANES / 2; off >= 1; off >>= 1) {
+            lo = fminf(lo, __shfl_xor(lo, off, WAVE));
+            hi = fmaxf(hi, __shfl_xor(hi, off, WAVE));
+        }
+        range_params(lo, hi, st, istep, z);
+        if ((lane & (LANES - 1)) == 0) {
+            step[pidx] = st;
+            zero[pidx] = (uint8_t)z;
+        }
+    }
+    uint32_t q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = dint4_code(x[j], istep, z);
+    *reinterpret_cast<uint2 *>(codes + n * K + k) =
+        make_uint2(q[0] | q[1] << 8 | q[2] << 16 | q[3] << 24, q[4] | q[5] << 8 | q[6] << 16 | q[7] << 24);
+}
+
 template <typename T>
 static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, const float *s,
                                  int64_t G, int use_given, uint8_t *codes, float *step,
@@ -149,7 +201,17 @@ static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, 
 #define W4A8_WQ_LAUNCH(V_)                                                                        \
     hipLaunchKernelGGL((weight_quant_kernel<T, V_>), dim3((unsigned)blocks), dim3(WQ_THREADS), 0, \
                        st, W, N, K, ldw, s, G, use_given, codes, step, zero)
-    if (G >= 512 && aligned(8)) {
+    if ((G == 128 || G == 256) && aligned(8)) {
+        const int64_t wsegs = N * ((K + 511) / 512);
+        const int64_t wblocks = (wsegs + (WQ_THREADS / WAVE) - 1) / (WQ_THREADS / WAVE);
+        if (wblocks > 0x7fffffffLL) return W4A8_ERR_SHAPE;
+        if (G == 128)
+            hipLaunchKernelGGL((weight_quant_small_groups_kernel<T, 16>), dim3((unsigned)wblocks),
+                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero);
+        else
+            hipLaunchKernelGGL((weight_quant_small_groups_kernel<T, 32>), dim3((unsigned)wblocks),
+                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero);
+    } else if (G >= 512 && aligned(8)) {
         W4A8_WQ_LAUNCH(8);
     } else if (aligned(2)) {
         W4A8_WQ_LAUNCH(2);
