@@ -5,3 +5,4 @@ import this package.  It never imports the GPU package and shares no code with i
 """
 from .w4a8_oracle import *  # noqa: F401,F403
 from . import aqas_search  # noqa: F401,E402
+from . import formats  # noqa: F401,E402
