@@ -457,6 +457,13 @@ def main():
                        "loss_at_best_over_loss_at_alpha_0_and_1": [round(float(ls.min() / ls[0]), 4),
                                                                    round(float(ls.min() / ls[16]), 4)],
                        "channels_clipped": int((clip_idx > 0).sum().item())}
+        # the underflow / rounding split of the output error (weight quantization alone) on the same layer
+        terms = {}
+        for fname, fid in (("int4", w.FMT_INT4), ("dint4", w.FMT_DINT4), ("dint3", w.FMT_DINT3)):
+            tt = w.dint_error_terms(Xc_d, Wd, s_best, G, fid).cpu().numpy()
+            terms[fname] = {"underflow": float(f"{tt[0]:.5g}"), "rounding": float(f"{tt[1]:.5g}"),
+                            "cross": float(f"{tt[2]:.5g}"), "underflowing_weights": int(tt[3])}
+        search_side["output_error_split"] = terms
 
     out = {
         "metric": METRIC, "value": round(weight_gbs, 1), "unit": "GB/s", "n_gpus": 1,

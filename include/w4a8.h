@@ -58,6 +58,9 @@ typedef enum { W4A8_F32 = 0, W4A8_F16 = 1, W4A8_BF16 = 2 } w4a8_dtype;
  */
 enum { W4A8_LAYOUT_CANONICAL = 0, W4A8_LAYOUT_TILED = 1 };
 
+/* Weight formats sharing the 4-bit code space (see quantize_weight_format). */
+enum { W4A8_FMT_DINT4 = 0, W4A8_FMT_INT4 = 1, W4A8_FMT_DINT3 = 2 };
+
 /* Per-token INT8 activation quantization with the AQAS scale folded in
  * (Eq. 1, factor Q(diag(s)^-1 X); token-wise 8-bit, App. A.1):
  *     t[m,k] = X[m,k] * (1 / s[k]);  a[m] = max_k |t[m,k]|;
@@ -244,6 +247,49 @@ int aqas_clip_search(const void *X, const void *W, int dtype, int64_t M, int64_t
                      int64_t ldx, int64_t ldw, const float *s, int64_t group_size, int32_t *index_out,
                      float *step_out, uint8_t *zero_out, double *err_table, void *workspace,
                      size_t workspace_bytes, void *stream);
+
+/* ---- Weight-format variants that the paper compares dINT4 with (3-bit dINT, Table 10; ordinary INT4,
+ * Tables 11-14), in one 4-bit code space so that pack_dint4 and the GEMM serve all of them:
+ *     W4A8_FMT_DINT4  p = 13 integer steps (codes 0..13) + special levels +step/2 (14), -step/2 (15)  (Eq. 5)
+ *     W4A8_FMT_DINT3  p = 2^3 - 3 = 5 (codes 0..5) + the same special codes 14, 15
+ *     W4A8_FMT_INT4   p = 15 (codes 0..15 all integer levels, zero-point 0..15), no special levels
+ * Rule as quantize_weight_dint4 with 13 replaced by p (and the two special cases dropped for INT4).
+ * w4a8_gemm_format is w4a8_gemm with the meaning of codes 14 / 15 chosen by `format`. */
+int quantize_weight_format(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                           int64_t group_size, int format, int use_given_params, uint8_t *codes,
+                           float *step, uint8_t *zero, void *stream);
+/* pack_dint4 / unpack_dint4 for a format.  The canonical layout stores the codes as they are; in the
+ * tiled layout INT4's codes 14 and 15 are the integer pair of the eighth base level, lower member first
+ * (nibble e = (c >> 1) | ((c & 1) << 3) for all sixteen codes), whereas the dINT formats keep the
+ * special pair as described at W4A8_LAYOUT_TILED. */
+int pack_format(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout, int format,
+                void *stream);
+int unpack_format(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout, int format,
+                  void *stream);
+int w4a8_gemm_format(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wp, int layout,
+                     const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t group_size,
+                     int format, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/* 3-bit storage of dINT3 codes: 0..5 stay, special codes 14 / 15 become 6 / 7; code i of each group of
+ * eight consecutive codes of a row sits at bits 3i..3i+2 of a little-endian 24-bit word (three bytes).
+ *   codes [N, K] in the 4-bit code space, K % 8 == 0      packed [N, 3K/8] bytes
+ * unpack_dint3 restores the 4-bit code space (ready for pack_dint4 and the GEMM). */
+int pack_dint3(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, void *stream);
+int unpack_dint3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, void *stream);
+
+/* The error split of Sec. 4.1 (Eq. 4) for weight quantization in `format`: with W' = W diag(s), Wq its
+ * dequantized codes and X' = X diag(s)^-1 (unquantized), Delta_u = Wq - W' on the weights whose
+ * quantized value is zero ("underflow"), Delta_r on the others ("rounding"):
+ *     terms[0] = sum (X' Delta_u^T)^2    terms[1] = sum (X' Delta_r^T)^2
+ *     terms[2] = sum 2 (X' Delta_u^T)(X' Delta_r^T)        terms[3] = number of underflowing weights
+ * (their first three add up to the squared output error of weight quantization alone).
+ *   X [M, ldx], W [N, ldw] of their dtypes; terms out [4] double (device);
+ *   workspace of dint_error_terms_workspace_bytes(M, N, K, group_size) bytes, 256-byte aligned. */
+size_t dint_error_terms_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size);
+int dint_error_terms(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const void *W,
+                     int w_dtype, int64_t N, int64_t ldw, const float *s, int64_t group_size, int format,
+                     double *terms, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *w4a8_status_string(int status);

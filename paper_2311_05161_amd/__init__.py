@@ -9,5 +9,7 @@ from .binding import (  # noqa: F401
     status_string, unpack_dint4, w4a8_gemm,
     dint4_weight_sums, quantize_act_int8_asym, w4a8_gemm_asym, w4a8_gemm_batched,
     quantize_value_dint4,
+    FMT_DINT3, FMT_DINT4, FMT_INT4, quantize_weight_format, w4a8_gemm_format, pack_dint3, unpack_dint3, pack_format, unpack_format,
+    dint_error_terms,
     aqas_channel_absmax, aqas_scale, aqas_search, dint4_clipped_params, aqas_clip_search,
 )

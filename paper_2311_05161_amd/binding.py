@@ -27,7 +27,11 @@ EXPORTS = (
     "quantize_value_dint4",
     "aqas_search_workspace_bytes", "aqas_channel_absmax", "aqas_scale", "aqas_search",
     "dint4_clipped_params", "aqas_clip_search",
+    "quantize_weight_format", "w4a8_gemm_format", "pack_dint3", "unpack_dint3", "pack_format",
+    "unpack_format",
+    "dint_error_terms_workspace_bytes", "dint_error_terms",
 )
+FMT_DINT4, FMT_INT4, FMT_DINT3 = 0, 1, 2
 
 _lib = None
 
@@ -86,6 +90,23 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.aqas_clip_search.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp,
                                      sz, vp]
     lib.aqas_clip_search.restype = ci
+    lib.quantize_weight_format.argtypes = [vp, ci, i64, i64, i64, vp, i64, ci, ci, vp, vp, vp, vp]
+    lib.quantize_weight_format.restype = ci
+    lib.w4a8_gemm_format.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, i64, vp, vp,
+                                     sz, vp]
+    lib.w4a8_gemm_format.restype = ci
+    lib.pack_format.argtypes = [vp, i64, i64, vp, ci, ci, vp]
+    lib.pack_format.restype = ci
+    lib.unpack_format.argtypes = [vp, i64, i64, vp, ci, ci, vp]
+    lib.unpack_format.restype = ci
+    lib.pack_dint3.argtypes = [vp, i64, i64, vp, vp]
+    lib.pack_dint3.restype = ci
+    lib.unpack_dint3.argtypes = [vp, i64, i64, vp, vp]
+    lib.unpack_dint3.restype = ci
+    lib.dint_error_terms_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.dint_error_terms_workspace_bytes.restype = sz
+    lib.dint_error_terms.argtypes = [vp, ci, i64, i64, i64, vp, ci, i64, i64, vp, i64, ci, vp, vp, sz, vp]
+    lib.dint_error_terms.restype = ci
     lib.w4a8_status_string.argtypes = [ci]
     lib.w4a8_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -341,3 +362,75 @@ def aqas_clip_search(X: torch.Tensor, W: torch.Tensor, s: torch.Tensor, group_si
                                            int(group_size or 0), _ptr(idx), _ptr(step), _ptr(zero),
                                            _ptr(table), _ptr(ws), need, _stream()), "aqas_clip_search")
     return (idx, step, zero, table) if want_table else (idx, step, zero)
+
+
+# ---- weight-format variants and the error split -----------------------------------------------------
+def quantize_weight_format(W: torch.Tensor, s=None, group_size: int = 0, fmt: int = FMT_DINT4):
+    N, K, ldw = _rows(W, "W")
+    G = K if not group_size else int(group_size)
+    ngr = K // G if G > 0 and K % G == 0 else 1
+    step = torch.empty((N, ngr), dtype=torch.float32, device=W.device)
+    zero = torch.empty((N, ngr), dtype=torch.uint8, device=W.device)
+    codes = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    _check(load_library().quantize_weight_format(_ptr(W), _DTYPES[W.dtype], N, K, ldw, _ptr(s),
+                                                 int(group_size or 0), int(fmt), 0, _ptr(codes), _ptr(step),
+                                                 _ptr(zero), _stream()), "quantize_weight_format")
+    return codes, step, zero
+
+
+def w4a8_gemm_format(Xq, sx, Wp, step, zero, N: int, K: int, group_size: int = 0, fmt: int = FMT_DINT4,
+                     out_dtype=torch.float16, want_acc=False):
+    M = Xq.shape[0]
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    G = K if not group_size else int(group_size)
+    acc = torch.empty((M, N, K // G), dtype=torch.int32, device=Xq.device) if want_acc else None
+    need = gemm_workspace_bytes(M, N, K, group_size, LAYOUT_TILED)
+    ws = torch.empty((max(need, 1),), dtype=torch.uint8, device=Xq.device)
+    _check(load_library().w4a8_gemm_format(_ptr(Xq), _ptr(sx), M, _ptr(Wp), LAYOUT_TILED, _ptr(step),
+                                           _ptr(zero), N, K, int(group_size or 0), int(fmt), _ptr(Y),
+                                           _DTYPES[Y.dtype], N, _ptr(acc), _ptr(ws), need, _stream()),
+           "w4a8_gemm_format")
+    return (Y, acc) if want_acc else Y
+
+
+def pack_format(codes: torch.Tensor, layout: int = LAYOUT_TILED, fmt: int = FMT_DINT4) -> torch.Tensor:
+    N, K = codes.shape
+    out = torch.empty((N * K // 2,), dtype=torch.uint8, device=codes.device)
+    _check(load_library().pack_format(_ptr(codes), N, K, _ptr(out), int(layout), int(fmt), _stream()),
+           "pack_format")
+    return out
+
+
+def unpack_format(packed: torch.Tensor, N: int, K: int, layout: int = LAYOUT_TILED,
+                  fmt: int = FMT_DINT4) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(load_library().unpack_format(_ptr(packed), N, K, _ptr(out), int(layout), int(fmt), _stream()),
+           "unpack_format")
+    return out
+
+
+def pack_dint3(codes: torch.Tensor) -> torch.Tensor:
+    N, K = codes.shape
+    out = torch.empty((N, 3 * K // 8), dtype=torch.uint8, device=codes.device)
+    _check(load_library().pack_dint3(_ptr(codes), N, K, _ptr(out), _stream()), "pack_dint3")
+    return out
+
+
+def unpack_dint3(packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(load_library().unpack_dint3(_ptr(packed), N, K, _ptr(out), _stream()), "unpack_dint3")
+    return out
+
+
+def dint_error_terms(X: torch.Tensor, W: torch.Tensor, s=None, group_size: int = 0, fmt: int = FMT_DINT4):
+    """The three terms of the underflow / rounding split of the output error and the number of
+    underflowing weights, float64 [4] on the device."""
+    M, K, ldx = _rows(X, "X")
+    N, _, ldw = _rows(W, "W")
+    need = int(load_library().dint_error_terms_workspace_bytes(M, N, K, int(group_size or 0)))
+    ws = torch.empty((max(need, 1),), dtype=torch.uint8, device=X.device)
+    terms = torch.empty((4,), dtype=torch.float64, device=X.device)
+    _check(load_library().dint_error_terms(_ptr(X), _DTYPES[X.dtype], M, K, ldx, _ptr(W), _DTYPES[W.dtype],
+                                           N, ldw, _ptr(s), int(group_size or 0), int(fmt), _ptr(terms),
+                                           _ptr(ws), need, _stream()), "dint_error_terms")
+    return terms

@@ -58,9 +58,12 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
                 const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
                 const int32_t *wsum, const int32_t *tsum, int64_t N, int64_t K, int64_t group_size,
                 void *Y, int y_dtype, int64_t ldy,
-                int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+                int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream,
+                int format = W4A8_FMT_DINT4)
 {
     if (!valid_layout(layout)) return W4A8_ERR_DTYPE;
+    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    const int plain = format == W4A8_FMT_INT4;   // dINT3 lives in dINT4's code space: nothing to change
     if (y_dtype != W4A8_F16 && y_dtype != W4A8_BF16) return W4A8_ERR_DTYPE;
     int64_t G = group_size;
     if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
@@ -88,7 +91,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
     const uint8_t *Wt = Wp;
     if (layout == W4A8_LAYOUT_CANONICAL) {
         uint8_t *tiled = wsb + ws.repack_off;
-        const int rc = launch_repack_canonical_to_tiled(Wp, N, K, tiled, st);
+        const int rc = launch_repack_canonical_to_tiled(Wp, N, K, tiled, st, plain);
         if (rc != W4A8_OK) return rc;
         Wt = tiled;
     }
@@ -98,7 +101,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
             if (rc != W4A8_OK) return rc;
         }
         const int rc = launch_gemv(Xq, sx, zp, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy,
-                                   acc_out, (float *)(wsb + ws.part_off), 1, st);
+                                   acc_out, (float *)(wsb + ws.part_off), 1, st, plain);
         if (rc != W4A8_OK || !zx || !acc_out) return rc;
         return launch_acc_zero_point(acc_out, zx, wsum, M, N * (K / G), st);
     }
@@ -107,7 +110,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
         if (rc != W4A8_OK) return rc;
     }
     const int rc = launch_gemm(Xq, sx, zp, (int32_t *)(wsb + ws.rs_off), M, Wt, step, zero, N,
-                               K, G, Y, y_dtype, ldy, acc_out, (float *)(wsb + ws.part_off), st);
+                               K, G, Y, y_dtype, ldy, acc_out, (float *)(wsb + ws.part_off), st, plain);
     if (rc != W4A8_OK || !zx || !acc_out) return rc;
     return launch_acc_zero_point(acc_out, zx, wsum, M, N * (K / G), st);
 }
@@ -172,7 +175,7 @@ int quantize_weight_dint4(const void *W, int w_dtype, int64_t N, int64_t K, int6
     if (N == 0) return W4A8_OK;
     if (!W || !codes || !step || !zero) return W4A8_ERR_NULL;
     return launch_weight_quant(W, w_dtype, N, K, ldw, s, G, use_given_params, codes, step, zero,
-                               (hipStream_t)stream);
+                               W4A8_FMT_DINT4, (hipStream_t)stream);
 }
 
 int quantize_value_dint4(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D,
@@ -450,3 +453,133 @@ int aqas_clip_search(const void *X, const void *W, int dtype, int64_t M, int64_t
 
 }  // extern "C"
 
+
+// ---- weight-format variants (App. A.5, Tables 10-14) and the error split of Sec. 4.1 -------------
+namespace {
+
+struct ErrWs {
+    size_t codes, step, zero, du, dr, xs, pu, pr, total;
+};
+ErrWs plan_err(int64_t M, int64_t N, int64_t K, int64_t G)
+{
+    ErrWs w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    w.codes = take((size_t)N * K);
+    w.step = take((size_t)N * (K / G) * 4);
+    w.zero = take((size_t)N * (K / G));
+    w.du = take((size_t)N * K * 4);
+    w.dr = take((size_t)N * K * 4);
+    w.xs = take((size_t)M * K * 4);
+    w.pu = take((size_t)M * N * 4);
+    w.pr = take((size_t)M * N * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+int quantize_weight_format(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                           int64_t group_size, int format, int use_given_params, uint8_t *codes,
+                           float *step, uint8_t *zero, void *stream)
+{
+    if (!valid_dtype(w_dtype)) return W4A8_ERR_DTYPE;
+    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (N < 0 || K < 1 || ldw < K || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (N == 0) return W4A8_OK;
+    if (!W || !codes || !step || !zero) return W4A8_ERR_NULL;
+    return launch_weight_quant(W, w_dtype, N, K, ldw, s, G, use_given_params, codes, step, zero, format,
+                               (hipStream_t)stream);
+}
+
+int w4a8_gemm_format(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wp, int layout,
+                     const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t group_size,
+                     int format, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    return gemm_common(Xq, sx, nullptr, M, Wp, layout, step, zero, nullptr, nullptr, N, K, group_size, Y,
+                       y_dtype, ldy, acc_out, workspace, workspace_bytes, stream, format);
+}
+
+int pack_format(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout, int format,
+                void *stream)
+{
+    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    const int rc = check_pack_shape(N, K, layout);
+    if (rc != W4A8_OK) return rc;
+    if (N == 0) return W4A8_OK;
+    if (!codes || !packed) return W4A8_ERR_NULL;
+    if (layout == W4A8_LAYOUT_TILED && (uintptr_t)packed % 4 != 0) return W4A8_ERR_SHAPE;
+    return launch_pack(codes, N, K, packed, layout, (hipStream_t)stream, format == W4A8_FMT_INT4);
+}
+
+int unpack_format(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout, int format,
+                  void *stream)
+{
+    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    const int rc = check_pack_shape(N, K, layout);
+    if (rc != W4A8_OK) return rc;
+    if (N == 0) return W4A8_OK;
+    if (!codes || !packed) return W4A8_ERR_NULL;
+    if (layout == W4A8_LAYOUT_TILED && (uintptr_t)packed % 4 != 0) return W4A8_ERR_SHAPE;
+    return launch_unpack(packed, N, K, codes, layout, (hipStream_t)stream, format == W4A8_FMT_INT4);
+}
+
+int pack_dint3(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, void *stream)
+{
+    if (N < 0 || K < 1 || K % 8 != 0) return W4A8_ERR_SHAPE;
+    if (N == 0) return W4A8_OK;
+    if (!codes || !packed) return W4A8_ERR_NULL;
+    return launch_pack3(codes, N, K, packed, (hipStream_t)stream);
+}
+
+int unpack_dint3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, void *stream)
+{
+    if (N < 0 || K < 1 || K % 8 != 0) return W4A8_ERR_SHAPE;
+    if (N == 0) return W4A8_OK;
+    if (!codes || !packed) return W4A8_ERR_NULL;
+    return launch_unpack3(packed, N, K, codes, (hipStream_t)stream);
+}
+
+size_t dint_error_terms_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size)
+{
+    int64_t G = group_size;
+    if (M < 1 || N < 1 || !resolve_group(K, G) || K % 2 != 0) return 0;
+    return plan_err(M, N, K, G).total;
+}
+
+int dint_error_terms(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const void *W,
+                     int w_dtype, int64_t N, int64_t ldw, const float *s, int64_t group_size, int format,
+                     double *terms, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(x_dtype) || !valid_dtype(w_dtype)) return W4A8_ERR_DTYPE;
+    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (M < 1 || N < 1 || !resolve_group(K, G) || K % 2 != 0 || ldx < K || ldw < K) return W4A8_ERR_SHAPE;
+    if (!X || !W || !terms) return W4A8_ERR_NULL;
+    const ErrWs w = plan_err(M, N, K, G);
+    if (!workspace || (uintptr_t)workspace % WS_ALIGN != 0 || workspace_bytes < w.total) return W4A8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    float *du = (float *)(ws + w.du), *dr = (float *)(ws + w.dr), *xs = (float *)(ws + w.xs);
+    float *pu = (float *)(ws + w.pu), *pr = (float *)(ws + w.pr);
+    int rc = launch_weight_quant(W, w_dtype, N, K, ldw, s, G, 0, ws + w.codes, (float *)(ws + w.step),
+                                 ws + w.zero, format, st);
+    if (rc != W4A8_OK) return rc;
+    if ((rc = launch_error_split(W, w_dtype, N, K, ldw, s, G, format != W4A8_FMT_INT4, ws + w.codes,
+                                 (const float *)(ws + w.step), ws + w.zero, du, dr, st)) != W4A8_OK)
+        return rc;
+    if ((rc = launch_scale_activations(X, x_dtype, M, K, ldx, s, xs, st)) != W4A8_OK) return rc;
+    if ((rc = launch_ref_gemm(xs, du, W4A8_F32, M, N, K, K, K, pu, st)) != W4A8_OK) return rc;
+    if ((rc = launch_ref_gemm(xs, dr, W4A8_F32, M, N, K, K, K, pr, st)) != W4A8_OK) return rc;
+    return launch_error_terms(pu, pr, M * N, du, N * K, terms, st);
+}
+
+}  // extern "C"

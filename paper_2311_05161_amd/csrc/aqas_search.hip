@@ -264,4 +264,110 @@ int launch_clip_select(const double *err, int64_t N, int i, double *best_err, in
     return hip_status(hipGetLastError());
 }
 
+// ---- the error split of Sec. 4.1 (Eq. 4) ---------------------------------------------------------
+// delta = Wq - W diag(s) per weight, written to du where the quantized value is zero (underflow) and
+// to dr otherwise (rounding); the other array gets 0.
+template <typename T>
+__global__ __launch_bounds__(256) void error_split_kernel(const T *__restrict__ W, int64_t N, int64_t K,
+                                                          int64_t ldw, const float *__restrict__ s, int64_t G,
+                                                          int special, const uint8_t *__restrict__ codes,
+                                                          const float *__restrict__ step,
+                                                          const uint8_t *__restrict__ zero,
+                                                          float *__restrict__ du, float *__restrict__ dr)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * K) return;
+    const int64_t n = i / K, k = i - n * K;
+    const int64_t pi = n * (K / G) + k / G;
+    const float w = to_f32(W[n * ldw + k]);
+    const float wp = s ? w * s[k] : w;
+    const int code = codes[i] & 15, z = zero[pi];
+    const int d = (special && code >= 14) ? (code == 14 ? 1 : -1) : 2 * (code - z);   // half steps
+    const float wq = (float)d * (0.5f * step[pi]);
+    const float delta = wq - wp;
+    du[i] = d == 0 ? delta : 0.0f;
+    dr[i] = d == 0 ? 0.0f : delta;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void scale_activations_kernel(const T *__restrict__ X, int64_t M, int64_t K,
+                                                                int64_t ldx, const float *__restrict__ s,
+                                                                float *__restrict__ xs)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * K) return;
+    const int64_t m = i / K, k = i - m * K;
+    const float x = to_f32(X[m * ldx + k]);
+    xs[i] = s ? x * (1.0f / s[k]) : x;
+}
+
+// terms = {sum pu^2, sum pr^2, sum 2 pu pr, number of non-zero entries of du}; one workgroup, fixed order
+__global__ __launch_bounds__(256) void error_terms_kernel(const float *__restrict__ pu,
+                                                          const float *__restrict__ pr, int64_t n,
+                                                          const float *__restrict__ du, int64_t nw,
+                                                          double *__restrict__ terms)
+{
+    __shared__ double part[4][256];
+    double a = 0.0, b = 0.0, c = 0.0, u = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) {
+        const double x = pu[i], y = pr[i];
+        a += x * x;
+        b += y * y;
+        c += 2.0 * x * y;
+    }
+    for (int64_t i = threadIdx.x; i < nw; i += 256) u += du[i] != 0.0f ? 1.0 : 0.0;
+    part[0][threadIdx.x] = a;
+    part[1][threadIdx.x] = b;
+    part[2][threadIdx.x] = c;
+    part[3][threadIdx.x] = u;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w)
+            for (int t = 0; t < 4; ++t) part[t][threadIdx.x] += part[t][threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x < 4) terms[threadIdx.x] = part[threadIdx.x][0];
+}
+
+int launch_error_split(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                       int64_t G, int special, const uint8_t *codes, const float *step,
+                       const uint8_t *zero, float *du, float *dr, hipStream_t st)
+{
+    const dim3 grid((unsigned)((N * K + 255) / 256));
+#define W4A8_ES_LAUNCH(T_)                                                                             \
+    hipLaunchKernelGGL((error_split_kernel<T_>), grid, dim3(256), 0, st, (const T_ *)W, N, K, ldw, s, G, \
+                       special, codes, step, zero, du, dr)
+    switch (w_dtype) {
+        case W4A8_F32: W4A8_ES_LAUNCH(float); break;
+        case W4A8_F16: W4A8_ES_LAUNCH(__half); break;
+        case W4A8_BF16: W4A8_ES_LAUNCH(bf16_t); break;
+        default: return W4A8_ERR_DTYPE;
+    }
+#undef W4A8_ES_LAUNCH
+    return hip_status(hipGetLastError());
+}
+
+int launch_scale_activations(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                             const float *s, float *xs, hipStream_t st)
+{
+    const dim3 grid((unsigned)((M * K + 255) / 256));
+#define W4A8_SA_LAUNCH(T_) \
+    hipLaunchKernelGGL((scale_activations_kernel<T_>), grid, dim3(256), 0, st, (const T_ *)X, M, K, ldx, s, xs)
+    switch (x_dtype) {
+        case W4A8_F32: W4A8_SA_LAUNCH(float); break;
+        case W4A8_F16: W4A8_SA_LAUNCH(__half); break;
+        case W4A8_BF16: W4A8_SA_LAUNCH(bf16_t); break;
+        default: return W4A8_ERR_DTYPE;
+    }
+#undef W4A8_SA_LAUNCH
+    return hip_status(hipGetLastError());
+}
+
+int launch_error_terms(const float *pu, const float *pr, int64_t n, const float *du, int64_t nw,
+                       double *terms, hipStream_t st)
+{
+    hipLaunchKernelGGL(error_terms_kernel, dim3(1), dim3(256), 0, st, pu, pr, n, du, nw, terms);
+    return hip_status(hipGetLastError());
+}
+
 }  // namespace w4a8

@@ -53,9 +53,9 @@ __device__ __forceinline__ void order_fence()
 // Decode record of one (channel, k-tile): LUT halves, step / 8, and in the last word -4 beta as an
 // int8 in byte 0 with 4 * tsum in the upper 24 bits (tsum: sum of the tile's weights in half steps,
 // |4 tsum| <= 4 * 26 * 128; zero without a token zero-point).
-__device__ __forceinline__ v4u decode_record(int z, float st, int tsum)
+__device__ __forceinline__ v4u decode_record(int z, float st, int tsum, bool plain)
 {
-    const DecodeLut t = make_decode_lut(z);
+    const DecodeLut t = make_decode_lut(z, plain);
     const uint32_t nb8 = (uint32_t)(-t.beta_q) & 0xffu;
     return v4u{t.lo, t.hi, __float_as_uint(st * 0.125f), ((uint32_t)(4 * tsum) << 8) | nb8};
 }
@@ -80,6 +80,7 @@ struct GemvArgs {
     int tiles_per_group, ng, y_dtype;
     int kt_per_split;      // k-tiles per K-split (blockIdx.y)
     int nt_lo, nt_rem;     // workgroup b owns nt_lo (+1 if b < nt_rem) consecutive n-tiles
+    int plain;             // code space of ordinary INT4 (16 integer levels) instead of dINT4
 };
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             const int e = threadIdx.x + i * GV_THREADS;
             if ((GROUPED || i == 0) && e < n_rec) {
                 const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
-                rec[t * RS + (e - t * recs_per_nt)] = decode_record(st_z[i], st_s[i], st_t[i]);
+                rec[t * RS + (e - t * recs_per_nt)] = decode_record(st_z[i], st_s[i], st_t[i], a.plain != 0);
             }
         }
     };
@@ -452,7 +453,7 @@ static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hi
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
                 int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
-                hipStream_t st)
+                hipStream_t st, int plain)
 {
     const GemvPlan pl = plan_gemv(M, N, K, G, batch);
     if (batch > 1 && (pl.splits > 1 || acc_out != nullptr)) return W4A8_ERR_SHAPE;
@@ -465,6 +466,7 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     ga.M = (int)M; ga.N = (int)N; ga.K = (int)K;
     ga.tiles_per_group = (int)(G / TILE_K); ga.ng = (int)(K / G); ga.y_dtype = y_dtype;
     ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
+    ga.plain = plain;
     const bool asym = zp.zx != nullptr;
     if (grouped) {
         // the per-tile zero-point term only exists in its own instances (asymmetric, grouped)

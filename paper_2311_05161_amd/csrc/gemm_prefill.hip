@@ -119,7 +119,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const uint8_t *__restrict__ zero, int N, int K, int tiles_per_group, int ng,
     uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store,
     int32_t *__restrict__ acc_out, int grid_m, int grid_n, int kt_per_split,
-    float *__restrict__ partial)
+    float *__restrict__ partial, int plain)
 {
     constexpr int GM_THREADS = WM * WN * 64;
     constexpr int GM_NS = GM_BN / (WN * 32);       // 32-channel sub-tiles per wave
@@ -241,10 +241,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
             if (GROUPED) {
-                slut[ns] = make_signed_lut(s_gz[g & 3][wn * (GM_NS * 32) + ns * 32 + r32]);
+                slut[ns] = make_signed_lut(s_gz[g & 3][wn * (GM_NS * 32) + ns * 32 + r32], plain != 0);
             } else {
                 const int nn = (n0 + ns * 32 + r32 < N) ? n0 + ns * 32 + r32 : 0;
-                lut[ns] = make_decode_lut(zero[(int64_t)nn * ng]);
+                lut[ns] = make_decode_lut(zero[(int64_t)nn * ng], plain != 0);
             }
         }
     };
@@ -549,7 +549,7 @@ template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM>
 static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                           const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                           const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                          int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
+                          int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain)
 {
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
@@ -567,7 +567,7 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
                        dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * WN * 64), lds_bytes, st,
                        Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,
                        (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
-                       acc_out, grid_m, grid_n, pl.kt_per_split, pl.splits > 1 ? partial : nullptr);
+                       acc_out, grid_m, grid_n, pl.kt_per_split, pl.splits > 1 ? partial : nullptr, plain);
     return hip_status(hipGetLastError());
 }
 
@@ -575,13 +575,13 @@ template <int BM, int WM, int WN, bool GROUPED>
 static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                          const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                          const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                         int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st)
+                         int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain)
 {
     // The accumulator test hook is a separate instance so that the fast path carries none of it;
     // so is the per-group zero-point term of group-wise weights.
 #define W4A8_GM2(AO_, AS_)                                                                       \
     return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
-                                                     G, Y, y_dtype, ldy, acc_out, partial, st)
+                                                     G, Y, y_dtype, ldy, acc_out, partial, st, plain)
     if (GROUPED && zp.zx != nullptr) {
         if (acc_out) W4A8_GM2(true, GROUPED);
         W4A8_GM2(false, GROUPED);
@@ -631,7 +631,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
 int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, int64_t M,
                 const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N, int64_t K,
                 int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, float *partial,
-                hipStream_t st)
+                hipStream_t st, int plain)
 {
     const bool grouped = G != K;
     if ((M + 63) / 64 * ((N + 255) / 256) * 64 > 0x7fffffLL || M * K > 0x7fffffffLL)
@@ -646,7 +646,7 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
     int rc;
 #define W4A8_GM(BM_, WM_, WN_, GR_)                                                                \
     rc = launch_gemm_t<BM_, WM_, WN_, GR_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
-                                      acc_out, partial, st)
+                                      acc_out, partial, st, plain)
     if (grouped) {
         if (pl.bm == 64) W4A8_GM(64, 1, 4, true);
         else W4A8_GM(128, 1, 8, true);

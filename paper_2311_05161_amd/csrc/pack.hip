@@ -56,8 +56,11 @@ __device__ __forceinline__ void tiled_word_coords(int64_t o, int64_t KT, int64_t
 // SRC = 0: one code per byte [N,K];  SRC = 1: canonical packed [N,K/2].
 template <int SRC>
 __global__ __launch_bounds__(PK_THREADS) void pack_tiled_kernel(
-    const uint8_t *__restrict__ src, int64_t N, int64_t K, uint32_t *__restrict__ tiled)
+    const uint8_t *__restrict__ src, int64_t N, int64_t K, uint32_t *__restrict__ tiled, int plain)
 {
+    // plain (ordinary INT4): codes 14 and 15 are the integer pair of l = 7, lower member first, so they
+    // trade places before the dINT re-encoding (which puts -step/2 = code 15 at the lower position)
+    const uint32_t swap = plain ? 1u : 0u;
     const int64_t words = N * K / 8;
     const int64_t KT = K / TILE_K;
     for (int64_t o = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; o < words;
@@ -81,16 +84,17 @@ __global__ __launch_bounds__(PK_THREADS) void pack_tiled_kernel(
         uint32_t w = 0;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {  // byte b: low nibble column +b, high nibble column +4+b
-            w |= recode(c[b]) << (8 * b);
-            w |= recode(c[4 + b]) << (8 * b + 4);
+            w |= recode(c[b] >= 14u ? c[b] ^ swap : c[b]) << (8 * b);
+            w |= recode(c[4 + b] >= 14u ? c[4 + b] ^ swap : c[4 + b]) << (8 * b + 4);
         }
         tiled[o] = w;
     }
 }
 
 __global__ __launch_bounds__(PK_THREADS) void unpack_tiled_kernel(
-    const uint32_t *__restrict__ tiled, int64_t N, int64_t K, uint8_t *__restrict__ codes)
+    const uint32_t *__restrict__ tiled, int64_t N, int64_t K, uint8_t *__restrict__ codes, int plain)
 {
+    const uint32_t swap = plain ? 1u : 0u;
     const int64_t words = N * K / 8;
     const int64_t KT = K / TILE_K;
     for (int64_t o = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; o < words;
@@ -101,8 +105,9 @@ __global__ __launch_bounds__(PK_THREADS) void unpack_tiled_kernel(
         uint8_t *p = codes + n * K + k;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            p[b] = (uint8_t)uncode((w >> (8 * b)) & 15u);
-            p[4 + b] = (uint8_t)uncode((w >> (8 * b + 4)) & 15u);
+            const uint32_t c0 = uncode((w >> (8 * b)) & 15u), c1 = uncode((w >> (8 * b + 4)) & 15u);
+            p[b] = (uint8_t)(c0 >= 14u ? c0 ^ swap : c0);
+            p[4 + b] = (uint8_t)(c1 >= 14u ? c1 ^ swap : c1);
         }
     }
 }
@@ -139,7 +144,7 @@ static unsigned grid_for(int64_t items)
 }
 
 int launch_pack(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout,
-                hipStream_t st)
+                hipStream_t st, int plain)
 {
     if (N * K == 0) return W4A8_OK;
     if (layout == W4A8_LAYOUT_CANONICAL) {
@@ -148,13 +153,13 @@ int launch_pack(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int
                            codes, bytes, packed);
     } else {
         hipLaunchKernelGGL(pack_tiled_kernel<0>, dim3(grid_for(N * K / 8)), dim3(PK_THREADS), 0, st,
-                           codes, N, K, (uint32_t *)packed);
+                           codes, N, K, (uint32_t *)packed, plain);
     }
     return hip_status(hipGetLastError());
 }
 
 int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout,
-                  hipStream_t st)
+                  hipStream_t st, int plain)
 {
     if (N * K == 0) return W4A8_OK;
     if (layout == W4A8_LAYOUT_CANONICAL) {
@@ -163,17 +168,17 @@ int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, i
                            packed, bytes, codes);
     } else {
         hipLaunchKernelGGL(unpack_tiled_kernel, dim3(grid_for(N * K / 8)), dim3(PK_THREADS), 0, st,
-                           (const uint32_t *)packed, N, K, codes);
+                           (const uint32_t *)packed, N, K, codes, plain);
     }
     return hip_status(hipGetLastError());
 }
 
 int launch_repack_canonical_to_tiled(const uint8_t *canon, int64_t N, int64_t K, uint8_t *tiled,
-                                     hipStream_t st)
+                                     hipStream_t st, int plain)
 {
     if (N * K == 0) return W4A8_OK;
     hipLaunchKernelGGL(pack_tiled_kernel<1>, dim3(grid_for(N * K / 8)), dim3(PK_THREADS), 0, st,
-                       canon, N, K, (uint32_t *)tiled);
+                       canon, N, K, (uint32_t *)tiled, plain);
     return hip_status(hipGetLastError());
 }
 
@@ -190,6 +195,55 @@ int launch_acc_zero_point(int32_t *acc, const int32_t *zx, const int32_t *wsum, 
     if (M * per_token == 0) return W4A8_OK;
     hipLaunchKernelGGL(acc_zero_point_kernel, dim3(grid_for(M * per_token)), dim3(PK_THREADS), 0, st,
                        acc, zx, wsum, M, per_token);
+    return hip_status(hipGetLastError());
+}
+
+// ---- 3-bit storage of dINT3 (Table 10): codes 0..5 and the special codes 14 / 15 of the 4-bit code
+// space become 0..5, 6, 7; code i of a group of eight sits at bits 3i..3i+2 of a little-endian
+// 24-bit word.  One thread per group of eight.
+__global__ __launch_bounds__(PK_THREADS) void pack3_kernel(const uint8_t *__restrict__ codes, int64_t groups,
+                                                           uint8_t *__restrict__ packed)
+{
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < groups;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t c = codes[i * 8 + j] & 15u;
+            word |= (c >= 14u ? c - 8u : (c & 7u)) << (3 * j);
+        }
+        packed[i * 3 + 0] = (uint8_t)word;
+        packed[i * 3 + 1] = (uint8_t)(word >> 8);
+        packed[i * 3 + 2] = (uint8_t)(word >> 16);
+    }
+}
+
+__global__ __launch_bounds__(PK_THREADS) void unpack3_kernel(const uint8_t *__restrict__ packed, int64_t groups,
+                                                             uint8_t *__restrict__ codes)
+{
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < groups;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const uint32_t word = (uint32_t)packed[i * 3] | ((uint32_t)packed[i * 3 + 1] << 8) |
+                              ((uint32_t)packed[i * 3 + 2] << 16);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t c = (word >> (3 * j)) & 7u;
+            codes[i * 8 + j] = (uint8_t)(c >= 6u ? c + 8u : c);
+        }
+    }
+}
+
+int launch_pack3(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, hipStream_t st)
+{
+    const int64_t groups = N * K / 8;
+    hipLaunchKernelGGL(pack3_kernel, dim3(grid_for(groups)), dim3(PK_THREADS), 0, st, codes, groups, packed);
+    return hip_status(hipGetLastError());
+}
+
+int launch_unpack3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, hipStream_t st)
+{
+    const int64_t groups = N * K / 8;
+    hipLaunchKernelGGL(unpack3_kernel, dim3(grid_for(groups)), dim3(PK_THREADS), 0, st, packed, groups, codes);
     return hip_status(hipGetLastError());
 }
 

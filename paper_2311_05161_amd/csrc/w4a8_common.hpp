@@ -81,13 +81,16 @@ struct DecodeLut {
     int beta_q;      // 4 * beta = 8 z + 4 b0
 };
 
-__device__ __forceinline__ DecodeLut make_decode_lut(int z)
+// plain: the code space of ordinary INT4 (16 integer levels, zero-point up to 15): the pair l = 7 is
+// the integer pair (14, 15) like the others, D = (112 + 4 b0) | (h << 3) <= 124.
+__device__ __forceinline__ DecodeLut make_decode_lut(int z, bool plain = false)
 {
     DecodeLut t;
     const uint32_t c4 = ((uint32_t)(~z) & 1u) << 2;  // 4 * b0
     const uint32_t c4x4 = c4 * 0x01010101u;
     t.lo = 0x30201000u | c4x4;
-    t.hi = (0x00605040u | (c4x4 & 0x00ffffffu)) | ((uint32_t)(8 * z + (int)c4 - 4) << 24);
+    t.hi = plain ? (0x70605040u | c4x4)
+                 : ((0x00605040u | (c4x4 & 0x00ffffffu)) | ((uint32_t)(8 * z + (int)c4 - 4) << 24));
     t.beta_q = 8 * z + (int)c4;
     return t;
 }
@@ -119,13 +122,14 @@ __device__ __forceinline__ void decode_lane(const v4u &p, const DecodeLut &t, v4
 struct SignedLut {
     uint32_t lo, hi;
 };
-__device__ __forceinline__ SignedLut make_signed_lut(int z)
+__device__ __forceinline__ SignedLut make_signed_lut(int z, bool plain = false)
 {
     SignedLut t;
-    const uint32_t b = (uint32_t)(128 - 8 * z);           // 24 .. 128
+    const uint32_t b = (uint32_t)(128 - 8 * z);           // 24 .. 128 (8 .. 128 for plain INT4)
     const uint32_t b4 = __builtin_amdgcn_perm(b, b, 0u);  // replicated to the four bytes
     t.lo = b4 + 0x30201000u;                              // no carries: b + 48 <= 176
-    t.hi = (b4 & 0x00ffffffu) + 0x00605040u + (124u << 24);
+    t.hi = plain ? b4 + 0x70605040u                       // b + 112 + 8 h <= 248
+                 : (b4 & 0x00ffffffu) + 0x00605040u + (124u << 24);
     return t;
 }
 __device__ __forceinline__ void decode_word_signed(uint32_t p, const SignedLut &t, int &a, int &b)
@@ -148,7 +152,7 @@ int launch_acc_zero_point(int32_t *acc, const int32_t *zx, const int32_t *wsum, 
                           int64_t per_token, hipStream_t st);
 int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
                         const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
-                        uint8_t *zero, hipStream_t st);
+                        uint8_t *zero, int format, hipStream_t st);
 // step / zero of the ranges shrunk by rho = 1 - 0.05 i, i = idx[n] (or `uniform` when idx is null)
 int launch_clip_params(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
                        int64_t G, const int32_t *idx, int uniform, float *step, uint8_t *zero,
@@ -166,16 +170,30 @@ int launch_loss_sum(const double *err, int64_t N, double *losses, int slot, hipS
 int launch_argmin(const double *losses, int count, int32_t *best, hipStream_t st);
 int launch_clip_select(const double *err, int64_t N, int i, double *best_err, int32_t *best_idx,
                        double *err_table, hipStream_t st);
+// 3-bit storage of dINT3 codes (0..5, 14 -> 6, 15 -> 7): eight codes in three bytes
+int launch_pack3(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, hipStream_t st);
+int launch_unpack3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, hipStream_t st);
+// error split of Sec. 4.1: du / dr [N,K] = quantization error of W diag(s) on the weights that
+// quantize to zero / on the others; xs = X diag(s)^-1 in fp32; terms = {sum pu^2, sum pr^2,
+// sum 2 pu pr, number of underflowing weights}
+int launch_error_split(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
+                       int64_t G, int special, const uint8_t *codes, const float *step,
+                       const uint8_t *zero, float *du, float *dr, hipStream_t st);
+int launch_scale_activations(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx,
+                             const float *s, float *xs, hipStream_t st);
+int launch_error_terms(const float *pu, const float *pr, int64_t n, const float *du, int64_t nw,
+                       double *terms, hipStream_t st);
 // Value cache: V [batch, T, D] (token stride ld_t, head stride ld_b) -> codes [batch * D, T]
 int launch_value_quant(const void *V, int v_dtype, int64_t batch, int64_t T, int64_t D, int64_t ld_t,
                        int64_t ld_b, int64_t G, uint8_t *codes, float *step, uint8_t *zero,
                        hipStream_t st);
+// plain != 0: code space of ordinary INT4 (codes 14 / 15 are the integer pair of l = 7)
 int launch_pack(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, int layout,
-                hipStream_t st);
+                hipStream_t st, int plain = 0);
 int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, int layout,
-                  hipStream_t st);
+                  hipStream_t st, int plain = 0);
 int launch_repack_canonical_to_tiled(const uint8_t *canon, int64_t N, int64_t K, uint8_t *tiled,
-                                     hipStream_t st);
+                                     hipStream_t st, int plain = 0);
 int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st);
 // Launch shape of the decode GEMV for a problem size (also sizes its K-split workspace).
 struct GemvPlan {
@@ -199,7 +217,7 @@ struct ZeroPoint {
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
                 int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
-                hipStream_t st);
+                hipStream_t st, int plain = 0);
 // Y = cast(sx * sum over splits of partial).  int_step != null: the partials are int32
 // accumulators of a per-channel launch, scaled by int_step[n] / 8 after the exact zero-point term.
 int launch_gemv_combine(const float *partial, const float *sx, const float *int_step, ZeroPoint zp,
@@ -217,7 +235,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G);
 int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, int64_t M,
                 const uint8_t *Wt, const float *step, const uint8_t *zero, int64_t N, int64_t K,
                 int64_t G, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, float *partial,
-                hipStream_t st);
+                hipStream_t st, int plain = 0);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
 

@@ -40,20 +40,31 @@ __device__ __forceinline__ void loadv(const T *p, float (&v)[V])
     }
 }
 
-__device__ __forceinline__ uint32_t dint4_code(float w, float istep, int z)
+// Format of the code space (Sec. 4.2): p uniform steps, with or without the two special levels
+// +-step/2.  dINT4: p = 13, special; dINT3: p = 5, special; plain INT4: p = 15, none.
+struct CodeFormat {
+    int p;
+    int special;
+};
+__host__ __device__ constexpr CodeFormat dint4_format() { return CodeFormat{DINT4_P, 1}; }
+
+__device__ __forceinline__ uint32_t dint4_code(float w, float istep, int z, CodeFormat f = dint4_format())
 {
     const float u = w * istep;
-    if (u > 0.25f && u <= 0.75f) return 14u;     // c1: +step/2
-    if (u >= -0.75f && u < -0.25f) return 15u;   // c2: -step/2
+    if (f.special) {
+        if (u > 0.25f && u <= 0.75f) return 14u;     // c1: +step/2
+        if (u >= -0.75f && u < -0.25f) return 15u;   // c2: -step/2
+    }
     int c = (int)__builtin_rintf(u) + z;
     c = c < 0 ? 0 : c;
-    c = c > DINT4_P ? DINT4_P : c;
+    c = c > f.p ? f.p : c;
     return (uint32_t)c;
 }
 
-// Min-max asymmetric parameters of a range that contains zero: step = (hi - lo) / 13,
-// z = clamp(rne(-lo / step), 0, 13); a degenerate range gives step 1, z 0.
-__device__ __forceinline__ void range_params(float lo, float hi, float &st, float &istep, int &z)
+// Min-max asymmetric parameters of a range that contains zero: step = (hi - lo) / p,
+// z = clamp(rne(-lo / step), 0, p); a degenerate range gives step 1, z 0.
+__device__ __forceinline__ void range_params(float lo, float hi, float &st, float &istep, int &z,
+                                             CodeFormat f = dint4_format())
 {
     if (hi == lo) {
         st = 1.0f;
@@ -61,11 +72,12 @@ __device__ __forceinline__ void range_params(float lo, float hi, float &st, floa
         z = 0;
     } else {
         const float range = hi - lo;
-        st = range / 13.0f;
+        const float pf = (float)f.p;
+        st = range / pf;
         istep = 1.0f / st;
         const float nlo = -lo;
         float zf = __builtin_rintf(nlo * istep);
-        zf = fminf(fmaxf(zf, 0.0f), 13.0f);
+        zf = fminf(fmaxf(zf, 0.0f), pf);
         z = (int)zf;
     }
 }
@@ -74,7 +86,7 @@ template <typename T, int V>
 __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
     const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
     int64_t G, int use_given, uint8_t *__restrict__ codes, float *__restrict__ step,
-    uint8_t *__restrict__ zero)
+    uint8_t *__restrict__ zero, CodeFormat fmt)
 {
     const int lane = threadIdx.x & 63;
     const int64_t ng = K / G;
@@ -104,7 +116,7 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
         }
         lo = wave_min(lo);
         hi = wave_max(hi);
-        range_params(lo, hi, st, istep, z);
+        range_params(lo, hi, st, istep, z, fmt);
         if (lane == 0) {
             step[seg] = st;
             zero[seg] = (uint8_t)z;
@@ -119,7 +131,7 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const float x = sg ? v[j] * sg[k + j] : v[j];
-            q[j] = dint4_code(x, istep, z);
+            q[j] = dint4_code(x, istep, z, fmt);
         }
         if constexpr (V == 8) {
             const uint32_t w0 = q[0] | q[1] << 8 | q[2] << 16 | q[3] << 24;
@@ -139,7 +151,8 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
 template <typename T, int LANES>
 __global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
     const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
-    int use_given, uint8_t *__restrict__ codes, float *__restrict__ step, uint8_t *__restrict__ zero)
+    int use_given, uint8_t *__restrict__ codes, float *__restrict__ step, uint8_t *__restrict__ zero,
+    CodeFormat fmt)
 {
     constexpr int G = LANES * 8;
     const int lane = threadIdx.x & 63;
@@ -172,7 +185,7 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
             lo = fminf(lo, __shfl_xor(lo, off, WAVE));
             hi = fmaxf(hi, __shfl_xor(hi, off, WAVE));
         }
-        range_params(lo, hi, st, istep, z);
+        range_params(lo, hi, st, istep, z, fmt);
         if ((lane & (LANES - 1)) == 0) {
             step[pidx] = st;
             zero[pidx] = (uint8_t)z;
@@ -180,7 +193,7 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
     }
     uint32_t q[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) q[j] = dint4_code(x[j], istep, z);
+    for (int j = 0; j < 8; ++j) q[j] = dint4_code(x[j], istep, z, fmt);
     *reinterpret_cast<uint2 *>(codes + n * K + k) =
         make_uint2(q[0] | q[1] << 8 | q[2] << 16 | q[3] << 24, q[4] | q[5] << 8 | q[6] << 16 | q[7] << 24);
 }
@@ -188,7 +201,7 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
 template <typename T>
 static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, const float *s,
                                  int64_t G, int use_given, uint8_t *codes, float *step,
-                                 uint8_t *zero, hipStream_t st)
+                                 uint8_t *zero, CodeFormat fmt, hipStream_t st)
 {
     const int64_t segs = N * (K / G);
     if (segs == 0) return W4A8_OK;
@@ -200,17 +213,17 @@ static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, 
     };
 #define W4A8_WQ_LAUNCH(V_)                                                                        \
     hipLaunchKernelGGL((weight_quant_kernel<T, V_>), dim3((unsigned)blocks), dim3(WQ_THREADS), 0, \
-                       st, W, N, K, ldw, s, G, use_given, codes, step, zero)
+                       st, W, N, K, ldw, s, G, use_given, codes, step, zero, fmt)
     if ((G == 128 || G == 256) && aligned(8)) {
         const int64_t wsegs = N * ((K + 511) / 512);
         const int64_t wblocks = (wsegs + (WQ_THREADS / WAVE) - 1) / (WQ_THREADS / WAVE);
         if (wblocks > 0x7fffffffLL) return W4A8_ERR_SHAPE;
         if (G == 128)
             hipLaunchKernelGGL((weight_quant_small_groups_kernel<T, 16>), dim3((unsigned)wblocks),
-                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero);
+                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero, fmt);
         else
             hipLaunchKernelGGL((weight_quant_small_groups_kernel<T, 32>), dim3((unsigned)wblocks),
-                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero);
+                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero, fmt);
     } else if (G >= 512 && aligned(8)) {
         W4A8_WQ_LAUNCH(8);
     } else if (aligned(2)) {
@@ -224,18 +237,25 @@ static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, 
 
 int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw,
                         const float *s, int64_t G, int use_given, uint8_t *codes, float *step,
-                        uint8_t *zero, hipStream_t st)
+                        uint8_t *zero, int format, hipStream_t st)
 {
+    CodeFormat fmt;
+    switch (format) {
+        case W4A8_FMT_DINT4: fmt = CodeFormat{13, 1}; break;
+        case W4A8_FMT_INT4: fmt = CodeFormat{15, 0}; break;
+        case W4A8_FMT_DINT3: fmt = CodeFormat{5, 1}; break;
+        default: return W4A8_ERR_DTYPE;
+    }
     switch (w_dtype) {
         case W4A8_F32:
             return launch_weight_quant_t((const float *)W, N, K, ldw, s, G, use_given, codes, step,
-                                         zero, st);
+                                         zero, fmt, st);
         case W4A8_F16:
             return launch_weight_quant_t((const __half *)W, N, K, ldw, s, G, use_given, codes, step,
-                                         zero, st);
+                                         zero, fmt, st);
         case W4A8_BF16:
             return launch_weight_quant_t((const bf16_t *)W, N, K, ldw, s, G, use_given, codes, step,
-                                         zero, st);
+                                         zero, fmt, st);
         default: return W4A8_ERR_DTYPE;
     }
 }

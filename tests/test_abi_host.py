@@ -178,6 +178,27 @@ def test_argument_errors_are_reported_before_any_launch(lib):
                               ctypes.c_void_p(0x10000), 1 << 30, Z) == b.ERR_NULL
     assert c.aqas_clip_search(P, P, b.F16, 32, 64, 256, 256, 256, P, 0, P, P, P, Z, Z, 0, Z) == b.ERR_WORKSPACE
 
+    # weight-format variants, 3-bit packing, error split
+    assert c.quantize_weight_format(P, b.F16, 16, 128, 128, Z, 0, 3, 0, P, P, P, Z) == b.ERR_DTYPE   # format id
+    assert c.quantize_weight_format(P, b.F16, 16, 128, 64, Z, 0, 1, 0, P, P, P, Z) == b.ERR_SHAPE
+    assert c.quantize_weight_format(P, b.F16, 16, 128, 128, Z, 0, 2, 0, Z, P, P, Z) == b.ERR_NULL
+    assert c.w4a8_gemm_format(P, P, 4, P, 1, P, P, 16, 128, 0, 7, P, b.F16, 16, Z, Z, 0, Z) == b.ERR_DTYPE
+    assert c.w4a8_gemm_format(P, P, 4, P, 1, P, P, 24, 128, 0, 1, P, b.F16, 24, Z, Z, 0, Z) == b.ERR_SHAPE
+    assert c.pack_format(P, 16, 128, P, 1, 5, Z) == b.ERR_DTYPE
+    assert c.pack_format(P, 8, 128, P, 1, 1, Z) == b.ERR_SHAPE
+    assert c.unpack_format(Z, 16, 128, P, 1, 1, Z) == b.ERR_NULL
+    assert c.pack_dint3(P, 4, 12, P, Z) == b.ERR_SHAPE               # eight codes per 24-bit word
+    assert c.pack_dint3(Z, 4, 16, P, Z) == b.ERR_NULL
+    assert c.unpack_dint3(P, 4, 16, Z, Z) == b.ERR_NULL
+    assert c.unpack_dint3(P, 0, 16, Z, Z) == b.OK
+    need = lib.load_library().dint_error_terms_workspace_bytes(8, 16, 128, 0)
+    assert need >= 16 * 128 * 9 + 8 * 128 * 4 + 2 * 8 * 16 * 4
+    W0 = ctypes.c_void_p(0x10000)
+    assert c.dint_error_terms(P, b.F16, 8, 128, 128, P, b.F16, 16, 128, Z, 0, 9, P, W0, 1 << 30, Z) == b.ERR_DTYPE
+    assert c.dint_error_terms(P, b.F16, 8, 128, 100, P, b.F16, 16, 128, Z, 0, 0, P, W0, 1 << 30, Z) == b.ERR_SHAPE
+    assert c.dint_error_terms(P, b.F16, 8, 128, 128, P, b.F16, 16, 128, Z, 0, 0, Z, W0, 1 << 30, Z) == b.ERR_NULL
+    assert c.dint_error_terms(P, b.F16, 8, 128, 128, P, b.F16, 16, 128, Z, 0, 0, P, W0, 100, Z) == b.ERR_WORKSPACE
+
 
 def test_product_path_has_no_cpu_fallback(lib, tmp_path):
     with pytest.raises(FileNotFoundError):
