@@ -265,12 +265,15 @@ def main():
         for i in range(max(3, reps // 10)):
             assert fn(*argsq[i % nring]) == 0
         torch.cuda.synchronize()
-        e0.record(stream)
-        for i in range(reps):
-            fn(*argsq[i % nring])
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps, per
+        runs = []
+        for _ in range(3):   # median of three timed loops
+            e0.record(stream)
+            for i in range(reps):
+                fn(*argsq[i % nring])
+            e1.record(stream)
+            torch.cuda.synchronize()
+            runs.append(e0.elapsed_time(e1) / reps)
+        return float(np.median(runs)), per
 
     decode_side = []
     if not args.no_prefill:
