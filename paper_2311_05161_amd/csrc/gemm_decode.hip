@@ -15,6 +15,10 @@
 //     towards HBM at any time.  Every load is issued unconditionally (tiles that do not exist are
 //     addressed out of range, which a buffer load answers with zeros and no traffic), so the
 //     s_waitcnt counts are static and a wave only ever waits for the one tile it is about to use.
+//   * start-up is bound by the CU's memory pipeline, which takes one 1 KB request per 16 clocks
+//     and serves requests in issue order: all nine waves first issue the (small, coalesced) loads
+//     of the quantization parameters, meet at a barrier, and only then issue the bulk loads, so
+//     that no wave's parameters queue behind another wave's weights.
 //   * per tile: one ds_read_b128 fetches the precomputed decode record of (channel, k-tile), the
 //     nibbles become int8 through the register LUT (w4a8_common.hpp), two MFMAs
 //     (v_mfma_i32_16x16x64_i8, the <= 16 token rows are the other operand) accumulate the biased
@@ -32,9 +36,11 @@ namespace w4a8 {
 constexpr int GV_CW = 8;                          // compute waves per workgroup
 constexpr int GV_THREADS = (GV_CW + 1) * WAVE;    // + 1 helper wave
 constexpr int GV_MAX_AT = 9;                      // k-tiles per compute wave -> K per split <= 9216 (5120 group-wise)
-constexpr int GV_STAGE = 6;                       // decode records staged per thread (grouped mode)
+constexpr int GV_STAGE = 6;                       // decode records a thread prepares at most
 constexpr int GV_LDS_BUDGET = 48 * 1024;          // bytes of decode records per workgroup
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
+constexpr int GV_RED_BYTES = 2 * GV_CW * 256 * 4; // partial sums of the compute waves, double buffered
+constexpr int GV_MAX_LDS = GV_RED_BYTES + GV_LDS_BUDGET;
 
 __device__ __forceinline__ void lds_barrier()
 {
@@ -84,7 +90,8 @@ struct GemvArgs {
 };
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
-// AT k-tile slots per compute wave, weight ring D n-tiles deep.
+// AT k-tile slots per compute wave, weight ring D n-tiles deep; D = 0: the workgroups own a
+// single n-tile each, so there is no ring and nothing is ever refilled.
 // ASYM: the activations carry a token zero-point zx (stored codes and zx both offset by -128);
 // the exact term zx * (sum of the weights) is taken out in int32, per tile (GROUPED) or once per
 // output after the waves' int32 sums have been added (!GROUPED) -- never in floating point, where
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     }
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     float *red = reinterpret_cast<float *>(smem);                        // [2][GV_CW][256]
-    v4u *rec = reinterpret_cast<v4u *>(smem + 2 * GV_CW * 256 * 4);      // [n-tile][channel][RS]
+    v4u *rec = reinterpret_cast<v4u *>(smem + GV_RED_BYTES);             // [n-tile][channel][RS]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -130,39 +137,56 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     const int RS = GROUPED ? (KTs | 1) : 1;
 
     // ---- quantization parameters of this workgroup -> decode records in LDS -------------------
-    // element e = (n-tile j, channel row, k-tile ktl), ktl fastest: consecutive lanes read
+    // Element e = (n-tile j, channel row, k-tile ktl), ktl fastest: consecutive lanes read
     // consecutive groups of one channel, i.e. consecutive addresses of step[] and zero[].
-    // Loads first, LUT arithmetic later.  Quotients by multiplication with an approximate
-    // reciprocal: exact here, since (e + 0.5) / d is at least 1 / (2 d) away from any integer
-    // and e < 2^13, d <= 64, against a relative error below 2^-21.
+    // Loads first (only the stages that exist, uniform over the workgroup), LUT arithmetic
+    // later.  Quotients by multiplication with an approximate reciprocal: exact here, since
+    // (e + 0.5) / d is at least 1 / (2 d) away from any integer and e < 2^13, d <= 64, against
+    // a relative error below 2^-21.
     int st_z[GV_STAGE], st_t[GV_STAGE];
     float st_s[GV_STAGE];
     const int n_rec = my_nt * 16 * recs_per_nt;
     const float inv_recs = __builtin_amdgcn_rcpf((float)recs_per_nt);
-    const float inv_tpg = __builtin_amdgcn_rcpf((float)a.tiles_per_group);
-#pragma unroll
-    for (int i = 0; i < GV_STAGE; ++i) {
-        if (!GROUPED && i > 0) break;
-        // unconditional (index clamped): keeps the loads of all stages in flight together
-        const int e = min((int)threadIdx.x + i * GV_THREADS, n_rec - 1);
-        const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;   // 16 j + row
-        const int ktl = e - t * recs_per_nt;
-        const int g = GROUPED ? (int)(((float)(kt_begin + ktl) + 0.5f) * inv_tpg) : 0;
-        const int idx = (nt0 * TILE_N + t) * a.ng + g;   // < N * ng <= N * K / 128 < 2^31
-        st_z[i] = a.zero[idx];
-        st_s[i] = a.step[idx];
-        st_t[i] = (ASYM && GROUPED) ? a.tsum[(nt0 * TILE_N + t) * KT + kt_begin + ktl] : 0;
-    }
-    auto write_records = [&]() {
+    auto issue_params = [&]() {
+        __amdgpu_buffer_rsrc_t rstep =
+            __builtin_amdgcn_make_buffer_rsrc((void *)a.step, 0, N * a.ng * 4, 0x00020000);
+        __amdgpu_buffer_rsrc_t rzero =
+            __builtin_amdgcn_make_buffer_rsrc((void *)a.zero, 0, N * a.ng, 0x00020000);
+        const float inv_tpg = __builtin_amdgcn_rcpf((float)a.tiles_per_group);
 #pragma unroll
         for (int i = 0; i < GV_STAGE; ++i) {
-            const int e = threadIdx.x + i * GV_THREADS;
-            if ((GROUPED || i == 0) && e < n_rec) {
-                const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
-                rec[t * RS + (e - t * recs_per_nt)] = decode_record(st_z[i], st_s[i], st_t[i], a.plain != 0);
+            // (a stage that is skipped leaves its registers unset: write_records skips it too)
+            if (i * GV_THREADS < n_rec) {
+                const int e = min((int)threadIdx.x + i * GV_THREADS, n_rec - 1);
+                const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;   // 16 j + row
+                const int ktl = e - t * recs_per_nt;
+                const int g = GROUPED ? (int)(((float)(kt_begin + ktl) + 0.5f) * inv_tpg) : 0;
+                const int idx = (nt0 * TILE_N + t) * a.ng + g;   // < N * ng <= N * K / 128 < 2^29
+                st_z[i] = __builtin_amdgcn_raw_buffer_load_b8(rzero, idx, 0, 0);
+                st_s[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rstep, idx * 4, 0, 0));
+                st_t[i] = (ASYM && GROUPED) ? a.tsum[(nt0 * TILE_N + t) * KT + kt_begin + ktl] : 0;
             }
         }
     };
+    auto write_records = [&]() {
+#pragma unroll
+        for (int i = 0; i < GV_STAGE; ++i) {
+            if (i * GV_THREADS < n_rec) {
+                const int e = (int)threadIdx.x + i * GV_THREADS;
+                const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
+                // (opaque copies: arithmetic on the loaded values must not be moved up to the
+                // loads, where it would wait for each stage in turn)
+                float sv = st_s[i];
+                int zv = st_z[i];
+                asm volatile("" : "+v"(sv), "+v"(zv));
+                if (e < n_rec)
+                    rec[t * RS + (e - t * recs_per_nt)] =
+                        decode_record(zv & 0xff, sv, st_t[i], a.plain != 0);
+            }
+        }
+    };
+
+    issue_params();
 
     if (wave == GV_CW) {
         // ================= helper wave: reduction across the compute waves + output ============
@@ -179,8 +203,9 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         }
         const bool zp = ASYM && !GROUPED && a.partial == nullptr;
         int wn = zp ? a.wsum[nt0 * TILE_N + (lane & 15)] : 0;   // fetched one n-tile ahead
+        lds_barrier();   // every wave's parameter loads are under way
         write_records();
-        lds_barrier();
+        lds_barrier();   // the records are complete
         for (int j = 0; j < my_nt; ++j) {
             lds_barrier();  // the compute waves have published their partial sums of n-tile j
             const int wn_next = (zp && j + 1 < my_nt) ? a.wsum[(nt0 + j + 1) * TILE_N + (lane & 15)] : 0;
@@ -221,14 +246,21 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     __amdgpu_buffer_rsrc_t rw =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.Wt, 0, (int)((int64_t)N * K / 2), 0x00020000);
     __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)a.Xq, 0, M * K, 0x00020000);
-    // activation operand: token row ln, bytes kb*32 .. +32 of the k-tile; rows >= M lie beyond the
-    // buffer and read as zero
-    const int voff_x = ln * K + kb * 32 + kt_begin * TILE_K;
+    // Activation operand of the matrix cores: lane (ln, kb) holds token row ln, bytes kb*32 .. +32
+    // of the k-tile.  Loading it in that pattern (16 rows per instruction, 16 bytes per lane and
+    // row) moves a third of the bytes per clock that a row-coalesced load does (measured on L2-
+    // resident data: 37 against 104 GB/s per CU), and at 16 tokens the activations are twice the
+    // bytes of a tile's weights.  So a quad of lanes reads 64 contiguous bytes of one row (lane l:
+    // row l / 4, bytes (l % 4) * 16 [+ 64]) and the fragments are transposed once through this
+    // wave's own rows of the reduction buffer.  Rows >= M lie beyond the buffer and read as zero.
+    const int voff_x = (lane >> 2) * K + (lane & 3) * 16 + kt_begin * TILE_K;
     const int wt_lane = lane * 16;
     const int tile0 = nt0 * KT + kt_begin + wave;       // first weight tile of this wave
 
+    lds_barrier();   // every wave's parameter loads are under way: now the bulk loads
     // slot [d][u]: k-tile u of an n-tile j with j % D == d; out of range when there is none
-    v4u p[D][AT], a0[AT], a1[AT];
+    constexpr int DR = D > 0 ? D : 1;   // ring rows
+    v4u p[DR][AT], a0[AT], a1[AT];
     auto load_w = [&](int j, int u) {
         const bool ok = j < my_nt && u < tpw;
         return __builtin_amdgcn_raw_buffer_load_b128(
@@ -240,23 +272,46 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         const int ktl = GROUPED ? min(wave + u * GV_CW, KTs - 1) : 0;
         return rec[(jr * 16 + ln) * RS + ktl];
     };
-    // Issue order = arrival order (a wave's loads return in order): after the parameters above,
-    // per slot the activations and the first n-tile's weights, then ring rows 1 .. D-1.
+    // Issue order = arrival order (a wave's loads return in order): after the parameters, per
+    // slot the activations and the first n-tile's weights, then ring rows 1 .. D-1.
 #pragma unroll
     for (int u = 0; u < AT; ++u) {
         // slots without a k-tile hold zero activations, so whatever is computed there adds nothing
         const int vo = u < tpw ? voff_x + (wave + u * GV_CW) * TILE_K : GV_OOB;
         a0[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, 0, 0);
-        a1[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo + 16, 0, 0);
+        a1[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo + 64, 0, 0);
         p[0][u] = load_w(0, u);
     }
 #pragma unroll
-    for (int d = 1; d < D; ++d)
+    for (int d = 1; d < DR; ++d)
 #pragma unroll
         for (int u = 0; u < AT; ++u) p[d][u] = load_w(d, u);
     order_fence();
     write_records();
-    lds_barrier();
+    lds_barrier();   // the records are complete
+
+    // fragments -> operand layout: lane (ln, kb) takes bytes kb*32 .. +32 of row ln, i.e. the
+    // 16-byte pieces 2 (kb % 2) and 2 (kb % 2) + 1 that lanes 4 ln + .. loaded, from the first
+    // (kb < 2) or second half-row load.  LDS executes a wave's accesses in order, so the two 1 KB
+    // staging rows are reused from slot to slot without further synchronization.
+    {
+        uint8_t *stg0 = reinterpret_cast<uint8_t *>(red + wave * 256);
+        uint8_t *stg1 = reinterpret_cast<uint8_t *>(red + (GV_CW + wave) * 256);
+        const uint8_t *src = ((kb & 2) ? stg1 : stg0) + (4 * ln + 2 * (kb & 1)) * 16;
+#pragma unroll
+        for (int u = 0; u < AT; ++u) {
+            *reinterpret_cast<v4u *>(stg0 + lane * 16) = a0[u];
+            *reinterpret_cast<v4u *>(stg1 + lane * 16) = a1[u];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            a0[u] = *reinterpret_cast<const v4u *>(src);
+            a1[u] = *reinterpret_cast<const v4u *>(src + 16);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
 
     const v4i zero4 = {0, 0, 0, 0};
     v4i acc = zero4;
@@ -302,7 +357,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             // after the last read of the old contents, so it can land in the same registers and
             // the ring needs no copies (which would have to wait for the data to arrive).
             order_fence();
-            if (refill) p[d][u] = load_w(j + D, u);
+            if (refill) p[d][u] = load_w(j + DR, u);
             order_fence();
             if (live) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c1, w1, acc, 0, 0, 0);
             if (GROUPED && live) {
@@ -354,13 +409,17 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 
     // whole rounds of D n-tiles with refill (loads past the last n-tile go out of range), then
     // the last my_nt % D n-tiles, which only consume
+    if (D == 0) {
+        step_ntile(0, 0, false);
+        return;
+    }
     int j0 = 0;
-    for (; j0 + D <= my_nt; j0 += D) {
+    for (; j0 + DR <= my_nt; j0 += DR) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) step_ntile(j0 + d, d, true);
+        for (int d = 0; d < DR; ++d) step_ntile(j0 + d, d, true);
     }
 #pragma unroll
-    for (int d = 0; d < D - 1; ++d)
+    for (int d = 0; d < DR - 1; ++d)
         if (j0 + d < my_nt) step_ntile(j0 + d, d, false);
 }
 
@@ -413,7 +472,7 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
     const int recs = grouped ? pl.kt_per_split : 1;
     const int rs = grouped ? (pl.kt_per_split | 1) : 1;
     const int q_lds = GV_LDS_BUDGET / (rs * 16 * 16);
-    const int q_stage = (grouped ? GV_STAGE * GV_THREADS : GV_THREADS) / (recs * 16);
+    const int q_stage = GV_STAGE * GV_THREADS / (recs * 16);
     const int q_cap = q_lds < q_stage ? q_lds : q_stage;
     if (q > q_cap) {
         q = q_cap;
@@ -423,31 +482,60 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
     pl.blocks_per_split = bps;
     pl.nt_lo = NT / bps;
     pl.nt_rem = NT % bps;
-    pl.lds_bytes = 2 * GV_CW * 256 * 4 + q * rs * 16 * 16;
+    pl.lds_bytes = GV_RED_BYTES + q * rs * 16 * 16;
     pl.partial_bytes = pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
     return pl;
 }
 
 template <bool GROUPED, bool ACC_OUT, bool ASYM>
-static void launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hipStream_t st)
+static int launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hipStream_t st)
 {
     const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits, (unsigned)batch);
+    // more than 64 KB of dynamic LDS has to be opted into, once per instance
 #define W4A8_GV_LAUNCH(AT_, D_)                                                                  \
-    hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>), grid, dim3(GV_THREADS),  \
-                       pl.lds_bytes, st, ga)
-    // ring depth: 8 - 10 KB per wave in flight, within the register budget of 9 waves per CU
+    do {                                                                                         \
+        static bool attr_set = false;                                                            \
+        if (pl.lds_bytes > 64 * 1024 && !attr_set) {                                             \
+            if (hipFuncSetAttribute((const void *)gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>,  \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,                  \
+                                    GV_MAX_LDS) != hipSuccess)                                   \
+                return W4A8_ERR_HIP;                                                             \
+            attr_set = true;                                                                     \
+        }                                                                                        \
+        hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>), grid,                 \
+                           dim3(GV_THREADS), pl.lds_bytes, st, ga);                              \
+    } while (0)
+    // ring depth: 8 - 10 KB per wave in flight, within the register budget of 9 waves per CU;
+    // no ring when every workgroup has a single n-tile (the accumulator hook keeps the ring form)
+#define W4A8_GV_CASE(AT_, D_)                                 \
+    case AT_:                                                 \
+        if (pl.q == 1 && !ACC_OUT) W4A8_GV_LAUNCH(AT_, 0);    \
+        else W4A8_GV_LAUNCH(AT_, D_);                         \
+        break
     switch (pl.at) {
-        case 1: W4A8_GV_LAUNCH(1, 4); break;
-        case 2: W4A8_GV_LAUNCH(2, 4); break;
-        case 3: W4A8_GV_LAUNCH(3, 3); break;
-        case 4: W4A8_GV_LAUNCH(4, 2); break;
-        case 5: W4A8_GV_LAUNCH(5, 2); break;
-        case 6: W4A8_GV_LAUNCH(6, 1); break;
-        case 7: W4A8_GV_LAUNCH(7, 1); break;
-        case 8: W4A8_GV_LAUNCH(8, 1); break;
-        default: W4A8_GV_LAUNCH(9, 1); break;
+        W4A8_GV_CASE(1, 4);
+        W4A8_GV_CASE(2, 4);
+        W4A8_GV_CASE(3, 3);
+        W4A8_GV_CASE(4, 2);
+        W4A8_GV_CASE(5, 2);
+        default:
+            // 6 .. 9 k-tiles per wave: per-channel weights only (see plan_gemv)
+            if constexpr (!GROUPED) {
+                switch (pl.at) {
+                    W4A8_GV_CASE(6, 1);
+                    W4A8_GV_CASE(7, 1);
+                    W4A8_GV_CASE(8, 1);
+                    W4A8_GV_CASE(9, 1);
+                    default: return W4A8_ERR_SHAPE;
+                }
+            } else {
+                return W4A8_ERR_SHAPE;
+            }
+            break;
     }
+#undef W4A8_GV_CASE
 #undef W4A8_GV_LAUNCH
+    return hip_status(hipGetLastError());
 }
 
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
@@ -468,25 +556,25 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
     ga.plain = plain;
     const bool asym = zp.zx != nullptr;
+    int rc;
     if (grouped) {
         // the per-tile zero-point term only exists in its own instances (asymmetric, grouped)
         if (asym) {
-            if (acc_out) launch_gemv_at<true, true, true>(pl, ga, (int)batch, st);
-            else launch_gemv_at<true, false, true>(pl, ga, (int)batch, st);
+            if (acc_out) rc = launch_gemv_at<true, true, true>(pl, ga, (int)batch, st);
+            else rc = launch_gemv_at<true, false, true>(pl, ga, (int)batch, st);
         } else {
-            if (acc_out) launch_gemv_at<true, true, false>(pl, ga, (int)batch, st);
-            else launch_gemv_at<true, false, false>(pl, ga, (int)batch, st);
+            if (acc_out) rc = launch_gemv_at<true, true, false>(pl, ga, (int)batch, st);
+            else rc = launch_gemv_at<true, false, false>(pl, ga, (int)batch, st);
         }
     } else {
         if (asym) {
-            if (acc_out) launch_gemv_at<false, true, true>(pl, ga, (int)batch, st);
-            else launch_gemv_at<false, false, true>(pl, ga, (int)batch, st);
+            if (acc_out) rc = launch_gemv_at<false, true, true>(pl, ga, (int)batch, st);
+            else rc = launch_gemv_at<false, false, true>(pl, ga, (int)batch, st);
         } else {
-            if (acc_out) launch_gemv_at<false, true, false>(pl, ga, (int)batch, st);
-            else launch_gemv_at<false, false, false>(pl, ga, (int)batch, st);
+            if (acc_out) rc = launch_gemv_at<false, true, false>(pl, ga, (int)batch, st);
+            else rc = launch_gemv_at<false, false, false>(pl, ga, (int)batch, st);
         }
     }
-    int rc = hip_status(hipGetLastError());
     if (rc != W4A8_OK || pl.splits == 1) return rc;
     return launch_gemv_combine(part, sx, grouped ? nullptr : step, zp, M, N, pl.splits, Y, y_dtype,
                                ldy, st);
