@@ -16,9 +16,9 @@
 //     addressed out of range, which a buffer load answers with zeros and no traffic), so the
 //     s_waitcnt counts are static and a wave only ever waits for the one tile it is about to use.
 //   * start-up is bound by the CU's memory pipeline, which takes one 1 KB request per 16 clocks
-//     and serves requests in issue order: all nine waves first issue the (small, coalesced) loads
-//     of the quantization parameters, meet at a barrier, and only then issue the bulk loads, so
-//     that no wave's parameters queue behind another wave's weights.
+//     and serves requests in issue order: the compute waves first issue the (small, coalesced)
+//     loads of the quantization parameters, meet at a barrier, and only then issue the bulk
+//     loads, so that no wave's parameters queue behind another wave's weights.
 //   * per tile: one ds_read_b128 fetches the precomputed decode record of (channel, k-tile), the
 //     nibbles become int8 through the register LUT (w4a8_common.hpp), two MFMAs
 //     (v_mfma_i32_16x16x64_i8, the <= 16 token rows are the other operand) accumulate the biased
@@ -36,7 +36,8 @@ namespace w4a8 {
 constexpr int GV_CW = 8;                          // compute waves per workgroup
 constexpr int GV_THREADS = (GV_CW + 1) * WAVE;    // + 1 helper wave
 constexpr int GV_MAX_AT = 9;                      // k-tiles per compute wave -> K per split <= 9216 (5120 group-wise)
-constexpr int GV_STAGE = 6;                       // decode records a thread prepares at most
+constexpr int GV_REC_THREADS = GV_CW * WAVE;      // the compute waves prepare the decode records
+constexpr int GV_STAGE = 7;                       // decode records such a thread prepares at most
 constexpr int GV_LDS_BUDGET = 48 * 1024;          // bytes of decode records per workgroup
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
 constexpr int GV_RED_BYTES = 2 * GV_CW * 256 * 4; // partial sums of the compute waves, double buffered
@@ -87,6 +88,7 @@ struct GemvArgs {
     int kt_per_split;      // k-tiles per K-split (blockIdx.y)
     int nt_lo, nt_rem;     // workgroup b owns nt_lo (+1 if b < nt_rem) consecutive n-tiles
     int plain;             // code space of ordinary INT4 (16 integer levels) instead of dINT4
+    int vec_store;         // Y and ldy allow 8-byte stores of four outputs
 };
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
@@ -156,8 +158,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 #pragma unroll
         for (int i = 0; i < GV_STAGE; ++i) {
             // (a stage that is skipped leaves its registers unset: write_records skips it too)
-            if (i * GV_THREADS < n_rec) {
-                const int e = min((int)threadIdx.x + i * GV_THREADS, n_rec - 1);
+            if (i * GV_REC_THREADS < n_rec) {
+                const int e = min((int)threadIdx.x + i * GV_REC_THREADS, n_rec - 1);
                 const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;   // 16 j + row
                 const int ktl = e - t * recs_per_nt;
                 const int g = GROUPED ? (int)(((float)(kt_begin + ktl) + 0.5f) * inv_tpg) : 0;
@@ -171,8 +173,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     auto write_records = [&]() {
 #pragma unroll
         for (int i = 0; i < GV_STAGE; ++i) {
-            if (i * GV_THREADS < n_rec) {
-                const int e = (int)threadIdx.x + i * GV_THREADS;
+            if (i * GV_REC_THREADS < n_rec) {
+                const int e = (int)threadIdx.x + i * GV_REC_THREADS;
                 const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
                 // (opaque copies: arithmetic on the loaded values must not be moved up to the
                 // loads, where it would wait for each stage in turn)
@@ -186,51 +188,68 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         }
     };
 
-    issue_params();
+    if (wave < GV_CW) issue_params();
 
     if (wave == GV_CW) {
         // ================= helper wave: reduction across the compute waves + output ============
-        // lane owns outputs o = lane + 64 i: token m = 4 i + lane / 16, channel lane % 16.
+        // lane owns token m = lane / 4 and the four channels 4 (lane % 4) .. + 3: one 16-byte LDS
+        // read per compute wave, one 8-byte store.
         // GROUPED: the waves publish fp32 sums (already scaled per group).  !GROUPED: they publish
         // their int32 accumulators; the sum is exact, then zero-point term, step / 8, token scale.
-        float sxm[4];
-        int zxm[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = 4 * i + (lane >> 4);
-            sxm[i] = (a.partial == nullptr && m < M) ? a.sx[m] : 0.f;
-            zxm[i] = (ASYM && !GROUPED && a.partial == nullptr && m < M) ? a.zx[m] : 0;
-        }
-        const bool zp = ASYM && !GROUPED && a.partial == nullptr;
-        int wn = zp ? a.wsum[nt0 * TILE_N + (lane & 15)] : 0;   // fetched one n-tile ahead
+        const int hm = lane >> 2, hc = (lane & 3) * 4;
+        const bool final_out = a.partial == nullptr;
+        const float sxm = (final_out && hm < M) ? a.sx[hm] : 0.f;
+        const bool zp = ASYM && !GROUPED && final_out;
+        const int zxm = (zp && hm < M) ? a.zx[hm] : 0;
+        const v4i zero4i = {0, 0, 0, 0};
+        // per-channel sums of the weights, fetched one n-tile ahead
+        auto load_wn = [&](int j) {
+            const int32_t *wp = a.wsum + (nt0 + j) * TILE_N + hc;
+            return v4i{wp[0], wp[1], wp[2], wp[3]};
+        };
+        v4i wn = zp ? load_wn(0) : zero4i;
         lds_barrier();   // every wave's parameter loads are under way
-        write_records();
         lds_barrier();   // the records are complete
         for (int j = 0; j < my_nt; ++j) {
             lds_barrier();  // the compute waves have published their partial sums of n-tile j
-            const int wn_next = (zp && j + 1 < my_nt) ? a.wsum[(nt0 + j + 1) * TILE_N + (lane & 15)] : 0;
-            const float *rb = red + (j & 1) * GV_CW * 256;
-            const float es = GROUPED ? 0.f : __uint_as_float(rec[j * 16 + (lane & 15)].z);
+            const v4i wn_next = (zp && j + 1 < my_nt) ? load_wn(j + 1) : zero4i;
+            const float *rb = red + (j & 1) * GV_CW * 256 + 4 * lane;
+            v4f sum = {0.f, 0.f, 0.f, 0.f};
+            v4i isum = zero4i;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int o = lane + i * 64;
-                const int m = o >> 4;
-                float sum = 0.f;
-                int isum = 0;
+            for (int w = 0; w < GV_CW; ++w) {   // fixed order: deterministic
+                const v4f part = *reinterpret_cast<const v4f *>(rb + w * 256);
+                if (GROUPED) sum += part;
+                else isum += v4i{__float_as_int(part.x), __float_as_int(part.y), __float_as_int(part.z),
+                                 __float_as_int(part.w)};
+            }
+            if (hm < M) {
+                const int n = (nt0 + j) * TILE_N + hc;
+                if (!final_out) {
+                    float *pp = a.partial + ((int64_t)split * M + hm) * N + n;
+                    *reinterpret_cast<v4f *>(pp) =
+                        GROUPED ? sum
+                                : v4f{__int_as_float(isum.x), __int_as_float(isum.y),
+                                      __int_as_float(isum.z), __int_as_float(isum.w)};
+                } else {
+                    uint16_t hh[4];
 #pragma unroll
-                for (int w = 0; w < GV_CW; ++w) {
-                    if (GROUPED) sum += rb[w * 256 + o];
-                    else isum += __float_as_int(rb[w * 256 + o]);
-                }
-                if (m < M) {
-                    const int n = (nt0 + j) * TILE_N + (o & 15);
-                    if (a.partial != nullptr) {
-                        a.partial[((int64_t)split * M + m) * N + n] = GROUPED ? sum : __int_as_float(isum);
+                    for (int i = 0; i < 4; ++i) {
+                        float v = sum[i];
+                        if (!GROUPED) {
+                            const float es = __uint_as_float(rec[j * 16 + hc + i].z);
+                            v = es * (float)(isum[i] - 4 * zxm * wn[i]);
+                        }
+                        const float out = sxm * v;
+                        hh[i] = (a.y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+                    }
+                    uint16_t *yp = a.Y + (int64_t)hm * a.ldy + n;
+                    if (a.vec_store) {
+                        *reinterpret_cast<uint2 *>(yp) =
+                            uint2{(uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16)};
                     } else {
-                        if (!GROUPED) sum = es * (float)(isum - 4 * zxm[i] * wn);
-                        const float out = sxm[i] * sum;
-                        a.Y[(int64_t)m * a.ldy + n] =
-                            (a.y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) yp[i] = hh[i];
                     }
                 }
             }
@@ -293,24 +312,29 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     // fragments -> operand layout: lane (ln, kb) takes bytes kb*32 .. +32 of row ln, i.e. the
     // 16-byte pieces 2 (kb % 2) and 2 (kb % 2) + 1 that lanes 4 ln + .. loaded, from the first
     // (kb < 2) or second half-row load.  LDS executes a wave's accesses in order, so the two 1 KB
-    // staging rows are reused from slot to slot without further synchronization.
-    {
-        uint8_t *stg0 = reinterpret_cast<uint8_t *>(red + wave * 256);
-        uint8_t *stg1 = reinterpret_cast<uint8_t *>(red + (GV_CW + wave) * 256);
-        const uint8_t *src = ((kb & 2) ? stg1 : stg0) + (4 * ln + 2 * (kb & 1)) * 16;
+    // staging rows are reused from slot to slot without further synchronization.  A workgroup
+    // with a single n-tile does this slot by slot, so that its first tiles are computed while
+    // the later fragments are still on their way (inside the ring loop the extra branch costs
+    // more than it hides).
+    uint8_t *stg0 = reinterpret_cast<uint8_t *>(red + wave * 256);
+    uint8_t *stg1 = reinterpret_cast<uint8_t *>(red + (GV_CW + wave) * 256);
+    const uint8_t *stg_src = ((kb & 2) ? stg1 : stg0) + (4 * ln + 2 * (kb & 1)) * 16;
+    auto to_operand_layout = [&](int u) __attribute__((always_inline)) {
+        *reinterpret_cast<v4u *>(stg0 + lane * 16) = a0[u];
+        *reinterpret_cast<v4u *>(stg1 + lane * 16) = a1[u];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        a0[u] = *reinterpret_cast<const v4u *>(stg_src);
+        a1[u] = *reinterpret_cast<const v4u *>(stg_src + 16);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    if (D != 0) {
 #pragma unroll
-        for (int u = 0; u < AT; ++u) {
-            *reinterpret_cast<v4u *>(stg0 + lane * 16) = a0[u];
-            *reinterpret_cast<v4u *>(stg1 + lane * 16) = a1[u];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            a0[u] = *reinterpret_cast<const v4u *>(src);
-            a1[u] = *reinterpret_cast<const v4u *>(src + 16);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
+        for (int u = 0; u < AT; ++u) to_operand_layout(u);
     }
 
     const v4i zero4 = {0, 0, 0, 0};
@@ -326,6 +350,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     auto step_ntile = [&](int j, int d, bool refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < AT; ++u) {
+            if (D == 0) to_operand_layout(u);
             // the record of the next slot is fetched one slot ahead
             v4u rn = r;
             if (u + 1 < AT) {
@@ -472,7 +497,7 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
     const int recs = grouped ? pl.kt_per_split : 1;
     const int rs = grouped ? (pl.kt_per_split | 1) : 1;
     const int q_lds = GV_LDS_BUDGET / (rs * 16 * 16);
-    const int q_stage = GV_STAGE * GV_THREADS / (recs * 16);
+    const int q_stage = GV_STAGE * GV_REC_THREADS / (recs * 16);
     const int q_cap = q_lds < q_stage ? q_lds : q_stage;
     if (q > q_cap) {
         q = q_cap;
@@ -555,6 +580,7 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     ga.tiles_per_group = (int)(G / TILE_K); ga.ng = (int)(K / G); ga.y_dtype = y_dtype;
     ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
     ga.plain = plain;
+    ga.vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
     const bool asym = zp.zx != nullptr;
     int rc;
     if (grouped) {
