@@ -28,8 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 # HBM bytes per gemv_kernel launch on this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script, scaled by a 256 MiB copy (profiles/gemv_kernel_C2_decode_hbm_traffic.md): 9,710,592 read + 131,072 written
-GEMV_C2_TRAFFIC_BYTES = 9841664
+# script, scaled by a 256 MiB copy (profiles/gemv_kernel_C2_decode_hbm_traffic.md): 9,689,088 read + 131,072 written
+GEMV_C2_TRAFFIC_BYTES = 9820160
 METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
 
 
