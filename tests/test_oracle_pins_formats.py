@@ -152,3 +152,106 @@ def test_dint4_trades_underflow_for_rounding_against_int4(oracle):
     n4 = np.count_nonzero(f.error_split(W, s, 0, "int4")[0])
     nd = np.count_nonzero(f.error_split(W, s, 0, "dint4")[0])
     assert nd < 0.6 * n4
+
+
+# ---- special value c = step / 2^t (App. A.5, Table 9) ---------------------------------------------
+
+def levels64_special(step, z, t):
+    return np.array([(k - z) * step for k in range(14)] + [step / 2 ** t, -step / 2 ** t], np.float64)
+
+
+def test_special_shift_one_is_the_dint4_rule(oracle):
+    _, W, s = syn.random_layer(11, 1, 512, 24)
+    for G in (0, 128):
+        c, st, z = oracle.formats.quantize_weight(W, s, G, "dint4", special_shift=1)
+        c0, st0, z0 = oracle.quantize_weight_dint4(W, s, G)
+        np.testing.assert_array_equal(c, c0)
+        np.testing.assert_array_equal(st, st0)
+        np.testing.assert_array_equal(z, z0)
+    with pytest.raises(ValueError):
+        oracle.formats.quantize_weight(W, s, 0, "dint4", special_shift=4)
+
+
+@pytest.mark.parametrize("t", [2, 3])
+@pytest.mark.parametrize("G", [0, 64])
+def test_special_value_codes_are_nearest_levels(oracle, t, G):
+    f = oracle.formats
+    _, W, s = syn.random_layer(12 + t, 1, 256, 24)
+    W = W.astype(np.float32)
+    W[0, :64] = np.abs(W[0, :64])
+    codes, step, zero = f.quantize_weight(W, s, G, "dint4", special_shift=t)
+    c1, step1, zero1 = f.quantize_weight(W, s, G, "dint4", special_shift=1)
+    np.testing.assert_array_equal(step, step1)          # the range rule does not depend on c
+    np.testing.assert_array_equal(zero, zero1)
+    g = 256 if G == 0 else G
+    wp = (W * s[None, :]).astype(np.float32).astype(np.float64)
+    dq = f.dequant(codes, step, zero, G, "dint4", special_shift=t)
+    units = f.level_units(codes, zero, G, "dint4", special_shift=t)
+    n_special = 0
+    for n in range(W.shape[0]):
+        for k in range(256 // g):
+            st, z = float(step[n, k]), int(zero[n, k])
+            lv = levels64_special(st, z, t)
+            x = wp[n, k * g:(k + 1) * g]
+            d = np.abs(x[:, None] - lv[None, :])
+            best = d.min(axis=1)
+            got = dq[n, k * g:(k + 1) * g]
+            assert np.all(np.abs(x - got) <= best + 1e-5 * st)            # nearest level (up to exact ties)
+            srt = np.sort(d, axis=1)
+            clear = srt[:, 1] - srt[:, 0] > 1e-4 * st                     # away from ties: the level itself
+            np.testing.assert_allclose(got[clear], lv[np.argmin(d, axis=1)][clear], rtol=0, atol=1e-9 * st)
+            # nothing larger than c/2 underflows to zero any more
+            assert np.all(got[np.abs(x) > st * 2.0 ** -(t + 1) * 1.00001] != 0)
+            u = units[n, k * g:(k + 1) * g]
+            np.testing.assert_allclose(u * (st / 2 ** t), got, rtol=0, atol=0)
+            n_special += int(np.sum(np.abs(u) == 1))
+    assert n_special > 20                                                  # the bands are exercised
+
+
+def test_hand_worked_special_value_rows(oracle):
+    f = oracle.formats
+    # range [-2, 11]: step 1, z = 2.  t = 2: c = 1/4, bands (1/8, 5/8];  t = 3: c = 1/8, bands (1/16, 9/16]
+    w2 = np.array([[-2.0, 11.0, 0.125, 0.13, 0.625, 0.63, -0.125, -0.13, -0.625, -0.63, 0.5, 0.3, 1.4, -1.5, 0.0, 3.0]],
+                  np.float32)
+    c, st, z = f.quantize_weight(w2, None, 0, "dint4", special_shift=2)
+    assert st[0, 0] == 1.0 and z[0, 0] == 2
+    assert c[0].tolist() == [0, 13, 2, 14, 14, 3, 2, 15, 15, 1, 14, 14, 3, 0, 2, 5]    # -1.5 ties to even: -2
+    np.testing.assert_array_equal(f.level_units(c, z, 0, "dint4", 2)[0],
+                                  [-8, 44, 0, 1, 1, 4, 0, -1, -1, -4, 1, 1, 4, -8, 0, 12])
+    np.testing.assert_array_equal(f.dequant(c, st, z, 0, "dint4", 2)[0],
+                                  [-2, 11, 0, .25, .25, 1, 0, -.25, -.25, -1, .25, .25, 1, -2, 0, 3])
+    w3 = np.array([[-2.0, 11.0, 0.0625, 0.07, 0.5625, 0.57, -0.0625, -0.07, -0.5625, -0.57, 0.5, 0.3, 0.05, 1.0, -1.0, 2.0]],
+                  np.float32)
+    c, st, z = f.quantize_weight(w3, None, 0, "dint4", special_shift=3)
+    assert c[0].tolist() == [0, 13, 2, 14, 14, 3, 2, 15, 15, 1, 14, 14, 2, 3, 1, 4]
+    np.testing.assert_array_equal(f.level_units(c, z, 0, "dint4", 3)[0],
+                                  [-16, 88, 0, 1, 1, 8, 0, -1, -1, -8, 1, 1, 0, 8, -8, 16])
+
+
+@pytest.mark.parametrize("t", [2, 3])
+def test_expand_special_is_the_same_product(oracle, t):
+    """The double-width rewriting against the definition, through the pinned ordinary dINT4 GEMM."""
+    f = oracle.formats
+    X, W, s = syn.random_layer(20 + t, 5, 256, 12)
+    Xq, sx = oracle.quantize_act_int8(X, s)
+    for G in (0, 128):
+        codes, step, zero = f.quantize_weight(W, s, G, "dint4", special_shift=t)
+        want = f.int_gemm(Xq, codes, zero, G, "dint4", special_shift=t).astype(np.int64)
+        c2, st2, z2 = f.expand_special(codes, step, zero, G, t)
+        g = 256 if G == 0 else G
+        ng = 256 // g
+        assert c2.shape == (12, 512) and st2.shape == (12, 2 * ng) and z2.shape == (12, 2 * ng)
+        np.testing.assert_array_equal(c2[:, :256], codes)
+        np.testing.assert_array_equal(st2[:, :ng], step)
+        np.testing.assert_array_equal(st2[:, ng:], (step * np.float32(1 - 2.0 ** (1 - t))).astype(np.float32))
+        both = oracle.int_gemm(np.concatenate([Xq, Xq], axis=1), oracle.pack_dint4(c2), z2, g).astype(np.int64)
+        a1, a2 = both[:, :, :ng], both[:, :, ng:]
+        np.testing.assert_array_equal(2 ** (t - 1) * a1 + (2 ** (t - 1) - 1) * a2, want)
+        # brute force of the definition on a few outputs
+        d = f.level_units(codes, zero, G, "dint4", t)
+        for (m, n, k) in [(0, 0, 0), (4, 11, ng - 1), (2, 5, 0)]:
+            assert want[m, n, k] == sum(int(Xq[m, j]) * int(d[n, j]) for j in range(k * g, (k + 1) * g))
+        # and the float outputs: the ordinary epilogue on the expanded operands is the variant's output
+        y = f.layer_output64(Xq, sx, codes, step, zero, G, "dint4", t)
+        y2 = f.layer_output64(np.concatenate([Xq, Xq], axis=1), sx, c2, st2, z2, g, "dint4", 1)
+        np.testing.assert_allclose(y2, y, rtol=1e-6, atol=1e-6 * np.abs(y).max())
