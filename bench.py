@@ -462,7 +462,9 @@ def main():
                        "channels_clipped": int((clip_idx > 0).sum().item())}
         # the underflow / rounding split of the output error (weight quantization alone) on the same layer
         terms = {}
-        for fname, fid in (("int4", w.FMT_INT4), ("dint4", w.FMT_DINT4), ("dint3", w.FMT_DINT3)):
+        for fname, fid in (("int4", w.FMT_INT4), ("dint4", w.FMT_DINT4), ("dint3", w.FMT_DINT3),
+                           ("dint4_special_step_over_4", w.FMT_DINT4_C4),
+                           ("dint4_special_step_over_8", w.FMT_DINT4_C8)):
             tt = w.dint_error_terms(Xc_d, Wd, s_best, G, fid).cpu().numpy()
             terms[fname] = {"underflow": float(f"{tt[0]:.5g}"), "rounding": float(f"{tt[1]:.5g}"),
                             "cross": float(f"{tt[2]:.5g}"), "underflowing_weights": int(tt[3])}

@@ -59,7 +59,13 @@ typedef enum { W4A8_F32 = 0, W4A8_F16 = 1, W4A8_BF16 = 2 } w4a8_dtype;
 enum { W4A8_LAYOUT_CANONICAL = 0, W4A8_LAYOUT_TILED = 1 };
 
 /* Weight formats sharing the 4-bit code space (see quantize_weight_format). */
-enum { W4A8_FMT_DINT4 = 0, W4A8_FMT_INT4 = 1, W4A8_FMT_DINT3 = 2 };
+enum {
+    W4A8_FMT_DINT4 = 0,
+    W4A8_FMT_INT4 = 1,
+    W4A8_FMT_DINT3 = 2,
+    W4A8_FMT_DINT4_C4 = 3, /* dINT4 with the special value step/4 (quantizer and expand_special_value only) */
+    W4A8_FMT_DINT4_C8 = 4  /* ... step/8 */
+};
 
 /* Per-token INT8 activation quantization with the AQAS scale folded in
  * (Eq. 1, factor Q(diag(s)^-1 X); token-wise 8-bit, App. A.1):
@@ -271,6 +277,31 @@ int w4a8_gemm_format(const int8_t *Xq, const float *sx, int64_t M, const uint8_t
                      int format, void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *workspace,
                      size_t workspace_bytes, void *stream);
 
+/* ---- The special value of dINT4 (App. A.5, Table 9: c = step/4 and step/8 in place of step/2).
+ * quantize_weight_format with W4A8_FMT_DINT4_C4 / _C8 keeps dINT4's code space (14 = +c, 15 = -c) and
+ * rounds to the nearest level: +c for c/2 < w' <= (step + c)/2, i.e. 2^-(t+1) < w'/step <= 1/2 + 2^-(t+1)
+ * with c = step / 2^t, ends open / closed as in Eq. 5, -c mirrored (for t = 1 this is Eq. 5 itself).
+ * The GEMMs only know c = step/2.  Since  +-c = +-step/2 -+ (1 - 2^(1-t)) step/2,  such a matrix is the
+ * ordinary dINT4 matrix of twice the width that expand_special_value writes:
+ *     codes2 [N, 2K]:  columns 0..K-1 the codes; columns K..2K-1 the special codes with their signs
+ *                      exchanged (14 <-> 15) and every other code replaced by the group's zero level z
+ *     step2  [N, 2K/G]: the steps, then (1 - 2^(1-t)) * step (one binary32 multiply);  zero2: zero twice
+ * Pack codes2 with pack_dint4 (N x 2K) and call w4a8_gemm_special, which multiplies it with [Xq | Xq]:
+ * Y as w4a8_gemm would give for the variant format (same fp32 order over the 2K/G groups), and
+ * acc_out [M, N, 2K/G] with the two sums A1 (groups 0..K/G-1) and A2 of every group, from which the sum
+ * in units of step / 2^t is  2^(t-1) A1 + (2^(t-1) - 1) A2.  Twice the work of w4a8_gemm: a tool for the
+ * format sweep, not a serving path.
+ *   group_size: 0 (per channel) or a multiple of 128 that divides K; 2K <= 65536; other limits, workspace
+ *   rules and errors as for w4a8_gemm with K replaced by 2K (the workspace also holds [Xq | Xq]). */
+int expand_special_value(const uint8_t *codes, const float *step, const uint8_t *zero, int64_t N, int64_t K,
+                         int64_t group_size, int format, uint8_t *codes2, float *step2, uint8_t *zero2,
+                         void *stream);
+size_t w4a8_gemm_special_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout);
+int w4a8_gemm_special(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wp2, int layout,
+                      const float *step2, const uint8_t *zero2, int64_t N, int64_t K, int64_t group_size,
+                      void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
 /* 3-bit storage of dINT3 codes: 0..5 stay, special codes 14 / 15 become 6 / 7; code i of each group of
  * eight consecutive codes of a row sits at bits 3i..3i+2 of a little-endian 24-bit word (three bytes).
  *   codes [N, K] in the 4-bit code space, K % 8 == 0      packed [N, 3K/8] bytes
@@ -284,6 +315,7 @@ int unpack_dint3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, vo
  *     terms[0] = sum (X' Delta_u^T)^2    terms[1] = sum (X' Delta_r^T)^2
  *     terms[2] = sum 2 (X' Delta_u^T)(X' Delta_r^T)        terms[3] = number of underflowing weights
  * (their first three add up to the squared output error of weight quantization alone).
+ *   format: any W4A8_FMT_* (the special-value variants included);
  *   X [M, ldx], W [N, ldw] of their dtypes; terms out [4] double (device);
  *   workspace of dint_error_terms_workspace_bytes(M, N, K, group_size) bytes, 256-byte aligned. */
 size_t dint_error_terms_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size);

@@ -176,25 +176,25 @@ def unpack3(packed):
     return out.reshape(N, 8 * (B // 3)).astype(np.uint8)
 
 
-def error_split(W, s, group_size=0, fmt="dint4"):
+def error_split(W, s, group_size=0, fmt="dint4", special_shift=1):
     """The split of Sec. 4.1: with W' = W diag(s) and Wq its dequantized codes, the error Wq - W' on
     the weights whose quantized value is zero (underflow, Delta_u) and on the others (rounding,
     Delta_r).  Returns (Delta_u, Delta_r) in float64; they have disjoint supports and add up to the
     total error."""
     W = np.asarray(W).astype(F32)
     wp = (W * np.asarray(s, F32)[None, :]).astype(F32) if s is not None else W
-    codes, step, zero = quantize_weight(W, s, group_size, fmt)
-    wq = dequant(codes, step, zero, group_size, fmt)
+    codes, step, zero = quantize_weight(W, s, group_size, fmt, special_shift)
+    wq = dequant(codes, step, zero, group_size, fmt, special_shift)
     delta = wq - wp.astype(np.float64)
     under = wq == 0.0
     return np.where(under, delta, 0.0), np.where(under, 0.0, delta)
 
 
-def output_error_terms(X, W, s, group_size=0, fmt="dint4"):
+def output_error_terms(X, W, s, group_size=0, fmt="dint4", special_shift=1):
     """The three terms of Eq. 4 on activations X [M,K] (unquantized, X' = X diag(s)^-1 in float64):
     sum (Delta_u X')^2, sum (Delta_r X')^2, sum 2 (Delta_u X')(Delta_r X'); their sum is the squared
     output error of weight quantization alone."""
-    du, dr = error_split(W, s, group_size, fmt)
+    du, dr = error_split(W, s, group_size, fmt, special_shift)
     Xs = np.asarray(X, np.float64)
     if s is not None:
         Xs = Xs * (F32(1) / np.asarray(s, F32)).astype(np.float64)[None, :]

@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     quantize_value_dint4,
     FMT_DINT3, FMT_DINT4, FMT_INT4, quantize_weight_format, w4a8_gemm_format, pack_dint3, unpack_dint3, pack_format, unpack_format,
     dint_error_terms,
+    FMT_DINT4_C4, FMT_DINT4_C8, expand_special_value, w4a8_gemm_special,
     aqas_channel_absmax, aqas_scale, aqas_search, dint4_clipped_params, aqas_clip_search,
 )

@@ -30,8 +30,9 @@ EXPORTS = (
     "quantize_weight_format", "w4a8_gemm_format", "pack_dint3", "unpack_dint3", "pack_format",
     "unpack_format",
     "dint_error_terms_workspace_bytes", "dint_error_terms",
+    "expand_special_value", "w4a8_gemm_special_workspace_bytes", "w4a8_gemm_special",
 )
-FMT_DINT4, FMT_INT4, FMT_DINT3 = 0, 1, 2
+FMT_DINT4, FMT_INT4, FMT_DINT3, FMT_DINT4_C4, FMT_DINT4_C8 = 0, 1, 2, 3, 4
 
 _lib = None
 
@@ -99,6 +100,12 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.pack_format.restype = ci
     lib.unpack_format.argtypes = [vp, i64, i64, vp, ci, ci, vp]
     lib.unpack_format.restype = ci
+    lib.expand_special_value.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp, vp, vp]
+    lib.expand_special_value.restype = ci
+    lib.w4a8_gemm_special_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
+    lib.w4a8_gemm_special_workspace_bytes.restype = sz
+    lib.w4a8_gemm_special.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, vp, ci, i64, vp, vp, sz, vp]
+    lib.w4a8_gemm_special.restype = ci
     lib.pack_dint3.argtypes = [vp, i64, i64, vp, vp]
     lib.pack_dint3.restype = ci
     lib.unpack_dint3.argtypes = [vp, i64, i64, vp, vp]
@@ -407,6 +414,34 @@ def unpack_format(packed: torch.Tensor, N: int, K: int, layout: int = LAYOUT_TIL
     _check(load_library().unpack_format(_ptr(packed), N, K, _ptr(out), int(layout), int(fmt), _stream()),
            "unpack_format")
     return out
+
+
+def expand_special_value(codes, step, zero, group_size: int = 0, fmt: int = FMT_DINT4_C4):
+    """dINT4 codes with special value step/4 or step/8 -> ordinary dINT4 operands of twice the width."""
+    N, K = codes.shape
+    ng = step.shape[1]
+    codes2 = torch.empty((N, 2 * K), dtype=torch.uint8, device=codes.device)
+    step2 = torch.empty((N, 2 * ng), dtype=torch.float32, device=codes.device)
+    zero2 = torch.empty((N, 2 * ng), dtype=torch.uint8, device=codes.device)
+    _check(load_library().expand_special_value(_ptr(codes), _ptr(step), _ptr(zero), N, K, int(group_size or 0),
+                                               int(fmt), _ptr(codes2), _ptr(step2), _ptr(zero2), _stream()),
+           "expand_special_value")
+    return codes2, step2, zero2
+
+
+def w4a8_gemm_special(Xq, sx, Wp2, step2, zero2, N: int, K: int, group_size: int = 0,
+                      out_dtype=torch.float16, want_acc=False):
+    """The GEMM on the operands of expand_special_value (packed N x 2K); acc [M, N, 2K/G] if asked for."""
+    M = Xq.shape[0]
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    G = K if not group_size else int(group_size)
+    acc = torch.empty((M, N, 2 * K // G), dtype=torch.int32, device=Xq.device) if want_acc else None
+    need = load_library().w4a8_gemm_special_workspace_bytes(M, N, K, int(group_size or 0), LAYOUT_TILED)
+    ws = torch.empty((max(need, 1),), dtype=torch.uint8, device=Xq.device)
+    _check(load_library().w4a8_gemm_special(_ptr(Xq), _ptr(sx), M, _ptr(Wp2), LAYOUT_TILED, _ptr(step2),
+                                            _ptr(zero2), N, K, int(group_size or 0), _ptr(Y), _DTYPES[Y.dtype],
+                                            N, _ptr(acc), _ptr(ws), need, _stream()), "w4a8_gemm_special")
+    return (Y, acc) if want_acc else Y
 
 
 def pack_dint3(codes: torch.Tensor) -> torch.Tensor:

@@ -59,7 +59,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
                 const int32_t *wsum, const int32_t *tsum, int64_t N, int64_t K, int64_t group_size,
                 void *Y, int y_dtype, int64_t ldy,
                 int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream,
-                int format = W4A8_FMT_DINT4)
+                int format = W4A8_FMT_DINT4, bool validate_only = false)
 {
     if (!valid_layout(layout)) return W4A8_ERR_DTYPE;
     if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
@@ -84,6 +84,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
         if (!workspace || workspace_bytes < ws.total) return W4A8_ERR_WORKSPACE;
         if ((uintptr_t)workspace % WS_ALIGN != 0) return W4A8_ERR_WORKSPACE;
     }
+    if (validate_only) return W4A8_OK;
     hipStream_t st = (hipStream_t)stream;
     uint8_t *wsb = (uint8_t *)workspace;
     const ZeroPoint zp = {zx, wsum, tsum};
@@ -490,7 +491,7 @@ int quantize_weight_format(const void *W, int w_dtype, int64_t N, int64_t K, int
                            float *step, uint8_t *zero, void *stream)
 {
     if (!valid_dtype(w_dtype)) return W4A8_ERR_DTYPE;
-    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    if (format < W4A8_FMT_DINT4 || format > W4A8_FMT_DINT4_C8) return W4A8_ERR_DTYPE;
     int64_t G = group_size;
     if (N < 0 || K < 1 || ldw < K || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
     if (N == 0) return W4A8_OK;
@@ -532,6 +533,52 @@ int unpack_format(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, i
     return launch_unpack(packed, N, K, codes, layout, (hipStream_t)stream, format == W4A8_FMT_INT4);
 }
 
+int expand_special_value(const uint8_t *codes, const float *step, const uint8_t *zero, int64_t N, int64_t K,
+                         int64_t group_size, int format, uint8_t *codes2, float *step2, uint8_t *zero2,
+                         void *stream)
+{
+    if (format != W4A8_FMT_DINT4_C4 && format != W4A8_FMT_DINT4_C8) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (N < 0 || K < 1 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (N == 0) return W4A8_OK;
+    if (!codes || !step || !zero || !codes2 || !step2 || !zero2) return W4A8_ERR_NULL;
+    return launch_expand_special(codes, step, zero, N, K, G, format == W4A8_FMT_DINT4_C4 ? 2 : 3, codes2,
+                                 step2, zero2, (hipStream_t)stream);
+}
+
+size_t w4a8_gemm_special_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout)
+{
+    int64_t G = group_size;
+    if (M <= 0 || N <= 0 || !resolve_group(K, G)) return 0;
+    return align_up((size_t)(M * 2 * K)) + plan_workspace(M, N, 2 * K, G, layout).total;
+}
+
+int w4a8_gemm_special(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wp2, int layout,
+                      const float *step2, const uint8_t *zero2, int64_t N, int64_t K, int64_t group_size,
+                      void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    int64_t G = group_size;
+    if (M < 0 || N < 0 || !resolve_group(K, G) || K % TILE_K != 0 || 2 * K > MAX_K) return W4A8_ERR_SHAPE;
+    if (M == 0 || N == 0) return W4A8_OK;
+    if (!Xq) return W4A8_ERR_NULL;
+    if ((uintptr_t)Xq % 16 != 0) return W4A8_ERR_SHAPE;
+    const size_t xx_bytes = align_up((size_t)(M * 2 * K));
+    if (!workspace || (uintptr_t)workspace % WS_ALIGN != 0 || workspace_bytes < xx_bytes)
+        return W4A8_ERR_WORKSPACE;
+    int8_t *xx = (int8_t *)workspace;
+    uint8_t *rest = (uint8_t *)workspace + xx_bytes;
+    // all of the GEMM's own checks first: nothing is launched when an argument is wrong
+    int rc = gemm_common(xx, sx, nullptr, M, Wp2, layout, step2, zero2, nullptr, nullptr, N, 2 * K, G, Y,
+                         y_dtype, ldy, acc_out, rest, workspace_bytes - xx_bytes, stream, W4A8_FMT_DINT4,
+                         true);
+    if (rc != W4A8_OK) return rc;
+    rc = launch_repeat_activations(Xq, M, K, xx, (hipStream_t)stream);
+    if (rc != W4A8_OK) return rc;
+    return gemm_common(xx, sx, nullptr, M, Wp2, layout, step2, zero2, nullptr, nullptr, N, 2 * K, G, Y,
+                       y_dtype, ldy, acc_out, rest, workspace_bytes - xx_bytes, stream, W4A8_FMT_DINT4);
+}
+
 int pack_dint3(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, void *stream)
 {
     if (N < 0 || K < 1 || K % 8 != 0) return W4A8_ERR_SHAPE;
@@ -560,7 +607,8 @@ int dint_error_terms(const void *X, int x_dtype, int64_t M, int64_t K, int64_t l
                      double *terms, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!valid_dtype(x_dtype) || !valid_dtype(w_dtype)) return W4A8_ERR_DTYPE;
-    if (format != W4A8_FMT_DINT4 && format != W4A8_FMT_INT4 && format != W4A8_FMT_DINT3) return W4A8_ERR_DTYPE;
+    if (format < W4A8_FMT_DINT4 || format > W4A8_FMT_DINT4_C8) return W4A8_ERR_DTYPE;
+    const int special = format == W4A8_FMT_INT4 ? 0 : (format == W4A8_FMT_DINT4_C4 ? 2 : (format == W4A8_FMT_DINT4_C8 ? 3 : 1));
     int64_t G = group_size;
     if (M < 1 || N < 1 || !resolve_group(K, G) || K % 2 != 0 || ldx < K || ldw < K) return W4A8_ERR_SHAPE;
     if (!X || !W || !terms) return W4A8_ERR_NULL;
@@ -573,7 +621,7 @@ int dint_error_terms(const void *X, int x_dtype, int64_t M, int64_t K, int64_t l
     int rc = launch_weight_quant(W, w_dtype, N, K, ldw, s, G, 0, ws + w.codes, (float *)(ws + w.step),
                                  ws + w.zero, format, st);
     if (rc != W4A8_OK) return rc;
-    if ((rc = launch_error_split(W, w_dtype, N, K, ldw, s, G, format != W4A8_FMT_INT4, ws + w.codes,
+    if ((rc = launch_error_split(W, w_dtype, N, K, ldw, s, G, special, ws + w.codes,
                                  (const float *)(ws + w.step), ws + w.zero, du, dr, st)) != W4A8_OK)
         return rc;
     if ((rc = launch_scale_activations(X, x_dtype, M, K, ldx, s, xs, st)) != W4A8_OK) return rc;

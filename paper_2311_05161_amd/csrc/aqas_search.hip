@@ -281,9 +281,12 @@ __global__ __launch_bounds__(256) void error_split_kernel(const T *__restrict__ 
     const int64_t pi = n * (K / G) + k / G;
     const float w = to_f32(W[n * ldw + k]);
     const float wp = s ? w * s[k] : w;
+    // special: 0 = no special levels, t = 1..3: codes 14 / 15 are +-step / 2^t
     const int code = codes[i] & 15, z = zero[pi];
-    const int d = (special && code >= 14) ? (code == 14 ? 1 : -1) : 2 * (code - z);   // half steps
-    const float wq = (float)d * (0.5f * step[pi]);
+    const int t = special ? special : 1;
+    const int d = (special && code >= 14) ? (code == 14 ? 1 : -1) : (code - z) * (1 << t);   // units of step / 2^t
+    const float unit = step[pi] * (t == 1 ? 0.5f : (t == 2 ? 0.25f : 0.125f));
+    const float wq = (float)d * unit;
     const float delta = wq - wp;
     du[i] = d == 0 ? delta : 0.0f;
     dr[i] = d == 0 ? 0.0f : delta;

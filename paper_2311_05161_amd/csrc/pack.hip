@@ -247,4 +247,75 @@ int launch_unpack3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, 
     return hip_status(hipGetLastError());
 }
 
+// ---- dINT4 with the special value c = step / 2^t, t = 2, 3 (App. A.5, Table 9) as an ordinary dINT4
+// matrix of twice the width:  +-c = +-step/2 -+ (1 - 2^(1-t)) step/2.  Columns K .. 2K-1 repeat the
+// groups with step' = (1 - 2^(1-t)) step, the same zero-points, the special codes with their signs
+// exchanged and every other code replaced by the zero level z.
+__global__ __launch_bounds__(PK_THREADS) void expand_special_codes_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ zero, int64_t N, int64_t K, int64_t G,
+    uint8_t *__restrict__ out)
+{
+    const int64_t total = N * K;
+    const int64_t ng = K / G;
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const int64_t n = i / K, k = i - n * K;
+        const uint8_t c = codes[i];
+        const uint8_t z = zero[n * ng + k / G];
+        out[n * 2 * K + k] = c;
+        out[n * 2 * K + K + k] = c == 14 ? 15 : (c == 15 ? 14 : z);
+    }
+}
+
+__global__ __launch_bounds__(PK_THREADS) void expand_special_params_kernel(
+    const float *__restrict__ step, const uint8_t *__restrict__ zero, int64_t N, int64_t ng, float factor,
+    float *__restrict__ step2, uint8_t *__restrict__ zero2)
+{
+    const int64_t total = N * ng;
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const int64_t n = i / ng, g = i - n * ng;
+        const float st = step[i];
+        const uint8_t z = zero[i];
+        step2[n * 2 * ng + g] = st;
+        step2[n * 2 * ng + ng + g] = st * factor;
+        zero2[n * 2 * ng + g] = z;
+        zero2[n * 2 * ng + ng + g] = z;
+    }
+}
+
+int launch_expand_special(const uint8_t *codes, const float *step, const uint8_t *zero, int64_t N,
+                          int64_t K, int64_t G, int shift, uint8_t *codes2, float *step2, uint8_t *zero2,
+                          hipStream_t st)
+{
+    const float factor = shift == 2 ? 0.5f : 0.75f;   // 1 - 2^(1-t)
+    hipLaunchKernelGGL(expand_special_codes_kernel, dim3(grid_for(N * K)), dim3(PK_THREADS), 0, st, codes,
+                       zero, N, K, G, codes2);
+    hipLaunchKernelGGL(expand_special_params_kernel, dim3(grid_for(N * (K / G))), dim3(PK_THREADS), 0, st,
+                       step, zero, N, K / G, factor, step2, zero2);
+    return hip_status(hipGetLastError());
+}
+
+// out [M, 2K] = [Xq | Xq], 16 bytes per thread (K % 16 == 0, both pointers 16-byte aligned)
+__global__ __launch_bounds__(PK_THREADS) void repeat_activations_kernel(const uint4 *__restrict__ Xq,
+                                                                       int64_t M, int64_t K16,
+                                                                       uint4 *__restrict__ out)
+{
+    const int64_t total = M * K16;
+    for (int64_t i = (int64_t)blockIdx.x * PK_THREADS + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * PK_THREADS) {
+        const int64_t m = i / K16, k = i - m * K16;
+        const uint4 v = Xq[i];
+        out[m * 2 * K16 + k] = v;
+        out[m * 2 * K16 + K16 + k] = v;
+    }
+}
+
+int launch_repeat_activations(const int8_t *Xq, int64_t M, int64_t K, int8_t *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(repeat_activations_kernel, dim3(grid_for(M * (K / 16))), dim3(PK_THREADS), 0, st,
+                       (const uint4 *)Xq, M, K / 16, (uint4 *)out);
+    return hip_status(hipGetLastError());
+}
+
 }  // namespace w4a8

@@ -175,7 +175,7 @@ int launch_pack3(const uint8_t *codes, int64_t N, int64_t K, uint8_t *packed, hi
 int launch_unpack3(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, hipStream_t st);
 // error split of Sec. 4.1: du / dr [N,K] = quantization error of W diag(s) on the weights that
 // quantize to zero / on the others; xs = X diag(s)^-1 in fp32; terms = {sum pu^2, sum pr^2,
-// sum 2 pu pr, number of underflowing weights}
+// sum 2 pu pr, number of underflowing weights}; special: 0 = no special levels, t = 1..3: +-step / 2^t
 int launch_error_split(const void *W, int w_dtype, int64_t N, int64_t K, int64_t ldw, const float *s,
                        int64_t G, int special, const uint8_t *codes, const float *step,
                        const uint8_t *zero, float *du, float *dr, hipStream_t st);
@@ -195,6 +195,11 @@ int launch_unpack(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, i
 int launch_repack_canonical_to_tiled(const uint8_t *canon, int64_t N, int64_t K, uint8_t *tiled,
                                      hipStream_t st, int plain = 0);
 int launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st);
+// dINT4 with special value step / 2^shift (shift 2, 3) -> ordinary dINT4 matrix [N, 2K]; [Xq | Xq]
+int launch_expand_special(const uint8_t *codes, const float *step, const uint8_t *zero, int64_t N,
+                          int64_t K, int64_t G, int shift, uint8_t *codes2, float *step2, uint8_t *zero2,
+                          hipStream_t st);
+int launch_repeat_activations(const int8_t *Xq, int64_t M, int64_t K, int8_t *out, hipStream_t st);
 // Launch shape of the decode GEMV for a problem size (also sizes its K-split workspace).
 struct GemvPlan {
     int splits;            // K is cut into this many ranges, each handled by its own workgroups

@@ -41,10 +41,12 @@ __device__ __forceinline__ void loadv(const T *p, float (&v)[V])
 }
 
 // Format of the code space (Sec. 4.2): p uniform steps, with or without the two special levels
-// +-step/2.  dINT4: p = 13, special; dINT3: p = 5, special; plain INT4: p = 15, none.
+// +-c, c = step / 2^shift.  dINT4: p = 13, special, shift 1 (Eq. 5); dINT3: p = 5, special; plain
+// INT4: p = 15, none; shift 2 / 3: the other special values of the sweep in App. A.5 (Table 9).
 struct CodeFormat {
     int p;
     int special;
+    int shift = 1;
 };
 __host__ __device__ constexpr CodeFormat dint4_format() { return CodeFormat{DINT4_P, 1}; }
 
@@ -52,8 +54,12 @@ __device__ __forceinline__ uint32_t dint4_code(float w, float istep, int z, Code
 {
     const float u = w * istep;
     if (f.special) {
-        if (u > 0.25f && u <= 0.75f) return 14u;     // c1: +step/2
-        if (u >= -0.75f && u < -0.25f) return 15u;   // c2: -step/2
+        // nearest level: the band of +c runs from the midpoint between 0 and c to the midpoint
+        // between c and one step (0.25 .. 0.75 for c = step/2), ends as in Eq. 5; both bounds exact
+        const float lo_t = f.shift == 1 ? 0.25f : (f.shift == 2 ? 0.125f : 0.0625f);
+        const float hi_t = 0.5f + lo_t;
+        if (u > lo_t && u <= hi_t) return 14u;       // c1: +c
+        if (u >= -hi_t && u < -lo_t) return 15u;     // c2: -c
     }
     int c = (int)__builtin_rintf(u) + z;
     c = c < 0 ? 0 : c;
@@ -244,6 +250,8 @@ int launch_weight_quant(const void *W, int w_dtype, int64_t N, int64_t K, int64_
         case W4A8_FMT_DINT4: fmt = CodeFormat{13, 1}; break;
         case W4A8_FMT_INT4: fmt = CodeFormat{15, 0}; break;
         case W4A8_FMT_DINT3: fmt = CodeFormat{5, 1}; break;
+        case W4A8_FMT_DINT4_C4: fmt = CodeFormat{13, 1, 2}; break;
+        case W4A8_FMT_DINT4_C8: fmt = CodeFormat{13, 1, 3}; break;
         default: return W4A8_ERR_DTYPE;
     }
     switch (w_dtype) {

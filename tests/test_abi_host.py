@@ -179,7 +179,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert c.aqas_clip_search(P, P, b.F16, 32, 64, 256, 256, 256, P, 0, P, P, P, Z, Z, 0, Z) == b.ERR_WORKSPACE
 
     # weight-format variants, 3-bit packing, error split
-    assert c.quantize_weight_format(P, b.F16, 16, 128, 128, Z, 0, 3, 0, P, P, P, Z) == b.ERR_DTYPE   # format id
+    assert c.quantize_weight_format(P, b.F16, 16, 128, 128, Z, 0, 5, 0, P, P, P, Z) == b.ERR_DTYPE   # format id
     assert c.quantize_weight_format(P, b.F16, 16, 128, 64, Z, 0, 1, 0, P, P, P, Z) == b.ERR_SHAPE
     assert c.quantize_weight_format(P, b.F16, 16, 128, 128, Z, 0, 2, 0, Z, P, P, Z) == b.ERR_NULL
     assert c.w4a8_gemm_format(P, P, 4, P, 1, P, P, 16, 128, 0, 7, P, b.F16, 16, Z, Z, 0, Z) == b.ERR_DTYPE
@@ -191,6 +191,31 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert c.pack_dint3(Z, 4, 16, P, Z) == b.ERR_NULL
     assert c.unpack_dint3(P, 4, 16, Z, Z) == b.ERR_NULL
     assert c.unpack_dint3(P, 0, 16, Z, Z) == b.OK
+    # special value step/4, step/8: expansion to double width and the GEMM on it
+    assert c.expand_special_value(P, P, P, 16, 128, 0, 0, P, P, P, Z) == b.ERR_DTYPE     # only formats 3, 4
+    assert c.expand_special_value(P, P, P, 16, 128, 48, 3, P, P, P, Z) == b.ERR_SHAPE
+    assert c.expand_special_value(P, P, P, 16, 128, 0, 3, P, Z, P, Z) == b.ERR_NULL
+    assert c.expand_special_value(P, P, P, 0, 128, 0, 4, Z, Z, Z, Z) == b.OK
+    L = lib.load_library()
+    assert L.w4a8_gemm_special_workspace_bytes(4, 16, 256, 128, 1) >= 4 * 512
+    assert (L.w4a8_gemm_special_workspace_bytes(4, 16, 256, 128, 1)
+            == 2048 + L.w4a8_gemm_workspace_bytes(4, 16, 512, 128, 1))
+    assert L.w4a8_gemm_special_workspace_bytes(4, 16, 256, 100, 1) == 0
+    WS = ctypes.c_void_p(0x10000)
+
+    def special(M=4, N=16, K=256, G=128, X=ctypes.c_void_p(0x2000), ws=WS, wsb=1 << 30, Y=P, yd=b.F16, ldy=16):
+        return c.w4a8_gemm_special(X, P, M, P, 1, P, P, N, K, G, Y, yd, ldy, Z, ws, wsb, Z)
+    assert special(K=200) == b.ERR_SHAPE
+    assert special(K=32768 + 128) == b.ERR_SHAPE                     # 2K <= 65536
+    assert special(N=24) == b.ERR_SHAPE
+    assert special(ldy=8) == b.ERR_SHAPE
+    assert special(yd=b.F32) == b.ERR_DTYPE
+    assert special(X=Z) == b.ERR_NULL
+    assert special(X=ctypes.c_void_p(0x2004)) == b.ERR_SHAPE
+    assert special(Y=Z) == b.ERR_NULL
+    assert special(ws=Z) == b.ERR_WORKSPACE
+    assert special(wsb=100) == b.ERR_WORKSPACE
+    assert special(M=0) == b.OK
     need = lib.load_library().dint_error_terms_workspace_bytes(8, 16, 128, 0)
     assert need >= 16 * 128 * 9 + 8 * 128 * 4 + 2 * 8 * 16 * 4
     W0 = ctypes.c_void_p(0x10000)

@@ -255,3 +255,20 @@ def test_expand_special_is_the_same_product(oracle, t):
         y = f.layer_output64(Xq, sx, codes, step, zero, G, "dint4", t)
         y2 = f.layer_output64(np.concatenate([Xq, Xq], axis=1), sx, c2, st2, z2, g, "dint4", 1)
         np.testing.assert_allclose(y2, y, rtol=1e-6, atol=1e-6 * np.abs(y).max())
+
+
+@pytest.mark.parametrize("t", [2, 3])
+def test_error_split_with_special_values(oracle, t):
+    f = oracle.formats
+    X, W, s = syn.random_layer(31, 9, 256, 20)
+    du, dr = f.error_split(W, s, 64, "dint4", special_shift=t)
+    codes, step, zero = f.quantize_weight(W, s, 64, "dint4", special_shift=t)
+    wq = f.dequant(codes, step, zero, 64, "dint4", t)
+    wp = (W.astype(np.float32) * s[None, :]).astype(np.float32).astype(np.float64)
+    np.testing.assert_array_equal(du + dr, wq - wp)
+    assert not np.any((du != 0) & (dr != 0))
+    assert np.all(np.abs(wp[du != 0]) <= np.repeat(step, 64, axis=1)[du != 0] * 2.0 ** -(t + 1) * 1.00001)
+    tu, tr, tc = f.output_error_terms(X, W, s, 64, "dint4", special_shift=t)
+    xs = X.astype(np.float64) * (np.float32(1) / s.astype(np.float32)).astype(np.float64)[None, :]
+    total = np.sum((xs @ (wq - wp).T) ** 2)
+    np.testing.assert_allclose(tu + tr + tc, total, rtol=1e-10)
