@@ -200,6 +200,25 @@ def test_gemm_bf16_output_and_canonical_layout(lib, oracle):
     _gemm_case(lib, oracle, 8, 70, 256, 48, 0, layout=0)
 
 
+@pytest.mark.parametrize("M,K,N,G", [(16, 512, 272, 128), (5, 1152, 48, 0), (3, 9216, 32, 128), (40, 512, 256, 0),
+                                     (130, 256, 304, 128)])
+def test_gemm_output_views(lib, oracle, M, K, N, G):
+    """Y as a view of a wider buffer: a leading dimension that allows 8-byte stores, and one (with an
+    odd element offset) that does not; the columns outside the view stay untouched."""
+    X, W, s = syn.random_layer(77 + M, M, K, N)
+    Xq, sx = lib.quantize_act_int8(dev(X), dev(s))
+    codes, step, zero = lib.quantize_weight_dint4(dev(W), dev(s), G)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    ref = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G)
+    for pad_l, pad_r in ((4, 4), (1, 5), (3, 2)):
+        big = torch.full((M, pad_l + N + pad_r), -7.0, dtype=torch.float16, device=ref.device)
+        view = big[:, pad_l:pad_l + N]
+        out = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, Y=view)
+        assert out.data_ptr() == view.data_ptr()
+        assert torch.equal(view, ref)
+        assert bool((big[:, :pad_l] == -7.0).all()) and bool((big[:, pad_l + N:] == -7.0).all())
+
+
 def test_gemm_every_code_and_zero_point(lib, oracle):
     """Random codes / zero-points / extreme activations straight into the GEMM (no quantizer)."""
     rng = np.random.default_rng(77)
