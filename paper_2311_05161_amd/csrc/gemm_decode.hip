@@ -240,7 +240,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
                             const float es = __uint_as_float(rec[j * 16 + hc + i].z);
                             v = es * (float)(isum[i] - 4 * zxm * wn[i]);
                         }
-                        const float out = sxm * v;
+                        float out = sxm * v;   // binary32 product, then the cast (never one fused
+                        asm volatile("" : "+v"(out));   // mixed-precision operation: that rounds once)
                         hh[i] = (a.y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
                     }
                     uint16_t *yp = a.Y + (int64_t)hm * a.ldy + n;
@@ -390,10 +391,11 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
                 if (ASYM) {
                     const int t4 = (int)r.w >> 8;   // 4 * (sum of the tile's weights)
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)(acc[rr] + __mul24(nzx[rr], t4));
+                    for (int rr = 0; rr < 4; ++rr)
+                        y[rr] = __builtin_fmaf(es, (float)(acc[rr] + __mul24(nzx[rr], t4)), y[rr]);
                 } else {
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) y[rr] += es * (float)acc[rr];
+                    for (int rr = 0; rr < 4; ++rr) y[rr] = __builtin_fmaf(es, (float)acc[rr], y[rr]);
                 }
                 if (ACC_OUT) {
                     const int g = (kt_begin + wave + u * GV_CW) / a.tiles_per_group;
@@ -471,7 +473,8 @@ __global__ __launch_bounds__(256) void gemv_combine_kernel(const float *__restri
     } else {
         for (int s = 0; s < splits; ++s) sum += partial[(int64_t)s * M * N + i];
     }
-    const float out = sx[m] * sum;
+    float out = sx[m] * sum;   // binary32 product, then the cast (see gemv_kernel)
+    asm volatile("" : "+v"(out));
     Y[(int64_t)m * ldy + n] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
 }
 

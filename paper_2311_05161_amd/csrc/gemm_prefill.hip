@@ -23,6 +23,8 @@
 // When the output has too few tiles to occupy 256 CUs (mid-size M) K is cut into ranges as well:
 // each workgroup writes an fp32 partial of its range and a small kernel adds the ranges in a fixed
 // order, applies the token scale and casts (deterministic; the int32 hook uses exact atomic adds).
+#include <type_traits>
+
 #include "w4a8_common.hpp"
 
 namespace w4a8 {
@@ -291,7 +293,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                     for (int r = 0; r < 4; ++r) {
                         const int v = acc[ms][ns][4 * b + r];
                         const int vz = ASYM ? v + __mul24(nzx[ms], gw[r]) : v;
-                        y[GROUPED ? ms : 0][ns][4 * b + r] += es[r] * (float)vz;
+                        // (an explicit fused multiply-add: left to contraction, instances of this
+                        // kernel could round the running sum differently)
+                        float &yr = y[GROUPED ? ms : 0][ns][4 * b + r];
+                        yr = __builtin_fmaf(es[r], (float)vz, yr);
                         if (ACC_OUT && m < M) {
                             const int nn = nb0 + nl + r;
                             if (nn < N) acc_out[((int64_t)m * N + nn) * ng + g] = v >> 2;
@@ -461,9 +466,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // epilogue parameters of the workgroup's 256 channels, in the (now free) staging buffer
-    float *s_es = reinterpret_cast<float *>(&lds[0][0]);          // step / 8
-    int *s_bq = reinterpret_cast<int *>(&lds[0][GM_BN * 4]);      // 4 beta
+    // Per-token values of the epilogue, fetched for all of the wave's rows at once and together
+    // with the per-channel parameters below.
+    const bool asym = !GROUPED && zx != nullptr;
+    float sxm_a[MS];
+    int zx4_a[MS], rs_a[MS];
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) {
+        const int m = min(m0 + wr0 + ms * 32 + r32, M - 1);
+        sxm_a[ms] = sx[m];
+        zx4_a[ms] = asym ? 4 * zx[m] : 0;
+        rs_a[ms] = GROUPED ? 0 : rs[(int64_t)split * M + m];
+    }
+
+    // epilogue parameters of the workgroup's 256 channels
+    __shared__ __attribute__((aligned(16))) int s_epi[3 * GM_BN];
+    float *s_es = reinterpret_cast<float *>(&s_epi[0]);           // step / 8
+    int *s_bq = &s_epi[GM_BN];                                    // 4 beta
     if (!GROUPED) {
         if (tid < GM_BN) {
             const int nn = nb0 + tid < N ? nb0 + tid : 0;
@@ -475,8 +494,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     }
     // per-channel weights with token zero-points: sums of each channel's weights over this
     // workgroup's K-range (all of K: the group sum; a K-split: its k-tiles added up)
-    const bool asym = !GROUPED && zx != nullptr;
-    int *s_w = reinterpret_cast<int *>(&lds[0][GM_BN * 8]);
+    int *s_w = &s_epi[2 * GM_BN];
     if (asym) {
         if (tid < GM_BN) {
             const int nn = nb0 + tid < N ? nb0 + tid : 0;
@@ -491,55 +509,111 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         __syncthreads();
     }
 
-    // epilogue: Y[m, n..n+3] = cast(sx[m] * y)
-#pragma unroll
-    for (int ms = 0; ms < MS; ++ms) {
-        const int m = m0 + wr0 + ms * 32 + r32;
-        if (m >= M) continue;
-        const float sxm = sx[m];
-        const int zx4m = asym ? 4 * zx[m] : 0;
-        const int rsm = GROUPED ? 0 : rs[(int64_t)split * M + m];
+    // epilogue: Y[m, n..n+3] = cast(sx[m] * y).  In the accumulator layout a lane holds four
+    // consecutive channels of one token, so direct stores are 8-byte pieces scattered over 32 rows
+    // of Y per instruction.  Where Y allows 16-byte stores the tile is staged in the (now free)
+    // activation ring as [token][256 channels] fp16 -- 16-byte columns XOR-swizzled with the row
+    // so that the 8-byte writes of 32 different rows spread over the banks -- and written out row
+    // by row, 32 lanes x 16 bytes = one whole 512-byte row segment per half wave.
+    // Everything uniform (output type, destination) is decided once, outside the loops, and the
+    // channel parameters of four outputs come with one 16-byte LDS read, reused over the wave's
+    // token blocks: as a single loop with those decisions per element the compiler produced one
+    // LDS read, one wait and several branches per output (17 us per 256 x 256 tile).
+    uint8_t *ytile = lds_raw;                                         // [BM][512]
+    enum { TO_PARTIAL = 0, TO_TILE = 1, TO_Y = 2 };
+    auto epilogue = [&](auto f16_tag, auto dest_tag) __attribute__((always_inline)) {
+        constexpr bool F16 = decltype(f16_tag)::value;
+        constexpr int DEST = decltype(dest_tag)::value;
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
-            if (!ns_valid[ns]) continue;
+            if (!ns_valid[ns]) continue;   // uniform over the wave
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int nl = wn * (GM_NS * 32) + ns * 32 + 8 * b + 4 * kh;   // channel within the workgroup
                 const int nn = nb0 + nl;
-                if (nn >= N) continue;   // N % 16 == 0 and nl % 4 == 0: the 4 channels are valid together
-                uint16_t hh[4];
-                v4f part;
+                // N % 16 == 0: the eight channels of (ns, b) are valid together, uniformly over the wave
+                if (nb0 + wn * (GM_NS * 32) + ns * 32 + 8 * b >= N) continue;
+                v4f es4 = {0.f, 0.f, 0.f, 0.f};
+                v4i bq4 = {0, 0, 0, 0}, sw4 = {0, 0, 0, 0};
+                if (!GROUPED) {
+                    es4 = *reinterpret_cast<const v4f *>(&s_es[nl]);
+                    bq4 = *reinterpret_cast<const v4i *>(&s_bq[nl]);
+                    if (asym) sw4 = *reinterpret_cast<const v4i *>(&s_w[nl]);
+                }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float yv;
-                    if (GROUPED) {
-                        yv = y[GROUPED ? ms : 0][ns][4 * b + r];
-                    } else {
-                        // remove the decode bias: 4 sum Xq d = acc - 4 beta * rowsum (exact)
-                        int v = acc[ms][ns][4 * b + r] - s_bq[nl + r] * rsm;
-                        if (ACC_OUT) {
-                            if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
-                            else acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                for (int ms = 0; ms < MS; ++ms) {
+                    const int m = m0 + wr0 + ms * 32 + r32;
+                    const bool row_ok = m < M;
+                    const float sxm = sxm_a[ms];
+                    uint16_t hh[4];
+                    v4f part;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float yv;
+                        if (GROUPED) {
+                            yv = y[GROUPED ? ms : 0][ns][4 * b + r];
+                        } else {
+                            // remove the decode bias: 4 sum Xq d = acc - 4 beta * rowsum (exact)
+                            int v = acc[ms][ns][4 * b + r] - bq4[r] * rs_a[ms];
+                            if (ACC_OUT && row_ok) {
+                                if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
+                                else acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                            }
+                            if (asym) v -= zx4_a[ms] * sw4[r];   // the accumulator hook keeps the raw sum
+                            yv = es4[r] * (float)v;
                         }
-                        if (asym) v -= zx4m * s_w[nl + r];   // the accumulator hook keeps the raw sum
-                        yv = s_es[nl + r] * (float)v;
+                        part[r] = yv;
+                        // binary32 product first, then the cast: the opaque copy keeps the compiler
+                        // from fusing the two into one mixed-precision operation, which rounds once
+                        // (it did so for some outputs and not for others, differently per instance)
+                        float out = sxm * yv;
+                        asm volatile("" : "+v"(out));
+                        hh[r] = F16 ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
                     }
-                    part[r] = yv;
-                    const float out = sxm * yv;
-                    hh[r] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
-                }
-                if (partial != nullptr) {   // K-split: the combine kernel applies sx and the cast
-                    *reinterpret_cast<v4f *>(&partial[((int64_t)split * M + m) * N + nn]) = part;
-                    continue;
-                }
-                uint16_t *yp = Y + (int64_t)m * ldy + nn;
-                if (vec_store) {
-                    *reinterpret_cast<uint2 *>(yp) = make_uint2(
-                        (uint32_t)hh[0] | ((uint32_t)hh[1] << 16), (uint32_t)hh[2] | ((uint32_t)hh[3] << 16));
-                } else {
+                    if (DEST == TO_PARTIAL) {   // K-split: the combine kernel applies sx and the cast
+                        if (row_ok) *reinterpret_cast<v4f *>(&partial[((int64_t)split * M + m) * N + nn]) = part;
+                        continue;
+                    }
+                    const uint2 h4 = make_uint2((uint32_t)hh[0] | ((uint32_t)hh[1] << 16),
+                                                (uint32_t)hh[2] | ((uint32_t)hh[3] << 16));
+                    if (DEST == TO_TILE) {
+                        const int rl = wr0 + ms * 32 + r32;   // row within the tile
+                        const int c8 = nl >> 2;               // 8-byte column within the row
+                        *reinterpret_cast<uint2 *>(ytile + rl * 512 +
+                                                   ((((c8 >> 1) ^ (rl & 15)) << 4) | ((c8 & 1) << 3))) = h4;
+                    } else if (row_ok) {
+                        uint16_t *yp = Y + (int64_t)m * ldy + nn;
+                        if (vec_store & 1) {
+                            *reinterpret_cast<uint2 *>(yp) = h4;
+                        } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) yp[r] = hh[r];
+                            for (int r = 0; r < 4; ++r) yp[r] = hh[r];
+                        }
+                    }
                 }
+            }
+        }
+    };
+    using std::integral_constant;
+    const bool staged = partial == nullptr && (vec_store & 2) != 0;   // uniform
+    if (partial != nullptr) {
+        epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_PARTIAL>{});
+    } else if (y_dtype == W4A8_F16) {
+        if (staged) epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_TILE>{});
+        else epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_Y>{});
+    } else {
+        if (staged) epilogue(integral_constant<bool, false>{}, integral_constant<int, TO_TILE>{});
+        else epilogue(integral_constant<bool, false>{}, integral_constant<int, TO_Y>{});
+    }
+    if (staged) {
+        __syncthreads();
+        constexpr int NWV = WM * WN;
+        for (int r = wave * 2 + (lane >> 5); r < BM; r += NWV * 2) {
+            const int c16 = lane & 31;
+            const int m = m0 + r, nn = nb0 + c16 * 8;
+            if (m < M && nn < N) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(ytile + r * 512 + ((c16 ^ (r & 15)) << 4));
+                *reinterpret_cast<uint4 *>(Y + (int64_t)m * ldy + nn) = v;
             }
         }
     }
@@ -553,7 +627,9 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
 {
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
-    const int vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
+    // bit 0: 8-byte stores of four outputs are aligned; bit 1: 16-byte stores of eight are
+    const int vec_store = ((((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0)) ? 1 : 0) |
+                          ((((uintptr_t)Y % 16 == 0) && (ldy % 8 == 0)) ? 2 : 0);
     constexpr int lds_bytes = GM_RING * BM * TILE_K;
     static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
     if (!attr_set) {
