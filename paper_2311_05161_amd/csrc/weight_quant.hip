@@ -53,17 +53,18 @@ __host__ __device__ constexpr CodeFormat dint4_format() { return CodeFormat{DINT
 __device__ __forceinline__ uint32_t dint4_code(float w, float istep, int z, CodeFormat f = dint4_format())
 {
     const float u = w * istep;
-    if (f.special) {
-        // nearest level: the band of +c runs from the midpoint between 0 and c to the midpoint
-        // between c and one step (0.25 .. 0.75 for c = step/2), ends as in Eq. 5; both bounds exact
-        const float lo_t = f.shift == 1 ? 0.25f : (f.shift == 2 ? 0.125f : 0.0625f);
-        const float hi_t = 0.5f + lo_t;
-        if (u > lo_t && u <= hi_t) return 14u;       // c1: +c
-        if (u >= -hi_t && u < -lo_t) return 15u;     // c2: -c
-    }
     int c = (int)__builtin_rintf(u) + z;
     c = c < 0 ? 0 : c;
     c = c > f.p ? f.p : c;
+    if (f.special) {
+        // nearest level: the band of +c runs from the midpoint between 0 and c to the midpoint
+        // between c and one step (0.25 .. 0.75 for c = step/2), ends as in Eq. 5; both bounds exact
+        // (selects, not branches: the lanes of a wave disagree all the time)
+        const float lo_t = f.shift == 1 ? 0.25f : (f.shift == 2 ? 0.125f : 0.0625f);
+        const float hi_t = 0.5f + lo_t;
+        c = (u > lo_t && u <= hi_t) ? 14 : c;        // c1: +c
+        c = (u >= -hi_t && u < -lo_t) ? 15 : c;      // c2: -c
+    }
     return (uint32_t)c;
 }
 
@@ -88,11 +89,31 @@ __device__ __forceinline__ void range_params(float lo, float hi, float &st, floa
     }
 }
 
+// The V scales of a lane's V consecutive columns (1 where there is no scale vector).  Eight of
+// them with two 16-byte loads where the vector is aligned: eight dword loads strided by 32 bytes
+// over the lanes cost the memory pipeline several times as many cycles.
+template <int V>
+__device__ __forceinline__ void load_scales(const float *sg, int64_t k, int s_vec, float (&sv)[V])
+{
+    if (sg == nullptr) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) sv[j] = 1.0f;
+    } else if (V == 8 && s_vec) {
+        const float4 s0 = *reinterpret_cast<const float4 *>(sg + k);
+        const float4 s1 = *reinterpret_cast<const float4 *>(sg + k + 4);
+        sv[0] = s0.x; sv[1] = s0.y; sv[2] = s0.z; sv[3] = s0.w;
+        sv[4 % V] = s1.x; sv[5 % V] = s1.y; sv[6 % V] = s1.z; sv[7 % V] = s1.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) sv[j] = sg[k + j];
+    }
+}
+
 template <typename T, int V>
 __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
     const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
     int64_t G, int use_given, uint8_t *__restrict__ codes, float *__restrict__ step,
-    uint8_t *__restrict__ zero, CodeFormat fmt)
+    uint8_t *__restrict__ zero, CodeFormat fmt, int s_vec)
 {
     const int lane = threadIdx.x & 63;
     const int64_t ng = K / G;
@@ -111,11 +132,12 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
     } else {
         float lo = 0.0f, hi = 0.0f;
         for (int64_t k = (int64_t)lane * V; k < G; k += (int64_t)WAVE * V) {
-            float v[V];
+            float v[V], sv[V];
             loadv<T, V>(w + k, v);
+            load_scales<V>(sg, k, s_vec, sv);
 #pragma unroll
             for (int j = 0; j < V; ++j) {
-                const float x = sg ? v[j] * sg[k + j] : v[j];
+                const float x = sg ? v[j] * sv[j] : v[j];
                 lo = fminf(lo, x);
                 hi = fmaxf(hi, x);
             }
@@ -131,12 +153,13 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_kernel(
 
     uint8_t *c = codes + n * K + g * G;
     for (int64_t k = (int64_t)lane * V; k < G; k += (int64_t)WAVE * V) {
-        float v[V];
+        float v[V], sv[V];
         loadv<T, V>(w + k, v);
+        load_scales<V>(sg, k, s_vec, sv);
         uint32_t q[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            const float x = sg ? v[j] * sg[k + j] : v[j];
+            const float x = sg ? v[j] * sv[j] : v[j];
             q[j] = dint4_code(x, istep, z, fmt);
         }
         if constexpr (V == 8) {
@@ -158,7 +181,7 @@ template <typename T, int LANES>
 __global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
     const T *__restrict__ W, int64_t N, int64_t K, int64_t ldw, const float *__restrict__ s,
     int use_given, uint8_t *__restrict__ codes, float *__restrict__ step, uint8_t *__restrict__ zero,
-    CodeFormat fmt)
+    CodeFormat fmt, int s_vec)
 {
     constexpr int G = LANES * 8;
     const int lane = threadIdx.x & 63;
@@ -170,8 +193,21 @@ __global__ __launch_bounds__(WQ_THREADS) void weight_quant_small_groups_kernel(
     if (k >= K) return;   // whole groups of LANES lanes leave together (K % G == 0)
     float v[8], x[8];
     loadv<T, 8>(W + n * ldw + k, v);
+    if (s == nullptr) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) x[j] = s ? v[j] * s[k + j] : v[j];
+        for (int j = 0; j < 8; ++j) x[j] = v[j];
+    } else if (s_vec) {
+        // the lane's eight scales with two 16-byte loads (eight dword loads strided by 32 bytes
+        // over the lanes cost the memory pipeline several times as many cycles)
+        const float4 s0 = *reinterpret_cast<const float4 *>(s + k);
+        const float4 s1 = *reinterpret_cast<const float4 *>(s + k + 4);
+        const float sv[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = v[j] * sv[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = v[j] * s[k + j];
+    }
     const int64_t pidx = n * (K / G) + k / G;
     float st, istep;
     int z;
@@ -213,23 +249,26 @@ static int launch_weight_quant_t(const T *W, int64_t N, int64_t K, int64_t ldw, 
     if (segs == 0) return W4A8_OK;
     const int64_t blocks = (segs + (WQ_THREADS / WAVE) - 1) / (WQ_THREADS / WAVE);
     if (blocks > 0x7fffffffLL) return W4A8_ERR_SHAPE;
+    const int s_vec = (uintptr_t)s % 16 == 0;   // (G % 8 == 0 wherever eight scales are loaded at once)
     const auto aligned = [&](int v) {
         return G % v == 0 && K % v == 0 && (ldw * sizeof(T)) % (v * sizeof(T)) == 0 &&
                (uintptr_t)W % (v * sizeof(T)) == 0 && (uintptr_t)codes % v == 0 && ldw % v == 0;
     };
 #define W4A8_WQ_LAUNCH(V_)                                                                        \
     hipLaunchKernelGGL((weight_quant_kernel<T, V_>), dim3((unsigned)blocks), dim3(WQ_THREADS), 0, \
-                       st, W, N, K, ldw, s, G, use_given, codes, step, zero, fmt)
+                       st, W, N, K, ldw, s, G, use_given, codes, step, zero, fmt, s_vec)
     if ((G == 128 || G == 256) && aligned(8)) {
         const int64_t wsegs = N * ((K + 511) / 512);
         const int64_t wblocks = (wsegs + (WQ_THREADS / WAVE) - 1) / (WQ_THREADS / WAVE);
         if (wblocks > 0x7fffffffLL) return W4A8_ERR_SHAPE;
         if (G == 128)
             hipLaunchKernelGGL((weight_quant_small_groups_kernel<T, 16>), dim3((unsigned)wblocks),
-                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero, fmt);
+                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero, fmt,
+                               s_vec);
         else
             hipLaunchKernelGGL((weight_quant_small_groups_kernel<T, 32>), dim3((unsigned)wblocks),
-                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero, fmt);
+                               dim3(WQ_THREADS), 0, st, W, N, K, ldw, s, use_given, codes, step, zero, fmt,
+                               s_vec);
     } else if (G >= 512 && aligned(8)) {
         W4A8_WQ_LAUNCH(8);
     } else if (aligned(2)) {
