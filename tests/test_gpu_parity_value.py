@@ -32,6 +32,8 @@ VQ_CASES = [
     ("interleaved_heads", 5, 320, 64, "f16", 0, "thd"),
     ("one_token_groups", 1, 8, 16, "f32", 1, "dense"),
     ("long", 2, 5120, 128, "f16", 0, "dense"),
+    ("eight_channel_loads_ragged_d", 3, 256, 72, "f16", 128, "thd"),   # second workgroup of channels partly empty
+    ("eight_channel_loads_bf16", 2, 384, 200, "bf16", 0, "dense"),
 ]
 
 
