@@ -470,12 +470,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     // with the per-channel parameters below.
     const bool asym = !GROUPED && zx != nullptr;
     float sxm_a[MS];
-    int zx4_a[MS], rs_a[MS];
+    int nzx4_a[MS], rs_a[MS];
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms) {
         const int m = min(m0 + wr0 + ms * 32 + r32, M - 1);
         sxm_a[ms] = sx[m];
-        zx4_a[ms] = asym ? 4 * zx[m] : 0;
+        nzx4_a[ms] = asym ? -4 * zx[m] : 0;
         rs_a[ms] = GROUPED ? 0 : rs[(int64_t)split * M + m];
     }
 
@@ -521,18 +521,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     // LDS read, one wait and several branches per output (17 us per 256 x 256 tile).
     uint8_t *ytile = lds_raw;                                         // [BM][512]
     enum { TO_PARTIAL = 0, TO_TILE = 1, TO_Y = 2 };
-    auto epilogue = [&](auto f16_tag, auto dest_tag) __attribute__((always_inline)) {
+    auto epilogue = [&](auto f16_tag, auto dest_tag, auto full_tag) __attribute__((always_inline)) {
         constexpr bool F16 = decltype(f16_tag)::value;
         constexpr int DEST = decltype(dest_tag)::value;
+        constexpr bool FULL = decltype(full_tag)::value;   // the tile lies inside Y: no range checks
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
-            if (!ns_valid[ns]) continue;   // uniform over the wave
+            if (!FULL && !ns_valid[ns]) continue;   // uniform over the wave
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int nl = wn * (GM_NS * 32) + ns * 32 + 8 * b + 4 * kh;   // channel within the workgroup
                 const int nn = nb0 + nl;
                 // N % 16 == 0: the eight channels of (ns, b) are valid together, uniformly over the wave
-                if (nb0 + wn * (GM_NS * 32) + ns * 32 + 8 * b >= N) continue;
+                if (!FULL && nb0 + wn * (GM_NS * 32) + ns * 32 + 8 * b >= N) continue;
                 v4f es4 = {0.f, 0.f, 0.f, 0.f};
                 v4i bq4 = {0, 0, 0, 0}, sw4 = {0, 0, 0, 0};
                 if (!GROUPED) {
@@ -540,10 +541,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                     bq4 = *reinterpret_cast<const v4i *>(&s_bq[nl]);
                     if (asym) sw4 = *reinterpret_cast<const v4i *>(&s_w[nl]);
                 }
+                const v4i nbq4 = -bq4;
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms) {
                     const int m = m0 + wr0 + ms * 32 + r32;
-                    const bool row_ok = m < M;
+                    const bool row_ok = FULL || m < M;
                     const float sxm = sxm_a[ms];
                     uint16_t hh[4];
                     v4f part;
@@ -554,12 +556,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                             yv = y[GROUPED ? ms : 0][ns][4 * b + r];
                         } else {
                             // remove the decode bias: 4 sum Xq d = acc - 4 beta * rowsum (exact)
-                            int v = acc[ms][ns][4 * b + r] - bq4[r] * rs_a[ms];
+                            // (24-bit multiplies: 4 beta <= 124, |row-sum| <= 2^23, |weight sum| < 2^23)
+                            int v = __mul24(nbq4[r], rs_a[ms]) + acc[ms][ns][4 * b + r];
                             if (ACC_OUT && row_ok) {
                                 if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
                                 else acc_out[(int64_t)m * N + nn + r] = v >> 2;
                             }
-                            if (asym) v -= zx4_a[ms] * sw4[r];   // the accumulator hook keeps the raw sum
+                            // (the accumulator hook keeps the raw sum; without token zero-points both factors are 0)
+                            v = __mul24(nzx4_a[ms], sw4[r]) + v;
                             yv = es4[r] * (float)v;
                         }
                         part[r] = yv;
@@ -596,14 +600,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     };
     using std::integral_constant;
     const bool staged = partial == nullptr && (vec_store & 2) != 0;   // uniform
+    const bool full = m0 + BM <= M && nb0 + GM_BN <= N;                // uniform
+    auto epilogue_for = [&](auto f16_tag, auto dest_tag) __attribute__((always_inline)) {
+        if (full) epilogue(f16_tag, dest_tag, integral_constant<bool, true>{});
+        else epilogue(f16_tag, dest_tag, integral_constant<bool, false>{});
+    };
     if (partial != nullptr) {
-        epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_PARTIAL>{});
+        epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_PARTIAL>{}, integral_constant<bool, false>{});
     } else if (y_dtype == W4A8_F16) {
-        if (staged) epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_TILE>{});
-        else epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_Y>{});
+        if (staged) epilogue_for(integral_constant<bool, true>{}, integral_constant<int, TO_TILE>{});
+        else epilogue_for(integral_constant<bool, true>{}, integral_constant<int, TO_Y>{});
     } else {
-        if (staged) epilogue(integral_constant<bool, false>{}, integral_constant<int, TO_TILE>{});
-        else epilogue(integral_constant<bool, false>{}, integral_constant<int, TO_Y>{});
+        if (staged) epilogue_for(integral_constant<bool, false>{}, integral_constant<int, TO_TILE>{});
+        else epilogue_for(integral_constant<bool, false>{}, integral_constant<int, TO_Y>{});
     }
     if (staged) {
         __syncthreads();

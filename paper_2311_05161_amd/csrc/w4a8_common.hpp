@@ -29,10 +29,11 @@ __device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float((uint
 // round-to-nearest-even narrowing of a finite binary32 value
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t rounded = u + 0x7fffu + ((u >> 16) & 1u);
+    const uint32_t quiet = u | 0x400000u;                        // NaN stays NaN
+    // (a select, not a branch: callers convert in the middle of long straight-line epilogues)
+    return (uint16_t)(((u & 0x7fffffffu) > 0x7f800000u ? quiet : rounded) >> 16);
 }
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
 {
