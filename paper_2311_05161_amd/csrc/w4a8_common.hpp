@@ -206,9 +206,9 @@ struct GemvPlan {
     int splits;            // K is cut into this many ranges, each handled by its own workgroups
     int kt_per_split;      // 128-column k-tiles per range
     int at;                // k-tiles per compute wave (template instance)
-    int q;                 // consecutive 16-channel n-tiles per workgroup
+    int q;                 // most 16-channel n-tiles any workgroup gets
     int blocks_per_split;
-    int nt_lo, nt_rem;     // workgroup b of a split owns nt_lo (+1 if b < nt_rem) n-tiles
+    int nt_lo, nt_rem;     // workgroup b of a split owns nt_lo (+1 if b < nt_rem) n-tiles: b, b + blocks_per_split, ...
     int lds_bytes;
     size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1, else 0
 };
