@@ -38,8 +38,8 @@ constexpr int GV_CW = 8;                          // compute waves per workgroup
 constexpr int GV_THREADS = (GV_CW + 1) * WAVE;    // + 1 helper wave
 constexpr int GV_MAX_AT = 9;                      // k-tiles per compute wave -> K per split <= 9216 (5120 group-wise)
 constexpr int GV_REC_THREADS = GV_CW * WAVE;      // the compute waves prepare the decode records
-constexpr int GV_STAGE = 7;                       // decode records such a thread prepares at most
-constexpr int GV_LDS_BUDGET = 48 * 1024;          // bytes of decode records per workgroup
+constexpr int GV_STAGE = 12;                      // decode records such a thread prepares at most
+constexpr int GV_LDS_BUDGET = 128 * 1024;         // bytes of decode records per workgroup
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
 constexpr int GV_RED_BYTES = 2 * GV_CW * 256 * 4; // partial sums of the compute waves, double buffered
 constexpr int GV_MAX_LDS = GV_RED_BYTES + GV_LDS_BUDGET;

@@ -167,6 +167,9 @@ DECODE_CASES = [
     ("per_channel_9_tiles_ragged", 16, 8576, 32, 0),
     ("many_n_tiles_per_block", 16, 512, 9232, 128),  # 577 n-tiles: several per workgroup, ragged
     ("many_n_tiles_per_channel", 2, 1024, 4640, 0),
+    # 1285 n-tiles x 40 groups: six n-tiles and 3840 decode records per workgroup (eight parameter
+    # stages per thread), workgroups with five and with six n-tiles
+    ("many_records_per_block", 2, 5120, 20560, 128),
 ]
 
 
