@@ -234,6 +234,56 @@ def main():
                 "bytes_per_launch": per_copy, "avg_launch_us": round(kern_ms * 1e3, 3),
                 "launch_floor_us": round(floor_us, 3)}
 
+    # ------------------------------------------------------------------ measured ceilings and the cache-resident figure
+    # What a plain streaming read and a register-resident int8 MFMA loop reach on this machine in this
+    # run (the roofline fractions stay against the nominal peaks), and the C2 GEMV launched over
+    # one weight copy that stays in the 256 MB last-level cache (never an HBM fraction).
+    ceilings = None
+    if not args.no_prefill:
+        big = torch.empty((1 << 30,), dtype=torch.uint8, device=dev)
+        big.random_(0, 256)
+        sink = torch.zeros((4,), dtype=torch.int32, device=dev)
+        reads = {}
+        for label, nbytes in (("9_MB", per_copy // 16 * 16), ("39_MB", 38_600_000 // 16 * 16),
+                              ("170_MB", 170_000_000 // 16 * 16)):
+            # consecutive launches walk through the 1 GiB buffer, so every launch reads from HBM
+            slots = (1 << 30) // nbytes
+            for i in range(8):
+                assert lib.w4a8_measure_stream_read(big.data_ptr() + (i % slots) * nbytes, nbytes, P(sink), st) == 0
+            torch.cuda.synchronize()
+            n_l = max(16, min(256, (4 << 30) // nbytes))
+            e0.record(stream)
+            for i in range(n_l):
+                lib.w4a8_measure_stream_read(big.data_ptr() + (i % slots) * nbytes, nbytes, P(sink), st)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / n_l * 1e3
+            reads[label] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1)}
+        del big
+        ops = ctypes.c_int64(0)
+        iters = 20000
+        for _ in range(2):
+            assert lib.w4a8_measure_mfma_i8(iters, P(sink), ctypes.byref(ops), st) == 0
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(5):
+            lib.w4a8_measure_mfma_i8(iters, P(sink), ctypes.byref(ops), st)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        mfma_ms = e0.elapsed_time(e1) / 5
+        e0.record(stream)
+        for i in range(L):
+            lib.w4a8_gemm(*gm_args[0])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        resident_us = e0.elapsed_time(e1) / L * 1e3
+        ceilings = {"what": "measured on this box in this run: a plain streaming read of as many bytes as "
+                            "the decode shapes move (each launch from HBM), a register-resident "
+                            "v_mfma_i32_32x32x32_i8 loop, and the C2 GEMV over one cache-resident weight copy",
+                    "stream_read": reads,
+                    "mfma_i8_loop_TOPS": round(ops.value / (mfma_ms * 1e-3) / 1e12, 1),
+                    "gemv_C2_cache_resident_us": round(resident_us, 3)}
+
     # ------------------------------------------------------------------ larger decode shapes (side figures)
     def time_gemm(Mq, Nq, Kq, Gq, reps, ring_bytes=600 << 20, asym=False):
         """Back-to-back w4a8_gemm (or w4a8_gemm_asym) launches over a ring of random packed weights
@@ -488,6 +538,7 @@ def main():
                                            "accumulators), same shapes and protocol as the lists above",
                                    "shapes": asym_side},
         "quantizers": quant_side, "value_cache": value_side, "aqas_search": search_side,
+        "ceilings": ceilings,
     }
     print(json.dumps(out), flush=True)
 

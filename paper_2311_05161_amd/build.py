@@ -25,6 +25,7 @@ SOURCES = {
     "gemm_decode.hip": [],
     "gemm_prefill.hip": [],
     "aqas_search.hip": ["-ffp-contract=off"],
+    "ceilings.hip": [],
 }
 
 COMMON = [

@@ -120,6 +120,20 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
 
 extern "C" {
 
+int w4a8_measure_stream_read(const void *buf, int64_t bytes, uint32_t *sink, void *stream)
+{
+    if (buf == nullptr) return W4A8_ERR_NULL;
+    if (bytes < 0 || bytes % 16 != 0 || (uintptr_t)buf % 16 != 0) return W4A8_ERR_SHAPE;
+    if (bytes == 0) return W4A8_OK;
+    return launch_stream_read(buf, bytes, sink, (hipStream_t)stream);
+}
+
+int w4a8_measure_mfma_i8(int64_t iters, uint32_t *sink, int64_t *ops, void *stream)
+{
+    if (iters < 0 || iters > (1LL << 24)) return W4A8_ERR_SHAPE;
+    return launch_mfma_i8_loop(iters, sink, ops, (hipStream_t)stream);
+}
+
 const char *w4a8_status_string(int status)
 {
     switch (status) {

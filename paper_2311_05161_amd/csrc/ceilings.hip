@@ -1,0 +1,82 @@
+// Measured ceilings of the machine, for the bench to print beside the nominal peaks: what a plain
+// streaming read reaches on the box the kernels are timed on, and what a register-resident loop of
+// the int8 MFMA that the prefill kernel is built on reaches.  Neither is a step of the W4A8 path
+// (Eq. 1 / Eq. 5 are computed by the other files); both only put the roofline fractions in context.
+#include "w4a8_common.hpp"
+
+namespace w4a8 {
+
+typedef int v16i_c __attribute__((ext_vector_type(16)));
+
+constexpr int SR_THREADS = 512;
+constexpr int SR_BLOCKS = 256 * 2;
+constexpr int SR_UNROLL = 4;   // 16-byte loads in flight per lane
+
+// Every lane streams 16-byte pieces, a wave 1 KB per instruction, the grid a contiguous window of
+// SR_BLOCKS x SR_THREADS x SR_UNROLL x 16 bytes per round.  The loaded words are folded into one
+// value per lane that is stored only if it equals a value it never takes in practice, so that the
+// loads cannot be removed and nothing is written.
+__global__ __launch_bounds__(SR_THREADS) void stream_read_kernel(const v4u *__restrict__ src, int64_t n16,
+                                                                uint32_t *__restrict__ sink)
+{
+    const int64_t stride = (int64_t)gridDim.x * SR_THREADS;
+    int64_t i = (int64_t)blockIdx.x * SR_THREADS + threadIdx.x;
+    uint32_t fold = 0;
+    for (; i + (SR_UNROLL - 1) * stride < n16; i += SR_UNROLL * stride) {
+        v4u v[SR_UNROLL];
+#pragma unroll
+        for (int u = 0; u < SR_UNROLL; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < SR_UNROLL; ++u) fold ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        const v4u v = src[i];
+        fold ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (fold == 0x9e3779b9u && sink != nullptr) sink[0] = fold;
+}
+
+constexpr int MF_THREADS = 256;
+constexpr int MF_BLOCKS = 256 * 2;   // two workgroups of four waves per CU: two waves per SIMD
+constexpr int MF_CHAINS = 8;         // independent accumulators per wave
+
+// `iters` rounds of MF_CHAINS independent v_mfma_i32_32x32x32_i8 per wave, operands in registers.
+__global__ __launch_bounds__(MF_THREADS) void mfma_i8_loop_kernel(int64_t iters, uint32_t *__restrict__ sink)
+{
+    const int lane = threadIdx.x & 63;
+    v4i a = {lane, lane + 1, lane + 2, lane + 3};
+    v4i b = {lane * 3, lane * 5, lane * 7, lane * 11};
+    v16i_c acc[MF_CHAINS];
+#pragma unroll
+    for (int c = 0; c < MF_CHAINS; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][r] = c;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < MF_CHAINS; ++c)
+            acc[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[c], 0, 0, 0);
+    }
+    int fold = 0;
+#pragma unroll
+    for (int c = 0; c < MF_CHAINS; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) fold ^= acc[c][r];
+    if (fold == 0x5bd1e995 && sink != nullptr) sink[0] = (uint32_t)fold;
+}
+
+int launch_stream_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(SR_BLOCKS), dim3(SR_THREADS), 0, st,
+                       reinterpret_cast<const v4u *>(buf), bytes / 16, sink);
+    return hip_status(hipGetLastError());
+}
+
+int launch_mfma_i8_loop(int64_t iters, uint32_t *sink, int64_t *ops, hipStream_t st)
+{
+    if (ops != nullptr)
+        *ops = (int64_t)MF_BLOCKS * (MF_THREADS / WAVE) * MF_CHAINS * iters * (2LL * 32 * 32 * 32);
+    hipLaunchKernelGGL(mfma_i8_loop_kernel, dim3(MF_BLOCKS), dim3(MF_THREADS), 0, st, iters, sink);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace w4a8

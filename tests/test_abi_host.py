@@ -223,6 +223,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert c.dint_error_terms(P, b.F16, 8, 128, 100, P, b.F16, 16, 128, Z, 0, 0, P, W0, 1 << 30, Z) == b.ERR_SHAPE
     assert c.dint_error_terms(P, b.F16, 8, 128, 128, P, b.F16, 16, 128, Z, 0, 0, Z, W0, 1 << 30, Z) == b.ERR_NULL
     assert c.dint_error_terms(P, b.F16, 8, 128, 128, P, b.F16, 16, 128, Z, 0, 0, P, W0, 100, Z) == b.ERR_WORKSPACE
+    # the two measurement aids
+    assert c.w4a8_measure_stream_read(Z, 1024, Z, Z) == b.ERR_NULL
+    assert c.w4a8_measure_stream_read(P, 1000, Z, Z) == b.ERR_SHAPE
+    assert c.w4a8_measure_stream_read(ctypes.c_void_p(0x1008), 1024, Z, Z) == b.ERR_SHAPE
+    assert c.w4a8_measure_stream_read(P, 0, Z, Z) == b.OK
+    assert c.w4a8_measure_mfma_i8(-1, Z, Z, Z) == b.ERR_SHAPE
+    assert c.w4a8_measure_mfma_i8((1 << 24) + 1, Z, Z, Z) == b.ERR_SHAPE
 
 
 def test_product_path_has_no_cpu_fallback(lib, tmp_path):

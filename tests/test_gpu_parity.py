@@ -335,3 +335,20 @@ def test_full_size_llama_shapes(lib, oracle, name, M):
 def test_full_size_c5_opt66b_end_to_end(lib, oracle):
     """OPT-66B-shaped layer: activation quantization and GEMM back to back on one stream."""
     _full_size_case(lib, oracle, "C5", n_samples=64, seed=5)
+
+
+def test_measurement_aids_run_and_count_their_work(lib):
+    """The streaming read and the MFMA loop that bench.py times as measured ceilings: both run,
+    write nothing (the sink stays as it was) and the loop reports its operation count."""
+    import ctypes
+    L = lib.load_library()
+    buf = torch.randint(0, 256, (1 << 20,), dtype=torch.uint8, device="cuda")
+    sink = torch.full((4,), 7, dtype=torch.int32, device="cuda")
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.w4a8_measure_stream_read(buf.data_ptr(), buf.numel(), sink.data_ptr(), st) == 0
+    assert L.w4a8_measure_stream_read(buf.data_ptr() + 16, 4096 + 16, sink.data_ptr(), st) == 0   # ragged tail
+    ops = ctypes.c_int64(0)
+    assert L.w4a8_measure_mfma_i8(3, sink.data_ptr(), ctypes.byref(ops), st) == 0
+    torch.cuda.synchronize()
+    assert ops.value == 512 * 4 * 8 * 3 * 2 * 32 ** 3
+    assert sink.tolist() == [7, 7, 7, 7]
