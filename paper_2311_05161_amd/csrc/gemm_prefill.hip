@@ -308,13 +308,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     };
 
     // activation fragments of k-step s = 2 sp + h: 16-byte chunk 2 (2 sp + kh) + h of the token's row
-    auto read_a = [&](int buf, int s, v4i(&dst)[MS]) {
-        const int chunk = 2 * (2 * (s >> 1) + kh) + (s & 1);
+    // (the swizzle term of a row does not depend on its 32-token block -- wr0 and 32 ms are multiples
+    // of 16 rows --, so block and ring slot are plain offsets on four per-lane addresses instead of
+    // sixteen)
+    int frag_off[4];
 #pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
-            const int row = wr0 + ms * 32 + r32;
-            dst[ms] = *reinterpret_cast<const v4i *>(&lds[buf][row * TILE_K + ((chunk ^ ((row >> 1) & 7)) << 4)]);
-        }
+    for (int s = 0; s < 4; ++s) {
+        const int chunk = 2 * (2 * (s >> 1) + kh) + (s & 1);
+        frag_off[s] = (wr0 + r32) * TILE_K + ((chunk ^ ((r32 >> 1) & 7)) << 4);
+    }
+    auto read_a = [&](int buf, int s, v4i(&dst)[MS]) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+            dst[ms] = *reinterpret_cast<const v4i *>(&lds_raw[buf * (BM * TILE_K) + ms * (32 * TILE_K) + frag_off[s]]);
     };
     auto decode_step = [&](const v4u(&pk)[GM_NS][2], int s, v4i(&dst)[GM_NS]) {
         const int sp = s >> 1, h = s & 1;
