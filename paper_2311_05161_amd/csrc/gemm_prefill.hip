@@ -112,8 +112,8 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ 
 // term zx * (sum of the weights) leaves the int32 accumulators before any floating-point step --
 // per group in the flush (GROUPED; its own instances, ASYM) or once in the epilogue (!GROUPED,
 // decided at run time by zx != null).
-template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
+template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TWO>
+__global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ zx,
     const int32_t *__restrict__ wsum, const int32_t *__restrict__ tsum,
     const int32_t *__restrict__ rs, int M,
@@ -378,7 +378,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     __syncthreads();
     if (GROUPED) load_luts(g0);
 
-    v4i af[2][MS], w[2][GM_NS];
+    // TWO: per-channel 128-token tiles of a launch with more workgroups than CUs keep one set of
+    // activation fragments and refill each right behind the MFMA that consumed it (the same block's
+    // fragment of the next k-step: three MFMAs of lead); with 128 registers two workgroups share a
+    // CU, and one's barrier waits and epilogue run under the other's main loop.  (With at most one
+    // workgroup per CU the two fragment sets are 1-2 % faster.)
+    constexpr bool ROLL = TWO;
+    static_assert(!TWO || (!GROUPED && BM == 128 && GM_NS == 1), "two workgroups per CU: per-channel 128-token tiles");
+    v4i af[ROLL ? 1 : 2][MS], w[2][GM_NS];
     read_a(0, 0, af[0]);
     decode_step(pa, 0, w[0]);
 
@@ -397,33 +404,48 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             if (s < 3) {
-                read_a(cur, s + 1, af[(s + 1) & 1]);
+                if (!ROLL) read_a(cur, s + 1, af[ROLL ? 0 : ((s + 1) & 1)]);
                 decode_step(P, s + 1, w[(s + 1) & 1]);
             } else {
                 gm_order_fence();
                 load_b(min(kt + 2, ktl), P);   // P: last read by the decode during the previous k-step
                 gm_order_fence();
                 if (GROUPED && t == tiles_in_group - 1 && g + 1 < g_end) load_luts(g + 1);
-                read_a(nxt, 0, af[0]);
+                if (!ROLL) read_a(nxt, 0, af[0]);
                 use_all(PN);
                 decode_step(PN, 0, w[0]);
             }
             // D[i][j]: rows i = output channels (weights operand), columns j = tokens.  The
             // first k-step of a group starts from a zero operand instead of cleared accumulators.
+            if (ROLL) {
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms) {
+                    acc[ms][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][0], af[0][ms], acc[ms][0], 0, 0, 0);
+                    af[0][ms] = *reinterpret_cast<const v4i *>(
+                        &lds_raw[(s < 3 ? cur : nxt) * (BM * TILE_K) + ms * (32 * TILE_K) + frag_off[(s + 1) & 3]]);
+                }
+#pragma unroll
+                for (int i = 0; i < MS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                }
+                continue;
+            }
             if (GROUPED && s == 0 && t == 0) {
                 const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                     for (int ns = 0; ns < GM_NS; ++ns)
-                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[ROLL ? 0 : (s & 1)][ms],
                                                                             z16, 0, 0, 0);
             } else {
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                     for (int ns = 0; ns < GM_NS; ++ns)
-                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[s & 1][ms],
+                        acc[ms][ns] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s & 1][ns], af[ROLL ? 0 : (s & 1)][ms],
                                                                             acc[ms][ns], 0, 0, 0);
             }
             // issue order for this step: the LDS reads of the next step first, then the decode
@@ -634,7 +656,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     }
 }
 
-template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM>
+template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TWO>
 static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                           const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                           const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
@@ -649,12 +671,12 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
     if (!attr_set) {
         if (lds_bytes > 48 * 1024 &&
-            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM>,
+            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return W4A8_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM>),
+    hipLaunchKernelGGL((gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>),
                        dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * WN * 64), lds_bytes, st,
                        Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,
                        (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
@@ -662,7 +684,7 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     return hip_status(hipGetLastError());
 }
 
-template <int BM, int WM, int WN, bool GROUPED>
+template <int BM, int WM, int WN, bool GROUPED, bool TWO = false>
 static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                          const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                          const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
@@ -671,7 +693,7 @@ static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, 
     // The accumulator test hook is a separate instance so that the fast path carries none of it;
     // so is the per-group zero-point term of group-wise weights.
 #define W4A8_GM2(AO_, AS_)                                                                       \
-    return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
+    return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_, TWO>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
                                                      G, Y, y_dtype, ldy, acc_out, partial, st, plain)
     if (GROUPED && zp.zx != nullptr) {
         if (acc_out) W4A8_GM2(true, GROUPED);
@@ -693,10 +715,14 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
         pl.bm = 128;   // group-wise: int32 group accumulators plus fp32 running sums
     } else {
         // 256-row tiles reuse each decoded weight twice as often, but whole rounds of 256 CUs are
-        // what count: take the 128-row tile when it needs clearly less machine time (cost ~0.6)
+        // what count.  128-row tiles run two to a CU: 512 of them cost about what a round of 256-row
+        // tiles costs, a remainder of up to 256 (one per CU) about 0.6 of it.  Take them when
+        // that is clearly less machine time.
+        const int64_t t128 = (M + 127) / 128 * gn;
         const double rounds256 = (double)(((M + 255) / 256 * gn + 255) / 256);
-        const double rounds128 = (double)(((M + 127) / 128 * gn + 255) / 256) * 0.6;
-        pl.bm = rounds128 < rounds256 ? 128 : 256;
+        const int64_t rem = t128 % 512;
+        const double rounds128 = (double)(t128 / 512) + (rem == 0 ? 0.0 : rem <= 256 ? 0.6 : 1.0);
+        pl.bm = rounds128 < 0.95 * rounds256 ? 128 : 256;
     }
     // too few output tiles for 256 CUs: split K as well (whole groups, at least 4 k-tiles each)
     const int64_t tiles = (M + pl.bm - 1) / pl.bm * gn;
@@ -735,16 +761,19 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
         if (hipGetLastError() != hipSuccess) return W4A8_ERR_HIP;
     }
     int rc;
-#define W4A8_GM(BM_, WM_, WN_, GR_)                                                                \
-    rc = launch_gemm_t<BM_, WM_, WN_, GR_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
-                                      acc_out, partial, st, plain)
+#define W4A8_GM(BM_, WM_, WN_, GR_, TWO_)                                                                \
+    rc = launch_gemm_t<BM_, WM_, WN_, GR_, TWO_>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype, ldy, \
+                                            acc_out, partial, st, plain)
+    // more workgroups than CUs: the 128-token per-channel tile in its two-per-CU form
+    const int64_t wgs = (M + pl.bm - 1) / pl.bm * ((N + GM_BN - 1) / GM_BN) * pl.splits;
     if (grouped) {
-        if (pl.bm == 64) W4A8_GM(64, 1, 4, true);
-        else W4A8_GM(128, 1, 8, true);
+        if (pl.bm == 64) W4A8_GM(64, 1, 4, true, false);
+        else W4A8_GM(128, 1, 8, true, false);
     } else {
-        if (pl.bm == 64) W4A8_GM(64, 1, 4, false);
-        else if (pl.bm == 128) W4A8_GM(128, 1, 8, false);
-        else W4A8_GM(256, 2, 4, false);
+        if (pl.bm == 64) W4A8_GM(64, 1, 4, false, false);
+        else if (pl.bm == 128 && wgs > 256) W4A8_GM(128, 1, 8, false, true);
+        else if (pl.bm == 128) W4A8_GM(128, 1, 8, false, false);
+        else W4A8_GM(256, 2, 4, false, false);
     }
 #undef W4A8_GM
     if (rc != W4A8_OK || pl.splits == 1) return rc;
