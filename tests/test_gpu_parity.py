@@ -187,6 +187,9 @@ PREFILL_CASES = [
     ("m300", 300, 768, 1040, 0),
     ("m300_g256", 300, 768, 512, 256),
     ("m600_multi_block", 600, 1024, 784, 0),
+    # 9 x 30 = 270 tiles of 128 tokens: more workgroups than CUs, i.e. the per-channel instance that
+    # runs two workgroups to a CU, with a ragged last token tile and a 16-channel last column
+    ("m1030_two_per_cu_ragged", 1030, 256, 7440, 0),
 ]
 
 
