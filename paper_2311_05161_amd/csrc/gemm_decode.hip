@@ -527,17 +527,14 @@ template <bool GROUPED, bool ACC_OUT, bool ASYM>
 static int launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hipStream_t st)
 {
     const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits, (unsigned)batch);
-    // more than 64 KB of dynamic LDS has to be opted into, once per instance
+    // more than 64 KB of dynamic LDS has to be opted into, once per instance and device
 #define W4A8_GV_LAUNCH(AT_, D_)                                                                  \
     do {                                                                                         \
-        static bool attr_set = false;                                                            \
-        if (pl.lds_bytes > 64 * 1024 && !attr_set) {                                             \
-            if (hipFuncSetAttribute((const void *)gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>,  \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,                  \
-                                    GV_MAX_LDS) != hipSuccess)                                   \
-                return W4A8_ERR_HIP;                                                             \
-            attr_set = true;                                                                     \
-        }                                                                                        \
+        static std::atomic<uint64_t> lds_opted{0};                                               \
+        if (pl.lds_bytes > 64 * 1024 &&                                                          \
+            opt_in_dynamic_lds((const void *)gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>,       \
+                               GV_MAX_LDS, lds_opted) != W4A8_OK)                                \
+            return W4A8_ERR_HIP;                                                                 \
         hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>), grid,                 \
                            dim3(GV_THREADS), pl.lds_bytes, st, ga);                              \
     } while (0)

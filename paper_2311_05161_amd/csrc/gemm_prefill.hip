@@ -668,14 +668,11 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     const int vec_store = ((((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0)) ? 1 : 0) |
                           ((((uintptr_t)Y % 16 == 0) && (ldy % 8 == 0)) ? 2 : 0);
     constexpr int lds_bytes = GM_RING * BM * TILE_K;
-    static bool attr_set = false;   // > 64 KB of dynamic LDS has to be opted into once per kernel
-    if (!attr_set) {
-        if (lds_bytes > 48 * 1024 &&
-            hipFuncSetAttribute((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
-            return W4A8_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_opted{0};
+    if (lds_bytes > 48 * 1024 &&
+        opt_in_dynamic_lds((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>, lds_bytes,
+                           lds_opted) != W4A8_OK)
+        return W4A8_ERR_HIP;
     hipLaunchKernelGGL((gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>),
                        dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * WN * 64), lds_bytes, st,
                        Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,

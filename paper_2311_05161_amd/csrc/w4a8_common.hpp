@@ -1,8 +1,10 @@
 // Shared device helpers of the gfx950 W4A8 kernels (wave64, CDNA4).
 #pragma once
-#include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <atomic>
 
 #include "../../include/w4a8.h"
 
@@ -247,5 +249,20 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
                 hipStream_t st, int plain = 0);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? W4A8_OK : W4A8_ERR_HIP; }
+
+// More than 64 KB of dynamic LDS has to be opted into per kernel and per device.  `done` is that
+// kernel's record of the devices it has been set on (bit = device ordinal modulo 64; setting it
+// twice is harmless, so concurrent callers need no lock).
+inline int opt_in_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return W4A8_ERR_HIP;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_relaxed) & bit) return W4A8_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return W4A8_ERR_HIP;
+    done.fetch_or(bit, std::memory_order_relaxed);
+    return W4A8_OK;
+}
 
 }  // namespace w4a8
