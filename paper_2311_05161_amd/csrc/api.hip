@@ -36,7 +36,7 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
         w.repack_bytes = (size_t)(N * K / 2);
         off = align_up(off + w.repack_bytes);
     }
-    if (M > 16) {
+    if (M > 16 && gemv_token_blocks(M, N, K, G) == 0) {
         const GemmPlan gp = plan_gemm(M, N, K, G);
         w.rs_off = off;            // per-channel weights: bias removal needs row-sums per token
         w.rs_bytes = gp.rs_bytes;
@@ -44,7 +44,7 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
         w.part_off = off;          // few output tiles: K is split, fp32 partial sums
         w.part_bytes = gp.partial_bytes;
         off = align_up(off + w.part_bytes);
-    } else if (M > 0 && N > 0) {
+    } else if (M > 0 && N > 0 && M <= 16) {
         w.part_off = off;
         w.part_bytes = plan_gemv(M, N, K, G).partial_bytes;
         off = align_up(off + w.part_bytes);
@@ -96,7 +96,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
         if (rc != W4A8_OK) return rc;
         Wt = tiled;
     }
-    if (M <= 16) {
+    if (M <= 16 || gemv_token_blocks(M, N, K, G) > 0) {   // the streaming kernel, also for a few 16-token blocks
         if (acc_out) {  // the split-K waves add exact partial sums into it
             const int rc = launch_fill_i32(acc_out, M * N * (K / G), 0, st);
             if (rc != W4A8_OK) return rc;

@@ -91,6 +91,7 @@ struct GemvArgs {
     int nt_stride;         // width: the number of workgroups per K-range
     int plain;             // code space of ordinary INT4 (16 integer levels) instead of dINT4
     int vec_store;         // Y and ldy allow 8-byte stores of four outputs
+    int token_blocks;      // blockIdx.z: 16-token blocks of one problem (shared weights) instead of problems
 };
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
@@ -103,11 +104,18 @@ struct GemvArgs {
 template <bool GROUPED, int AT, int D, bool ACC_OUT, bool ASYM>
 __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 {
-    // blockIdx.z: independent problems of one shape, densely stacked (batched launch)
+    // blockIdx.z: independent problems of one shape, densely stacked (batched launch), or the
+    // 16-token blocks of one problem with more than 16 tokens: the same weights, and the last block
+    // may be shorter
     GemvArgs a = args;
     if (gridDim.z > 1) {
         const int64_t b = blockIdx.z;
-        const int64_t rows_w = b * a.N, rows_x = b * a.M;
+        const int64_t rows_w = a.token_blocks ? 0 : b * a.N;
+        const int64_t rows_x = a.token_blocks ? b * 16 : b * a.M;
+        if (a.token_blocks) {
+            if (a.acc_out != nullptr) a.acc_out += rows_x * a.N * a.ng;
+            a.M = min(16, a.M - (int)rows_x);
+        }
         a.Xq += rows_x * a.K;
         a.sx += rows_x;
         a.Wt += rows_w * a.K / 2;
@@ -571,13 +579,31 @@ static int launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hip
     return hip_status(hipGetLastError());
 }
 
+int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G)
+{
+    // Measured against the tile kernel: up to four blocks win on every layer shape tried (C2 at 32
+    // tokens 16 -> 7 us, 13824 x 5120 group-128 at 64 tokens 46 -> 35 us), five to eight blocks only
+    // on small layers (4096 x 4096 at 128 tokens: 24 -> 15 us); each block streams the weights again.
+    if (M <= 16 || M > 128 || N <= 0) return 0;
+    if (M > 64 && N * K > (1LL << 24)) return 0;
+    if (K > (G != K ? 5120 : GV_MAX_AT * GV_CW * TILE_K)) return 0;   // K in one range only
+    const int nb = (int)((M + 15) / 16);
+    // the decode records cap the n-tiles per workgroup: not more than two generations of workgroups
+    if ((int64_t)plan_gemv(16, N, K, G, nb).blocks_per_split * nb > 512) return 0;
+    return nb;
+}
+
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
                 int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
                 hipStream_t st, int plain)
 {
-    const GemvPlan pl = plan_gemv(M, N, K, G, batch);
-    if (batch > 1 && (pl.splits > 1 || acc_out != nullptr)) return W4A8_ERR_SHAPE;
+    // 16 < M <= 128 where gemv_token_blocks says so: one launch over the 16-token blocks (batch must be 1)
+    const int token_blocks = M > 16 ? gemv_token_blocks(M, N, K, G) : 0;
+    if (M > 16 && (token_blocks == 0 || batch != 1)) return W4A8_ERR_SHAPE;
+    if (token_blocks) batch = token_blocks;
+    const GemvPlan pl = plan_gemv(token_blocks ? 16 : M, N, K, G, batch);
+    if (batch > 1 && (pl.splits > 1 || (acc_out != nullptr && !token_blocks))) return W4A8_ERR_SHAPE;
     const bool grouped = G != K;
     float *part = pl.splits > 1 ? partial : nullptr;
     GemvArgs ga;
@@ -588,6 +614,7 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     ga.tiles_per_group = (int)(G / TILE_K); ga.ng = (int)(K / G); ga.y_dtype = y_dtype;
     ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
     ga.nt_stride = pl.blocks_per_split;
+    ga.token_blocks = token_blocks;
     ga.plain = plain;
     ga.vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
     const bool asym = zp.zx != nullptr;

@@ -225,6 +225,9 @@ struct ZeroPoint {
 };
 // batch > 1: `batch` problems of one shape, every operand densely stacked (Y: M * ldy apart);
 // needs a single K-range and no accumulator hook.
+// 16 < M <= 128: the number of 16-token blocks that launch_gemv runs as one launch over shared weights
+// where that is faster than the tile kernel (K within one K-range, few blocks or a small layer); else 0
+int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G);
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
                 int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,

@@ -60,6 +60,13 @@ def test_workspace_sizes(lib):
     part = 10 * 128 * 5120 * 4
     assert lib.gemm_workspace_bytes(128, 5120, 5120, 128, lib.LAYOUT_TILED) == part
     assert lib.gemm_workspace_bytes(128, 5120, 5120, 0, lib.LAYOUT_TILED) == 10 * 128 * 4 + part
+    # 17 .. 64 tokens (.. 128 on small layers) run as 16-token blocks of the streaming kernel where K fits
+    # one range: nothing needed
+    assert lib.gemm_workspace_bytes(64, 5120, 5120, 128, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(17, 36864, 9216, 0, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(64, 5120, 13824, 128, lib.LAYOUT_TILED) > 0   # K in ranges: tile kernel
+    assert lib.gemm_workspace_bytes(128, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(128, 4096, 4096, 0, lib.LAYOUT_TILED) == 0
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):
@@ -101,8 +108,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert gemm(layout=3) == b.ERR_DTYPE
     assert gemm(Xq=Z) == b.ERR_NULL
     assert gemm(Xq=ctypes.c_void_p(0x1004)) == b.ERR_SHAPE   # int8 rows must be 16-byte aligned
-    assert gemm(M=64) == b.ERR_WORKSPACE             # prefill needs the row-sum workspace
-    assert gemm(M=64, ws=P, wsb=8) == b.ERR_WORKSPACE
+    assert gemm(M=200) == b.ERR_WORKSPACE            # the tile kernel needs the row-sum workspace
+    assert gemm(M=200, ws=P, wsb=8) == b.ERR_WORKSPACE
     assert gemm(layout=0) == b.ERR_WORKSPACE         # canonical weights are re-tiled into workspace
     assert gemm(M=0) == b.OK
     # asymmetric activations

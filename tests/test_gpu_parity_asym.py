@@ -107,6 +107,8 @@ GEMM_CASES = [
     ("decode_per_channel_7_tiles_ragged", 5, 6784, 48, 0),
     ("decode_many_n_tiles", 16, 512, 9232, 128),
     ("prefill_m17", 17, 384, 272, 0),
+    ("blocks_m33_g128", 33, 1280, 400, 128),
+    ("blocks_m50_per_channel", 50, 2304, 272, 0),
     ("prefill_m64_g128", 64, 512, 256, 128),
     ("prefill_m130_g128_ksplit", 130, 1024, 304, 128),
     ("prefill_m300", 300, 768, 1040, 0),
