@@ -38,7 +38,7 @@ constexpr int GV_CW = 8;                          // compute waves per workgroup
 constexpr int GV_THREADS = (GV_CW + 1) * WAVE;    // + 1 helper wave
 constexpr int GV_MAX_AT = 9;                      // k-tiles per compute wave -> K per split <= 9216 (5120 group-wise)
 constexpr int GV_REC_THREADS = GV_CW * WAVE;      // the compute waves prepare the decode records
-constexpr int GV_STAGE = 12;                      // decode records such a thread prepares at most
+constexpr int GV_STAGE = 16;                      // decode records such a thread prepares at most
 constexpr int GV_LDS_BUDGET = 128 * 1024;         // bytes of decode records per workgroup
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
 constexpr int GV_RED_BYTES = 2 * GV_CW * 256 * 4; // partial sums of the compute waves, double buffered
@@ -172,7 +172,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 #pragma unroll
         for (int i = 0; i < GV_STAGE; ++i) {
             // (a stage that is skipped leaves its registers unset: write_records skips it too)
-            if (i * GV_REC_THREADS < n_rec) {
+            if (i * GV_REC_THREADS >= n_rec) break;   // (uniform; one taken branch ends the stages)
+            {
                 const int e = min((int)threadIdx.x + i * GV_REC_THREADS, n_rec - 1);
                 const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;   // 16 j + row
                 const int ktl = e - t * recs_per_nt;
@@ -188,7 +189,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     auto write_records = [&]() {
 #pragma unroll
         for (int i = 0; i < GV_STAGE; ++i) {
-            if (i * GV_REC_THREADS < n_rec) {
+            if (i * GV_REC_THREADS >= n_rec) break;   // (uniform; one taken branch ends the stages)
+            {
                 const int e = (int)threadIdx.x + i * GV_REC_THREADS;
                 const int t = GROUPED ? (int)(((float)e + 0.5f) * inv_recs) : e;
                 // (opaque copies: arithmetic on the loaded values must not be moved up to the
@@ -585,11 +587,12 @@ int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G)
     // tokens 16 -> 7 us, 13824 x 5120 group-128 at 64 tokens 46 -> 35 us), five to eight blocks only
     // on small layers (4096 x 4096 at 128 tokens: 24 -> 15 us); each block streams the weights again.
     if (M <= 16 || M > 128 || N <= 0) return 0;
-    if (M > 64 && N * K > (1LL << 24)) return 0;
+    if (M > 64 && N * K > 48LL * (1 << 20)) return 0;
     if (K > (G != K ? 5120 : GV_MAX_AT * GV_CW * TILE_K)) return 0;   // K in one range only
     const int nb = (int)((M + 15) / 16);
     // the decode records cap the n-tiles per workgroup: not more than two generations of workgroups
-    if ((int64_t)plan_gemv(16, N, K, G, nb).blocks_per_split * nb > 512) return 0;
+    // (one for more than four blocks)
+    if ((int64_t)plan_gemv(16, N, K, G, nb).blocks_per_split * nb > (nb > 4 ? 256 : 512)) return 0;
     return nb;
 }
 

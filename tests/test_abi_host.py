@@ -55,11 +55,11 @@ def test_workspace_sizes(lib):
     # per-channel weights: a workgroup covers up to 9216 columns, no split below that
     assert lib.gemm_workspace_bytes(16, 36864, 9216, 0, lib.LAYOUT_TILED) == 0
     assert lib.gemm_workspace_bytes(16, 4096, 11008, 0, lib.LAYOUT_TILED) == 2 * 16 * 4096 * 4
-    # mid-size M with few output tiles: K is split as well (here 10 ranges of 4 k-tiles), and the
+    # mid-size M with few output tiles: K is split as well (here 9 ranges of 12 k-tiles), and the
     # per-channel variant adds one row-sum per (range, token), 256-byte aligned before the partials
-    part = 10 * 128 * 5120 * 4
-    assert lib.gemm_workspace_bytes(128, 5120, 5120, 128, lib.LAYOUT_TILED) == part
-    assert lib.gemm_workspace_bytes(128, 5120, 5120, 0, lib.LAYOUT_TILED) == 10 * 128 * 4 + part
+    part = 9 * 128 * 5120 * 4
+    assert lib.gemm_workspace_bytes(128, 5120, 13824, 128, lib.LAYOUT_TILED) == part
+    assert lib.gemm_workspace_bytes(128, 5120, 13824, 0, lib.LAYOUT_TILED) == 9 * 128 * 4 + part
     # 17 .. 64 tokens (.. 128 on small layers) run as 16-token blocks of the streaming kernel where K fits
     # one range: nothing needed
     assert lib.gemm_workspace_bytes(64, 5120, 5120, 128, lib.LAYOUT_TILED) == 0
