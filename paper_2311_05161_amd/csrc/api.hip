@@ -44,9 +44,12 @@ WsPlan plan_workspace(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
         w.part_off = off;          // few output tiles: K is split, fp32 partial sums
         w.part_bytes = gp.partial_bytes;
         off = align_up(off + w.part_bytes);
-    } else if (M > 0 && N > 0 && M <= 16) {
+    } else if (M > 0 && N > 0) {
+        // the streaming kernel (M <= 16, or a few 16-token blocks): fp32 partial sums when K is cut
+        const int nb = M > 16 ? gemv_token_blocks(M, N, K, G) : 1;
+        const GemvPlan gp = plan_gemv(M > 16 ? 16 : M, N, K, G, nb);
         w.part_off = off;
-        w.part_bytes = plan_gemv(M, N, K, G).partial_bytes;
+        w.part_bytes = gp.splits > 1 ? (size_t)gp.splits * M * N * sizeof(float) : 0;
         off = align_up(off + w.part_bytes);
     }
     w.total = off;

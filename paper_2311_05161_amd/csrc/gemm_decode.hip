@@ -92,6 +92,7 @@ struct GemvArgs {
     int plain;             // code space of ordinary INT4 (16 integer levels) instead of dINT4
     int vec_store;         // Y and ldy allow 8-byte stores of four outputs
     int token_blocks;      // blockIdx.z: 16-token blocks of one problem (shared weights) instead of problems
+    int part_rows;         // token rows of one K-range's slab of `partial` (all blocks' rows)
 };
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         const int64_t rows_x = a.token_blocks ? b * 16 : b * a.M;
         if (a.token_blocks) {
             if (a.acc_out != nullptr) a.acc_out += rows_x * a.N * a.ng;
+            if (a.partial != nullptr) a.partial += rows_x * a.N;
             a.M = min(16, a.M - (int)rows_x);
         }
         a.Xq += rows_x * a.K;
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             if (hm < M) {
                 const int n = nt_of(j) * TILE_N + hc;
                 if (!final_out) {
-                    float *pp = a.partial + ((int64_t)split * M + hm) * N + n;
+                    float *pp = a.partial + ((int64_t)split * a.part_rows + hm) * N + n;
                     *reinterpret_cast<v4f *>(pp) =
                         GROUPED ? sum
                                 : v4f{__int_as_float(isum.x), __int_as_float(isum.y),
@@ -521,8 +523,15 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
     const int q_stage = GV_STAGE * GV_REC_THREADS / (recs * 16);
     const int q_cap = q_lds < q_stage ? q_lds : q_stage;
     if (q > q_cap) {
-        q = q_cap;
-        bps = (NT + q - 1) / q;
+        // more than 256 workgroups: whole generations of them, all equally long (a short last
+        // generation still costs a workgroup's whole lifetime)
+        const int per = (int)(pl.splits * batch);
+        const int at_cap = (NT + q_cap - 1) / q_cap * per;
+        const int gens = (at_cap + 255) / 256;
+        bps = 256 * gens / per;
+        if (bps < (NT + q_cap - 1) / q_cap) bps = (NT + q_cap - 1) / q_cap;
+        if (bps > NT) bps = NT;
+        q = (NT + bps - 1) / bps;
     }
     pl.q = q;
     pl.blocks_per_split = bps;
@@ -588,11 +597,11 @@ int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G)
     // on small layers (4096 x 4096 at 128 tokens: 24 -> 15 us); each block streams the weights again.
     if (M <= 16 || M > 128 || N <= 0) return 0;
     if (M > 64 && N * K > 48LL * (1 << 20)) return 0;
-    if (K > (G != K ? 5120 : GV_MAX_AT * GV_CW * TILE_K)) return 0;   // K in one range only
     const int nb = (int)((M + 15) / 16);
     // the decode records cap the n-tiles per workgroup: not more than two generations of workgroups
     // (one for more than four blocks)
-    if ((int64_t)plan_gemv(16, N, K, G, nb).blocks_per_split * nb > (nb > 4 ? 256 : 512)) return 0;
+    const GemvPlan pl = plan_gemv(16, N, K, G, nb);
+    if ((int64_t)pl.blocks_per_split * pl.splits * nb > (nb > 4 ? 256 : 512)) return 0;
     return nb;
 }
 
@@ -606,7 +615,7 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     if (M > 16 && (token_blocks == 0 || batch != 1)) return W4A8_ERR_SHAPE;
     if (token_blocks) batch = token_blocks;
     const GemvPlan pl = plan_gemv(token_blocks ? 16 : M, N, K, G, batch);
-    if (batch > 1 && (pl.splits > 1 || (acc_out != nullptr && !token_blocks))) return W4A8_ERR_SHAPE;
+    if (batch > 1 && !token_blocks && (pl.splits > 1 || acc_out != nullptr)) return W4A8_ERR_SHAPE;
     const bool grouped = G != K;
     float *part = pl.splits > 1 ? partial : nullptr;
     GemvArgs ga;
@@ -618,6 +627,7 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     ga.kt_per_split = pl.kt_per_split; ga.nt_lo = pl.nt_lo; ga.nt_rem = pl.nt_rem;
     ga.nt_stride = pl.blocks_per_split;
     ga.token_blocks = token_blocks;
+    ga.part_rows = (int)M;
     ga.plain = plain;
     ga.vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
     const bool asym = zp.zx != nullptr;

@@ -64,7 +64,8 @@ def test_workspace_sizes(lib):
     # one range: nothing needed
     assert lib.gemm_workspace_bytes(64, 5120, 5120, 128, lib.LAYOUT_TILED) == 0
     assert lib.gemm_workspace_bytes(17, 36864, 9216, 0, lib.LAYOUT_TILED) == 0
-    assert lib.gemm_workspace_bytes(64, 5120, 13824, 128, lib.LAYOUT_TILED) > 0   # K in ranges: tile kernel
+    # K in three ranges: fp32 partial sums of all 64 token rows
+    assert lib.gemm_workspace_bytes(64, 5120, 13824, 128, lib.LAYOUT_TILED) == 3 * 64 * 5120 * 4
     assert lib.gemm_workspace_bytes(128, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
     assert lib.gemm_workspace_bytes(128, 4096, 4096, 0, lib.LAYOUT_TILED) == 0
 

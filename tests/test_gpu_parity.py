@@ -186,7 +186,8 @@ PREFILL_CASES = [
     ("m33_three_blocks_last_of_one_row_g128", 33, 1280, 400, 128),
     ("m50_blocks_per_channel_9_tiles_per_wave", 50, 9216, 272, 0),
     ("m64_blocks_many_n_tiles", 64, 512, 4112, 128),
-    ("m40_k_in_ranges_stays_on_the_tile_kernel", 40, 5248, 272, 128),
+    ("m40_blocks_with_k_in_two_ranges_g128", 40, 5248, 272, 128),
+    ("m24_blocks_with_k_in_two_ranges_per_channel", 24, 11008, 48, 0),
     ("m113_eight_blocks_small_layer", 113, 640, 528, 128),
     ("m100_ragged", 100, 640, 528, 0),
     ("m130_g128", 130, 1024, 304, 128),

@@ -109,6 +109,8 @@ GEMM_CASES = [
     ("prefill_m17", 17, 384, 272, 0),
     ("blocks_m33_g128", 33, 1280, 400, 128),
     ("blocks_m50_per_channel", 50, 2304, 272, 0),
+    ("blocks_m20_k_ranges_per_channel", 20, 11008, 32, 0),
+    ("blocks_m36_k_ranges_g128", 36, 9216, 48, 128),
     ("prefill_m64_g128", 64, 512, 256, 128),
     ("prefill_m130_g128_ksplit", 130, 1024, 304, 128),
     ("prefill_m300", 300, 768, 1040, 0),
