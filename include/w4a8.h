@@ -129,8 +129,8 @@ int unpack_dint4(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, in
  * (W4A8_ERR_SHAPE otherwise).  M == 0 or N == 0 is a no-op.
  * The M <= 16 path streams the packed weights once (memory-bound "decode" GEMV); larger M
  * uses the MFMA tile kernel ("prefill"), except that 17 .. 64 tokens (.. 128 on layers of at most
- * 48 Mi weights) with K <= 9216 (5120 with groups) run as 16-token blocks of the streaming kernel
- * in one launch where that is faster.  Results are deterministic (fixed reduction order). */
+ * 48 Mi weights) run as 16-token blocks of the streaming kernel in one launch where that is
+ * faster (w4a8_gemm_workspace_bytes knows which path a shape takes).  Results are deterministic (fixed reduction order). */
 size_t w4a8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size,
                                  int layout);
 int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
