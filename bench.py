@@ -345,6 +345,22 @@ def main():
             prefill.append({"workload": f"{name} M={Mp} K={Kp} N={Np} G={Gp or Kp}", "ms": round(ms, 4),
                             "TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
 
+    # ------------------------------------------------------------------ the LLaMA-13B layer sweep (side)
+    # K -> N in {5120 -> 5120, 5120 -> 13824, 13824 -> 5120} x M in {1, 16, 128, 512, 2048}, group-128:
+    # time per w4a8_gemm call, against both rooflines (M <= 16 is the HBM side, M >= 512 the matrix-core
+    # side, M = 128 sits at the ridge)
+    c4_sweep = []
+    if not args.no_prefill:
+        for (Kq, Nq) in [(5120, 5120), (5120, 13824), (13824, 5120)]:
+            for Mq in (1, 16, 128, 512, 2048):
+                ms, per = time_gemm(Mq, Nq, Kq, 128, 200 if Mq <= 128 else 20,
+                                    ring_bytes=(600 << 20) if Mq <= 16 else 0)
+                tops = 2.0 * Mq * Nq * Kq / (ms * 1e-3) / 1e12
+                c4_sweep.append({"workload": f"M={Mq} K={Kq} N={Nq} G=128", "us": round(ms * 1e3, 2),
+                                 "GBps": round(per / ms / 1e6, 1), "TOPS": round(tops, 1),
+                                 "frac_of_hbm_peak": round(per / ms / 1e6 / HBM_PEAK_GBS, 4),
+                                 "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
+
     # ------------------------------------------------------------------ quantizer kernels and C5 end to end (side)
     quant_side = None
     if not args.no_prefill:
@@ -533,7 +549,7 @@ def main():
         "offline": {"what": "quantize_weight_dint4 + pack_dint4 (tiled), once per weight matrix",
                     "ms": round(offline_ms, 4),
                     "GBps": round((N * K * 2 + N * K + N * K + N * K // 2) / (offline_ms * 1e-3) / 1e9, 1)},
-        "decode_other_shapes": decode_side, "prefill": prefill,
+        "decode_other_shapes": decode_side, "prefill": prefill, "c4_layer_sweep": c4_sweep,
         "asymmetric_activations": {"what": "w4a8_gemm_asym (token zero-point taken out of the int32 "
                                            "accumulators), same shapes and protocol as the lists above",
                                    "shapes": asym_side},

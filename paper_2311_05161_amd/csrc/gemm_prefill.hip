@@ -727,7 +727,9 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
     pl.splits = 1;
     pl.kt_per_split = KT;
     if (tiles < 128 && KT >= 8) {
-        const int want = (int)((256 + tiles - 1) / tiles);
+        // (rounded down: a few workgroups beyond 256 make a second generation that costs as much as
+        // the first)
+        const int want = (int)(256 / tiles);
         int unit = grouped ? tpg : 1;           // k-tiles that must stay together
         while (unit < 4) unit += grouped ? tpg : 1;
         int kps = (KT + want - 1) / want;
