@@ -114,6 +114,7 @@ GEMM_CASES = [
     ("prefill_m64_g128", 64, 512, 256, 128),
     ("prefill_m130_g128_ksplit", 130, 1024, 304, 128),
     ("prefill_m300", 300, 768, 1040, 0),
+    ("prefill_two_workgroups_per_cu_ragged", 1030, 256, 7440, 0),
     ("prefill_m300_g256", 300, 768, 512, 256),
     ("prefill_m600_multi_block", 600, 1024, 784, 0),
     ("prefill_m128_ksplit_per_channel", 128, 2048, 512, 0),
