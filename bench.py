@@ -361,6 +361,14 @@ def main():
                                  "frac_of_hbm_peak": round(per / ms / 1e6 / HBM_PEAK_GBS, 4),
                                  "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
 
+    # 17 .. 128 tokens on the C2 layer: 16-token blocks of the streaming kernel in one launch
+    mid_tokens = []
+    if not args.no_prefill:
+        for Mq in (17, 32, 64, 128):
+            ms, per = time_gemm(Mq, N, K, G, 300, ring_bytes=0)
+            mid_tokens.append({"workload": f"M={Mq} K={K} N={N} G={G}", "us": round(ms * 1e3, 2),
+                               "TOPS": round(2.0 * Mq * N * K / (ms * 1e-3) / 1e12, 1)})
+
     # ------------------------------------------------------------------ quantizer kernels and C5 end to end (side)
     quant_side = None
     if not args.no_prefill:
@@ -549,7 +557,7 @@ def main():
         "offline": {"what": "quantize_weight_dint4 + pack_dint4 (tiled), once per weight matrix",
                     "ms": round(offline_ms, 4),
                     "GBps": round((N * K * 2 + N * K + N * K + N * K // 2) / (offline_ms * 1e-3) / 1e9, 1)},
-        "decode_other_shapes": decode_side, "prefill": prefill, "c4_layer_sweep": c4_sweep,
+        "decode_other_shapes": decode_side, "prefill": prefill, "c4_layer_sweep": c4_sweep, "c2_17_to_128_tokens": mid_tokens,
         "asymmetric_activations": {"what": "w4a8_gemm_asym (token zero-point taken out of the int32 "
                                            "accumulators), same shapes and protocol as the lists above",
                                    "shapes": asym_side},
