@@ -593,8 +593,8 @@ static int launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hip
 int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G)
 {
     // Measured against the tile kernel: up to four blocks win on every layer shape tried (C2 at 32
-    // tokens 16 -> 7 us, 13824 x 5120 group-128 at 64 tokens 46 -> 35 us), five to eight blocks only
-    // on small layers (4096 x 4096 at 128 tokens: 24 -> 15 us); each block streams the weights again.
+    // tokens 16 -> 7 us, 13824 x 5120 group-128 at 64 tokens 46 -> 31 us), five to eight blocks only
+    // on smaller layers (5120 x 5120 at 128 tokens: 27 -> 20 us); each block streams the weights again.
     if (M <= 16 || M > 128 || N <= 0) return 0;
     if (M > 64 && N * K > 48LL * (1 << 20)) return 0;
     const int nb = (int)((M + 15) / 16);
