@@ -15,6 +15,7 @@ from __future__ import annotations
 import argparse
 import ctypes
 import json
+import math
 import os
 import sys
 import time
@@ -285,20 +286,66 @@ def main():
                     "gemv_C2_cache_resident_us": round(resident_us, 3)}
 
     # ------------------------------------------------------------------ larger decode shapes (side figures)
-    def time_gemm(Mq, Nq, Kq, Gq, reps, ring_bytes=600 << 20, asym=False):
-        """Back-to-back w4a8_gemm (or w4a8_gemm_asym) launches over a ring of random packed weights
-        (timing only)."""
+    def draw_layer(fam, Mq, Kq, Nq, Gq, g):
+        """Quantized operands of a layer drawn on the GPU by the recipe of synthetic_inputs.make_layer
+        (same distributions and outlier structure, not the same bits), through the library's own
+        quantizers.  The compute-bound timings need this: what the int8 operands look like decides
+        the power the matrix cores draw and with it the clock (all-zero activations: 2.38 GHz,
+        uniformly random int8: 1.78 GHz on the same launch)."""
+        X = torch.randn((Mq, Kq), device=dev, generator=g)
+        n_out = max(1, round(0.01 * Kq)) if fam == "C5" else max(1, math.ceil(0.005 * Kq))
+        ch = torch.randperm(Kq, device=dev, generator=g)[:n_out]
+        if fam == "C4":   # heavy-tailed outlier channels: 50 x Student-t(3)
+            z = torch.randn((Mq, n_out), device=dev, generator=g)
+            chi = torch.randn((3, Mq, n_out), device=dev, generator=g).square().sum(0) / 3.0
+            X[:, ch] = 50.0 * z / chi.sqrt()
+        else:
+            X[:, ch] *= 100.0 if fam == "C5" else 50.0
+        X = X.clamp_(-65504.0, 65504.0).to(torch.float16)
+        s = torch.rand((Kq,), device=dev, generator=g) * 1.5 + 0.5
+        wp_, st_, z_ = None, [], []
+        rows = max(16, (1 << 26) // Kq // 16 * 16)   # weights in slabs of about 64 Mi elements
+        if fam == "C5":   # the alpha = 0.5 point of the max-based scale family
+            aw = torch.zeros((Kq,), device=dev)
+            gw = torch.Generator(device=dev)
+            gw.manual_seed(g.initial_seed() + 1)
+            for r0 in range(0, Nq, rows):
+                Wb = (torch.randn((min(rows, Nq - r0), Kq), device=dev, generator=gw) * 0.02).to(torch.float16)
+                aw = torch.maximum(aw, Wb.float().abs().amax(0))
+            s = (X.float().abs().amax(0).clamp_min(1e-5).sqrt() / aw.clamp_min(1e-5).sqrt()).contiguous()
+        xq_, sx_ = w.quantize_act_int8(X, s)
+        gw = torch.Generator(device=dev)
+        gw.manual_seed(g.initial_seed() + 1)
+        codes = torch.empty((Nq, Kq), dtype=torch.uint8, device=dev)
+        for r0 in range(0, Nq, rows):
+            Wb = (torch.randn((min(rows, Nq - r0), Kq), device=dev, generator=gw) * 0.02).to(torch.float16)
+            c_, s_b, z_b = w.quantize_weight_dint4(Wb, s, Gq)
+            codes[r0:r0 + Wb.shape[0]] = c_
+            st_.append(s_b)
+            z_.append(z_b)
+        wp_ = w.pack_dint4(codes, w.LAYOUT_TILED)
+        return xq_, sx_, wp_, torch.cat(st_).contiguous(), torch.cat(z_).contiguous()
+
+    def time_gemm(Mq, Nq, Kq, Gq, reps, ring_bytes=600 << 20, asym=False, fam=None):
+        """Back-to-back w4a8_gemm (or w4a8_gemm_asym) launches (timing only).  fam = None: a ring of
+        random packed weights and random int8 activations (the memory-bound side: values do not
+        matter there); fam = "C3" / "C4" / "C5": one set of operands quantized from that
+        configuration's distributions."""
         g = torch.Generator(device=dev)
         g.manual_seed(20231105)
         Gs = Kq if Gq == 0 else Gq
         per = decode_bytes(Mq, Nq, Kq, Gs)
         nring = max(2, min(32, ring_bytes // per + 1))
-        wps = [torch.randint(0, 256, (Nq * Kq // 2,), dtype=torch.uint8, device=dev, generator=g)
-               for _ in range(nring)]
-        stq = torch.rand((Nq, Kq // Gs), device=dev, generator=g) * 0.01 + 0.001
-        zq = torch.randint(0, 14, (Nq, Kq // Gs), dtype=torch.uint8, device=dev, generator=g)
-        xq = torch.randint(-127, 128, (Mq, Kq), dtype=torch.int8, device=dev, generator=g)
-        sxq = torch.rand((Mq,), device=dev, generator=g) * 0.01 + 0.001
+        if fam is not None:
+            xq, sxq, wp0, stq, zq = draw_layer(fam, Mq, Kq, Nq, Gq, g)
+            wps, nring = [wp0], 1
+        else:
+            wps = [torch.randint(0, 256, (Nq * Kq // 2,), dtype=torch.uint8, device=dev, generator=g)
+                   for _ in range(nring)]
+            stq = torch.rand((Nq, Kq // Gs), device=dev, generator=g) * 0.01 + 0.001
+            zq = torch.randint(0, 14, (Nq, Kq // Gs), dtype=torch.uint8, device=dev, generator=g)
+            xq = torch.randint(-127, 128, (Mq, Kq), dtype=torch.int8, device=dev, generator=g)
+            sxq = torch.rand((Mq,), device=dev, generator=g) * 0.01 + 0.001
         yq = torch.empty((Mq, Nq), dtype=torch.float16, device=dev)
         wsb = w.gemm_workspace_bytes(Mq, Nq, Kq, Gq)
         wsq = torch.empty((max(1, wsb),), dtype=torch.uint8, device=dev)
@@ -340,7 +387,7 @@ def main():
         for (name, Mp, Kp, Np, Gp) in [("C3_up", 2048, 4096, 11008, 0), ("C3_down", 2048, 11008, 4096, 0),
                                        ("C4", 2048, 5120, 13824, 128), ("C4", 512, 5120, 13824, 128),
                                        ("C5", 4096, 9216, 36864, 0)]:
-            ms, _ = time_gemm(Mp, Np, Kp, Gp, 20, ring_bytes=0)
+            ms, _ = time_gemm(Mp, Np, Kp, Gp, 20, ring_bytes=0, fam=name[:2])
             tops = 2.0 * Mp * Np * Kp / (ms * 1e-3) / 1e12
             prefill.append({"workload": f"{name} M={Mp} K={Kp} N={Np} G={Gp or Kp}", "ms": round(ms, 4),
                             "TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)})
@@ -354,7 +401,7 @@ def main():
         for (Kq, Nq) in [(5120, 5120), (5120, 13824), (13824, 5120)]:
             for Mq in (1, 16, 128, 512, 2048):
                 ms, per = time_gemm(Mq, Nq, Kq, 128, 200 if Mq <= 128 else 20,
-                                    ring_bytes=(600 << 20) if Mq <= 16 else 0)
+                                    ring_bytes=(600 << 20) if Mq <= 16 else 0, fam=None if Mq <= 16 else "C4")
                 tops = 2.0 * Mq * Nq * Kq / (ms * 1e-3) / 1e12
                 c4_sweep.append({"workload": f"M={Mq} K={Kq} N={Nq} G=128", "us": round(ms * 1e3, 2),
                                  "GBps": round(per / ms / 1e6, 1), "TOPS": round(tops, 1),
