@@ -211,6 +211,11 @@ def test_gemm_bf16_output_and_canonical_layout(lib, oracle):
     _gemm_case(lib, oracle, 6, 40, 512, 64, 0, out_dtype="bf16")
     _gemm_case(lib, oracle, 7, 9, 256, 32, 128, layout=0)
     _gemm_case(lib, oracle, 8, 70, 256, 48, 0, layout=0)
+    # the tile kernel's bf16 epilogue: staged whole-row stores, direct stores of a ragged tile,
+    # group-wise sums, K cut into ranges, and its canonical-layout repack
+    _gemm_case(lib, oracle, 9, 300, 512, 512, 0, out_dtype="bf16")
+    _gemm_case(lib, oracle, 10, 150, 384, 272, 128, out_dtype="bf16")
+    _gemm_case(lib, oracle, 11, 200, 1024, 304, 0, out_dtype="bf16", layout=0)
 
 
 @pytest.mark.parametrize("M,K,N,G", [(16, 512, 272, 128), (5, 1152, 48, 0), (3, 9216, 32, 128), (40, 512, 256, 0),
