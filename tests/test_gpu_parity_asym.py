@@ -130,6 +130,9 @@ def test_gemm_asym_parity(lib, oracle, case):
 def test_gemm_asym_bf16_and_canonical(lib, oracle):
     _gemm_asym_case(lib, oracle, 6, 12, 512, 64, 128, out_dtype="bf16")
     _gemm_asym_case(lib, oracle, 7, 40, 256, 48, 0, layout=0)
+    # the tile kernel: bf16 output per-channel and group-wise, canonical weights
+    _gemm_asym_case(lib, oracle, 8, 200, 512, 272, 0, out_dtype="bf16")
+    _gemm_asym_case(lib, oracle, 9, 150, 384, 256, 128, out_dtype="bf16", layout=0)
 
 
 def test_asym_with_symmetric_tokens_matches_dequantized_product(lib, oracle):
