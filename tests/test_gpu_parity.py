@@ -289,11 +289,11 @@ def test_aqas_power_of_two_invariance_on_gpu(lib, oracle):
 
 
 # --------------------------------------------------------------------------- full-size configurations
-def _full_size_case(lib, oracle, name, M=None, n_samples=96, seed=0):
+def _full_size_case(lib, oracle, name, M=None, n_samples=96, seed=0, N=None):
     """A BASELINE configuration at its real size, in the launch configuration bench.py times:
     quantizers compared in full (bit-exact), accumulators and Y on sampled outputs that the plain
     oracle computes one by one (whole rows and columns would take the triple loop hours)."""
-    X, W, s, G = syn.make_layer(name, M=M)
+    X, W, s, G = syn.make_layer(name, M=M, N=N)
     Mq, K = X.shape
     N = W.shape[0]
     Xd, Wd, sd = dev(X), dev(W), dev(s)
@@ -345,6 +345,14 @@ def test_full_size_c2_decode_all_m(lib, oracle):
                                     ("C4_5120x5120", 128), ("C4_5120x13824", 1)])
 def test_full_size_llama_shapes(lib, oracle, name, M):
     _full_size_case(lib, oracle, name, M=M, seed=M)
+
+
+def test_64_token_tiles_on_a_layer_too_large_for_token_blocks(lib, oracle):
+    """64 tokens on 24832 x 5120 group-128 weights: four 16-token blocks would need more than two
+    generations of workgroups, so this runs on the tile kernel's 64-row instance."""
+    # (the workspace tells: two K-ranges of fp32 partial sums, which only the tile kernel asks for here)
+    assert lib.gemm_workspace_bytes(64, 24832, 5120, 128, lib.LAYOUT_TILED) == 2 * 64 * 24832 * 4
+    _full_size_case(lib, oracle, "C4_5120x13824", M=64, N=24832, seed=64)
 
 
 def test_full_size_c5_opt66b_end_to_end(lib, oracle):
