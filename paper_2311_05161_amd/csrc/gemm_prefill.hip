@@ -706,8 +706,8 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
     GemmPlan pl;
     const bool grouped = G != K;
     const int64_t gn = (N + GM_BN - 1) / GM_BN;
-    if (M <= 64) {
-        pl.bm = 64;
+    if (M <= 64 && grouped) {
+        pl.bm = 64;    // (per-channel layers with so few tokens run as token blocks of the streaming kernel)
     } else if (grouped || M <= 128) {
         pl.bm = 128;   // group-wise: int32 group accumulators plus fp32 running sums
     } else {
@@ -769,8 +769,7 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
         if (pl.bm == 64) W4A8_GM(64, 1, 4, true, false);
         else W4A8_GM(128, 1, 8, true, false);
     } else {
-        if (pl.bm == 64) W4A8_GM(64, 1, 4, false, false);
-        else if (pl.bm == 128 && wgs > 256) W4A8_GM(128, 1, 8, false, true);
+        if (pl.bm == 128 && wgs > 256) W4A8_GM(128, 1, 8, false, true);
         else if (pl.bm == 128) W4A8_GM(128, 1, 8, false, false);
         else W4A8_GM(256, 2, 4, false, false);
     }
