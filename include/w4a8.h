@@ -10,6 +10,7 @@
  * Conventions for EVERY entry point
  *   - All data pointers are DEVICE pointers (HIP global memory) owned by the caller; the
  *     library allocates nothing, frees nothing and keeps no state between calls.
+ *     (The bench aids that time the machine's own ceilings are declared in w4a8_measure.h.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued on it and the call returns without synchronizing.
  *   - The return value is a w4a8_status.  Argument errors are detected on the host before
@@ -324,17 +325,6 @@ size_t dint_error_terms_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t
 int dint_error_terms(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const void *W,
                      int w_dtype, int64_t N, int64_t ldw, const float *s, int64_t group_size, int format,
                      double *terms, void *workspace, size_t workspace_bytes, void *stream);
-
-/* Measured ceilings of the machine, printed by the bench beside the nominal peaks; neither is a step of
- * the method.  w4a8_measure_stream_read reads `bytes` bytes of device memory once (16-byte loads,
- * 512 x 512 lanes, four loads in flight per lane) and writes nothing; w4a8_measure_mfma_i8 runs `iters`
- * rounds of eight independent v_mfma_i32_32x32x32_i8 per wave on register operands (512 workgroups of
- * four waves) and stores the number of integer operations issued (2 per multiply-accumulate) to *ops.
- *   buf: device, 16-byte aligned, bytes % 16 == 0; sink: device uint32 or NULL (never written in
- *   practice: it only keeps the work alive); ops: HOST pointer or NULL; iters <= 2^24.
- * Both only enqueue work on `stream`; the caller times them. */
-int w4a8_measure_stream_read(const void *buf, int64_t bytes, uint32_t *sink, void *stream);
-int w4a8_measure_mfma_i8(int64_t iters, uint32_t *sink, int64_t *ops, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *w4a8_status_string(int status);

@@ -20,6 +20,19 @@ inline bool resolve_group(int64_t K, int64_t &G)
     return G > 0 && K > 0 && K % G == 0;
 }
 
+// the shape limits of the GEMM entry points (G already resolved): what the kernels' tiles, 32-bit
+// offsets and launch plans assume.  Everything that sizes a workspace or plans a launch checks
+// this first, so no plan ever sees an empty dimension.
+inline bool gemm_shape_ok(int64_t M, int64_t N, int64_t K, int64_t G)
+{
+    if (M < 0 || N < 0 || K < TILE_K || G < TILE_K || K % G != 0) return false;
+    if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K) return false;
+    if (M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL) return false;   // 32-bit byte offsets into the weights
+    // the tile kernel addresses Xq with 32-bit byte offsets and numbers its tiles in 32 bits
+    if (M > 16 && (M * K > 0x7fffffffLL || (M + 63) / 64 * ((N + 255) / 256) > 0x1ffffLL)) return false;
+    return true;
+}
+
 struct WsPlan {
     size_t repack_off, repack_bytes;  // canonical -> tiled copy of the weights
     size_t rs_off, rs_bytes;          // per-token row-sums (M > 16, per-channel weights only)
@@ -70,12 +83,7 @@ int gemm_common(const int8_t *Xq, const float *sx, const int32_t *zx, int64_t M,
     if (y_dtype != W4A8_F16 && y_dtype != W4A8_BF16) return W4A8_ERR_DTYPE;
     int64_t G = group_size;
     if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
-    if (N % TILE_N != 0 || K % TILE_K != 0 || G % TILE_K != 0 || K > MAX_K || ldy < N ||
-        M > 0x7fffffffLL || N * K / 2 > 0x7fffffffLL)  // 32-bit byte offsets into the weights
-        return W4A8_ERR_SHAPE;
-    // the tile kernel addresses Xq with 32-bit byte offsets and numbers its tiles in 32 bits
-    if (M > 16 && (M * K > 0x7fffffffLL || (M + 63) / 64 * ((N + 255) / 256) > 0x1ffffLL))
-        return W4A8_ERR_SHAPE;
+    if (!gemm_shape_ok(M, N, K, G) || ldy < N) return W4A8_ERR_SHAPE;
     if (M == 0 || N == 0) return W4A8_OK;
     if (!Xq || !sx || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;
     if ((uintptr_t)Xq % 16 != 0 || (uintptr_t)Wp % 16 != 0 || (uintptr_t)Y % 2 != 0 ||
@@ -245,8 +253,7 @@ int unpack_dint4(const uint8_t *packed, int64_t N, int64_t K, uint8_t *codes, in
 size_t w4a8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout)
 {
     int64_t G = group_size;
-    if (M < 0 || N < 0 || !resolve_group(K, G) || !valid_layout(layout) || K % TILE_K != 0 ||
-        G % TILE_K != 0 || N % TILE_N != 0)
+    if (!resolve_group(K, G) || !gemm_shape_ok(M, N, K, G) || !valid_layout(layout) || M == 0 || N == 0)
         return 0;
     return plan_workspace(M, N, K, G, layout).total;
 }
@@ -566,7 +573,8 @@ int expand_special_value(const uint8_t *codes, const float *step, const uint8_t 
 size_t w4a8_gemm_special_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout)
 {
     int64_t G = group_size;
-    if (M <= 0 || N <= 0 || !resolve_group(K, G)) return 0;
+    if (M <= 0 || N <= 0 || !resolve_group(K, G) || !gemm_shape_ok(M, N, 2 * K, G) || !valid_layout(layout))
+        return 0;
     return align_up((size_t)(M * 2 * K)) + plan_workspace(M, N, 2 * K, G, layout).total;
 }
 

@@ -500,8 +500,9 @@ __global__ __launch_bounds__(256) void gemv_combine_kernel(const float *__restri
 
 GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
 {
-    GemvPlan pl;
+    GemvPlan pl{};
     const int KT = (int)(K / TILE_K), NT = (int)(N / TILE_N);
+    if (KT < 1 || NT < 1 || batch < 1) return pl;   // nothing to launch (callers check shapes first)
     // group-wise weights keep at most 5 k-tiles per wave: their decode records (one per channel and
     // k-tile) would otherwise leave room for too few n-tiles per workgroup in LDS
     const int max_at = (G != K) ? 5 : GV_MAX_AT;

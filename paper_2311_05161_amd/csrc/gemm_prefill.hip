@@ -9,10 +9,11 @@
 // 4 KB of its 64 channels straight from global memory (16-byte buffer loads, issued two k-tiles
 // ahead), turns the nibbles into int8 through the per-channel register LUT and reuses each
 // decoded operand for all its 32-token sub-tiles.  The int8 activations are shared by the waves
-// through a three-deep ring of LDS tiles (global -> registers -> LDS, three k-tiles ahead of the
-// MFMAs; 16-byte chunks XOR-swizzled by row pair so that staging writes and ds_read_b128 operand
-// reads are conflict free on the 64-bank LDS).  One barrier per k-tile; the operands of the
-// first k-step of the next tile are fetched before it.
+// through a ring of four LDS tiles that are filled global -> LDS directly (buffer_load ... lds, no
+// staging registers, no ds_write), three k-tiles ahead of the MFMAs; their 16-byte chunks are
+// XOR-swizzled by row pair -- on the global side, since a wave's copy lands in lane order -- so that
+// the ds_read_b128 operand reads are conflict free on the 64-bank LDS.  One barrier per k-tile; the
+// operands of the first k-step of the next tile are fetched before it.
 //
 // Per-channel weights use the biased decode (7 operations per 8 weights); the bias is removed once,
 // in the epilogue, with per-token row-sums from a small pre-pass.  Group-wise weights must rescale
@@ -703,9 +704,10 @@ static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, 
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
 {
-    GemmPlan pl;
+    GemmPlan pl{};
     const bool grouped = G != K;
     const int64_t gn = (N + GM_BN - 1) / GM_BN;
+    if (M < 1 || gn < 1 || K < TILE_K) return pl;   // nothing to launch (callers check shapes first)
     if (M <= 64 && grouped) {
         pl.bm = 64;    // (per-channel layers with so few tokens run as token blocks of the streaming kernel)
     } else if (grouped || M <= 128) {

@@ -7,6 +7,7 @@
 #include <atomic>
 
 #include "../../include/w4a8.h"
+#include "../../include/w4a8_measure.h"
 
 namespace w4a8 {
 

@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "w4a8.h")
+INCLUDE = os.path.join(ROOT, "include")
 
 
 @pytest.fixture(scope="module")
@@ -20,9 +20,15 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
+    """Every function that any header under include/ declares."""
+    names = set()
+    for fn in sorted(os.listdir(INCLUDE)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(INCLUDE, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -68,6 +74,23 @@ def test_workspace_sizes(lib):
     assert lib.gemm_workspace_bytes(64, 5120, 13824, 128, lib.LAYOUT_TILED) == 3 * 64 * 5120 * 4
     assert lib.gemm_workspace_bytes(128, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
     assert lib.gemm_workspace_bytes(128, 4096, 4096, 0, lib.LAYOUT_TILED) == 0
+    # empty or invalid shapes size to nothing (and divide by nothing): an empty dimension, a K or a
+    # group that is no multiple of 128, a channel count that is no multiple of 16
+    L = lib.load_library()
+    assert lib.gemm_workspace_bytes(32, 0, 1024, 0, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(0, 4096, 1024, 0, lib.LAYOUT_CANONICAL) == 0
+    assert lib.gemm_workspace_bytes(2048, 0, 1024, 128, lib.LAYOUT_CANONICAL) == 0
+    assert lib.gemm_workspace_bytes(32, 16, 0, 0, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(32, 16, 64, 0, lib.LAYOUT_TILED) == 0
+    assert lib.gemm_workspace_bytes(32, 16, 65536 + 128, 0, lib.LAYOUT_TILED) == 0
+    assert L.w4a8_gemm_special_workspace_bytes(1, 16, 32, 0, 1) == 0
+    assert L.w4a8_gemm_special_workspace_bytes(1, 16, 0, 0, 1) == 0
+    assert L.w4a8_gemm_special_workspace_bytes(1, 24, 128, 0, 1) == 0
+    assert L.w4a8_gemm_special_workspace_bytes(1, 16, 256, 64, 1) == 0
+    assert L.w4a8_gemm_special_workspace_bytes(1, 16, 256, 0, 7) == 0
+    assert L.w4a8_gemm_special_workspace_bytes(40, 16, 32768 + 128, 0, 1) == 0
+    # the no-op GEMM with an empty output and many tokens goes through the binding's workspace query
+    assert L.w4a8_gemm(None, None, 32, None, 1, None, None, 0, 1024, 0, None, 1, 16, None, None, 0, None) == 0
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):
