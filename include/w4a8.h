@@ -140,6 +140,30 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
               void *Y, int y_dtype, int64_t ldy,
               int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* w4a8_gemm for callers that cannot allocate device memory or carry a workspace around: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
+ * kernels, same results and same argument errors as w4a8_gemm; the workspace is a static device
+ * array inside the library of W4A8_STATIC_SCRATCH_BYTES bytes (64 MiB; every GPU the library runs
+ * on holds it until the process ends).  The call allocates and frees nothing.
+ *   - A shape whose w4a8_gemm_workspace_bytes exceeds W4A8_STATIC_SCRATCH_BYTES is rejected with
+ *     W4A8_ERR_WORKSPACE before anything is launched.  (What a shape needs: nothing for tiled
+ *     weights whose K fits one range of the streaming kernel; splits * M * N * 4 bytes of partial
+ *     sums where K is cut into ranges; 4 bytes per token for per-channel weights on the tile
+ *     kernel; N * K / 2 bytes for canonical-layout weights.  64 MiB holds all of that for the
+ *     LLaMA-7B/13B and OPT-66B layer shapes with tiled weights at any token count.)
+ *   - All calls on one GPU share that GPU's array: calls whose work may overlap in time on one GPU
+ *     (different streams, different threads) race on it and must be serialized by the caller.  A
+ *     call needs nothing from what an earlier call left in the array.
+ *   - The first call on a device that needs scratch asks the runtime for the array's address there
+ *     (hipGetSymbolAddress, no allocation); make that call outside graph capture.
+ *   w4a8_gemm_static_scratch_bytes returns W4A8_STATIC_SCRATCH_BYTES. */
+#define W4A8_STATIC_SCRATCH_BYTES (64u << 20)
+size_t w4a8_gemm_static_scratch_bytes(void);
+int w4a8_gemm_static(const int8_t *Xq, const float *sx, int64_t M,
+                     const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                     int64_t N, int64_t K, int64_t group_size,
+                     void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *stream);
+
 /* ---- Asymmetric activations: the min-max, token-wise 8-bit quantizer with a zero-point that the
  * paper itself uses for activations (App. A.1, "Quantization Settings"), and the GEMM for it. ----
  *

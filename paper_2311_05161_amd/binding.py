@@ -23,6 +23,7 @@ _DTYPES = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 EXPORTS = (
     "quantize_act_int8", "quantize_weight_dint4", "pack_dint4", "unpack_dint4",
     "w4a8_gemm_workspace_bytes", "w4a8_gemm", "w4a8_status_string",
+    "w4a8_gemm_static", "w4a8_gemm_static_scratch_bytes",
     "quantize_act_int8_asym", "dint4_weight_sums", "w4a8_gemm_asym", "w4a8_gemm_batched",
     "quantize_value_dint4",
     "aqas_search_workspace_bytes", "aqas_channel_absmax", "aqas_scale", "aqas_search",
@@ -67,6 +68,10 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.w4a8_gemm_workspace_bytes.restype = sz
     lib.w4a8_gemm.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, vp, ci, i64, vp, vp, sz, vp]
     lib.w4a8_gemm.restype = ci
+    lib.w4a8_gemm_static.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, vp, ci, i64, vp, vp]
+    lib.w4a8_gemm_static.restype = ci
+    lib.w4a8_gemm_static_scratch_bytes.argtypes = []
+    lib.w4a8_gemm_static_scratch_bytes.restype = sz
     lib.quantize_act_int8_asym.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp, vp]
     lib.quantize_act_int8_asym.restype = ci
     lib.dint4_weight_sums.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
@@ -222,6 +227,20 @@ def w4a8_gemm(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.
                                     _DTYPES[Y.dtype], ldy, _ptr(acc_out), _ptr(workspace), ws_bytes,
                                     _stream()), "w4a8_gemm")
     return (Y, acc_out) if want_acc else Y
+
+
+def w4a8_gemm_static(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.Tensor,
+                     zero: torch.Tensor, N: int, K: int, group_size: int = 0, layout: int = LAYOUT_TILED,
+                     Y=None, acc_out=None):
+    """w4a8_gemm on the library's static scratch: Y and acc_out come from the caller (this wrapper
+    allocates nothing either)."""
+    M = Xq.shape[0]
+    ldy = Y.stride(0) if M > 1 else max(Y.stride(0), N)
+    _check(load_library().w4a8_gemm_static(_ptr(Xq), _ptr(sx), M, _ptr(Wp), int(layout), _ptr(step),
+                                           _ptr(zero), N, K, int(group_size or 0), _ptr(Y),
+                                           _DTYPES[Y.dtype], ldy, _ptr(acc_out), _stream()),
+           "w4a8_gemm_static")
+    return Y
 
 
 def quantize_act_int8_asym(X: torch.Tensor, s: torch.Tensor | None = None, Xq=None, sx=None,

@@ -304,6 +304,76 @@ int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int6
                        batch, (hipStream_t)stream);
 }
 
+
+// ---- w4a8_gemm for callers that cannot allocate: the workspace is a static device array ----------
+}  // extern "C"
+
+// The scratch memory of w4a8_gemm_static: every GPU the library runs on holds its own copy of this
+// array, at its own address, until the process ends.  In host code the array's NAME is only a
+// stand-in for the symbol (not a device address): the address on the current device comes from
+// hipGetSymbolAddress, once per device, and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) uint8_t scratch[W4A8_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int SCRATCH_MAX_DEVICES = 64;
+std::atomic<uint8_t *> scratch_ptr[SCRATCH_MAX_DEVICES];   // per device ordinal; null = not asked yet
+
+// Address of `scratch` on the current device (nullptr with *status set on failure).  Racing first
+// calls on one device both ask the runtime and store the same answer.
+uint8_t *scratch_on_current_device(int *status)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        *status = W4A8_ERR_HIP;
+        return nullptr;
+    }
+    const bool cached = dev >= 0 && dev < SCRATCH_MAX_DEVICES;
+    if (cached) {
+        uint8_t *known = scratch_ptr[dev].load(std::memory_order_acquire);
+        if (known != nullptr) return known;
+    }
+    uint8_t *ptr = nullptr;
+    if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+        (void)hipGetLastError();   // reported through the status; leave no sticky error behind
+        *status = W4A8_ERR_HIP;
+        return nullptr;
+    }
+    if (cached) scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t w4a8_gemm_static_scratch_bytes(void) { return W4A8_STATIC_SCRATCH_BYTES; }
+
+int w4a8_gemm_static(const int8_t *Xq, const float *sx, int64_t M,
+                     const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                     int64_t N, int64_t K, int64_t group_size,
+                     void *Y, int y_dtype, int64_t ldy, int32_t *acc_out, void *stream)
+{
+    // every check of w4a8_gemm first (with a workspace that is certainly large enough), so that
+    // argument errors come back exactly as they do there and before the size limit is looked at
+    static_assert(W4A8_STATIC_SCRATCH_BYTES % WS_ALIGN == 0, "scratch size keeps the workspace alignment");
+    void *const probe = (void *)(uintptr_t)WS_ALIGN;   // never dereferenced: validate_only launches nothing
+    int rc = gemm_common(Xq, sx, nullptr, M, Wp, layout, step, zero, nullptr, nullptr, N, K, group_size, Y,
+                         y_dtype, ldy, acc_out, probe, SIZE_MAX, stream, W4A8_FMT_DINT4, true);
+    if (rc != W4A8_OK || M == 0 || N == 0) return rc;
+    int64_t G = group_size;
+    resolve_group(K, G);
+    const size_t need = plan_workspace(M, N, K, G, layout).total;
+    if (need > W4A8_STATIC_SCRATCH_BYTES) return W4A8_ERR_WORKSPACE;
+    uint8_t *ws = nullptr;
+    if (need > 0 && (ws = scratch_on_current_device(&rc)) == nullptr) return rc;
+    // Nothing in the workspace has to start at zero: the re-tiled weights, the row-sums and the
+    // partial sums of the K ranges are all written in full before they are read, so what the last
+    // call left there does not matter.
+    return gemm_common(Xq, sx, nullptr, M, Wp, layout, step, zero, nullptr, nullptr, N, K, group_size, Y,
+                       y_dtype, ldy, acc_out, ws, need, stream);
+}
+
 }  // extern "C"
 
 // ---- AQAS scale search and weight clipping (Sec. 3.2, Eq. 1; App. A.4) ---------------------------

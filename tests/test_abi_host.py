@@ -136,6 +136,23 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert gemm(M=200, ws=P, wsb=8) == b.ERR_WORKSPACE
     assert gemm(layout=0) == b.ERR_WORKSPACE         # canonical weights are re-tiled into workspace
     assert gemm(M=0) == b.OK
+    # the entry point on static scratch: the same argument errors, and a clear one beyond its limit
+    def gemm_static(M=4, N=16, K=128, G=0, layout=1, ydt=b.F16, ldy=16, Xq=P):
+        return c.w4a8_gemm_static(Xq, P, M, P, layout, P, P, N, K, G, P, ydt, ldy, Z, Z)
+    limit = c.w4a8_gemm_static_scratch_bytes()
+    assert limit == 64 << 20
+    assert gemm_static(N=24) == b.ERR_SHAPE
+    assert gemm_static(K=256, G=64) == b.ERR_SHAPE
+    assert gemm_static(ldy=8) == b.ERR_SHAPE
+    assert gemm_static(ydt=b.F32) == b.ERR_DTYPE
+    assert gemm_static(layout=3) == b.ERR_DTYPE
+    assert gemm_static(Xq=Z) == b.ERR_NULL
+    assert gemm_static(Xq=ctypes.c_void_p(0x1004)) == b.ERR_SHAPE
+    assert gemm_static(M=0) == b.OK
+    assert lib.gemm_workspace_bytes(16, 16384, 16384, 0, 0) > limit      # canonical weights of 256 Mi codes
+    assert gemm_static(M=16, N=16384, K=16384, ldy=16384, layout=0) == b.ERR_WORKSPACE
+    assert lib.gemm_workspace_bytes(16, 800000, 5248, 128, 1) > limit    # two K ranges of a very tall layer
+    assert gemm_static(M=16, N=800000, K=5248, G=128, ldy=800000) == b.ERR_WORKSPACE
     # asymmetric activations
     assert c.quantize_act_int8_asym(P, b.F16, 4, 128, 128, Z, P, P, Z, Z) == b.ERR_NULL   # zx missing
     assert c.quantize_act_int8_asym(P, b.F16, 4, 128, 64, Z, P, P, P, Z) == b.ERR_SHAPE
