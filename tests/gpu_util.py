@@ -43,3 +43,27 @@ def assert_y_close(y_gpu, y64, out_dtype="f16"):
     bad = err > bound
     assert not bad.any(), (f"{bad.sum()} of {bad.size} outputs off; worst rel "
                            f"{(err / np.maximum(np.abs(y64), floor)).max():.3e}")
+
+
+def decode_table_np(codes, zero, G):
+    """Weights in half steps from the closed form of Eq. 5's second half, in numpy only:
+    2 (code - z) for the integer codes 0..13, +1 for code 14, -1 for code 15."""
+    codes = np.asarray(codes)
+    N, K = codes.shape
+    G = G or K
+    z = np.repeat(np.asarray(zero).reshape(N, K // G).astype(np.int16), G, axis=1)
+    c = codes.astype(np.int16)
+    return np.where(c <= 13, 2 * (c - z), np.where(c == 14, 1, -1)).astype(np.int16)
+
+
+def acc_by_float64_matmul(Xq, d, G):
+    """acc[m, n, g] = sum_{k in g} Xq[m,k] d[n,k] as a float64 library matmul of the integer-valued
+    operands.  Exact: every partial sum is an integer far below 2^53, so the result is the integer
+    product of Eq. 1 whatever order the library adds in.  Returns float64 [M, n, K/G]."""
+    Xq = np.asarray(Xq)
+    M, K = Xq.shape
+    G = G or K
+    ng = K // G
+    X3 = Xq.astype(np.float64).reshape(M, ng, G).transpose(1, 0, 2)            # [ng, M, G]
+    D3 = np.asarray(d).astype(np.float64).reshape(-1, ng, G).transpose(1, 2, 0)  # [ng, G, n]
+    return np.matmul(X3, D3).transpose(1, 2, 0)                                   # [M, n, ng]

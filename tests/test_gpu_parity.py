@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import synthetic_inputs as syn
-from gpu_util import assert_y_close, dev, host, tiled_layout_np
+from gpu_util import acc_by_float64_matmul, assert_y_close, decode_table_np, dev, host, tiled_layout_np
 
 pytestmark = pytest.mark.gpu
 
@@ -194,9 +194,12 @@ PREFILL_CASES = [
     ("m300", 300, 768, 1040, 0),
     ("m300_g256", 300, 768, 512, 256),
     ("m600_multi_block", 600, 1024, 784, 0),
-    # 9 x 30 = 270 tiles of 128 tokens: more workgroups than CUs, i.e. the per-channel instance that
-    # runs two workgroups to a CU, with a ragged last token tile and a 16-channel last column
-    ("m1030_two_per_cu_ragged", 1030, 256, 7440, 0),
+    # 5 x 30 tiles of 256 tokens with a ragged last token tile and a 16-channel last column
+    ("m1030_256_row_tiles_ragged", 1030, 256, 7440, 0),
+    # 16 x 44 = 704 tiles of 128 tokens against 352 of 256 (two rounds of the CUs): the tile-height rule
+    # takes the per-channel instance that runs two workgroups to a CU; ragged last token tile (10 rows)
+    # and a 16-channel last column
+    ("m1930_two_per_cu_ragged", 1930, 256, 11024, 0),
 ]
 
 
@@ -289,13 +292,20 @@ def test_aqas_power_of_two_invariance_on_gpu(lib, oracle):
 
 
 # --------------------------------------------------------------------------- full-size configurations
-def _full_size_case(lib, oracle, name, M=None, n_samples=96, seed=0, N=None):
-    """A BASELINE configuration at its real size, in the launch configuration bench.py times:
-    quantizers compared in full (bit-exact), accumulators and Y on sampled outputs that the plain
-    oracle computes one by one (whole rows and columns would take the triple loop hours)."""
+def _full_size_case(lib, oracle, name, M=None, seed=0, N=None, whole=True, n_samples=4096):
+    """A BASELINE configuration at its real size, in the launch configuration bench.py times.
+
+    Quantizers: compared with the oracle in full, bit for bit.  Accumulators: the WHOLE [M, N, K/G]
+    array against Eq. 1's integer product evaluated on the CPU as a float64 library matmul of the
+    oracle's int8 activations and of its codes decoded by the closed form (exact: all partial sums
+    are integers below 2^53; chunked over N) -- plus outputs that the oracle's own plain loop
+    computes one by one.  Y: the whole matrix against the float64 evaluation of the epilogue on
+    those accumulators.  `whole` = False (the OPT-66B layer, 1.4e12 multiply-accumulates): 32 full
+    output rows, 32 full output columns and `n_samples` single entries instead of everything."""
     X, W, s, G = syn.make_layer(name, M=M, N=N)
     Mq, K = X.shape
     N = W.shape[0]
+    Gs = G or K
     Xd, Wd, sd = dev(X), dev(W), dev(s)
     Xq, sx = lib.quantize_act_int8(Xd, sd)
     codes, step, zero = lib.quantize_weight_dint4(Wd, sd, G)
@@ -311,28 +321,60 @@ def _full_size_case(lib, oracle, name, M=None, n_samples=96, seed=0, N=None):
     Y = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, workspace=ws)     # the timed configuration
     Y2, acc = lib.w4a8_gemm(Xq, sx, Wp, step, zero, N, K, G, workspace=ws, want_acc=True)
     assert torch.equal(Y, Y2)
+    assert int(acc.abs().max()) <= 127 * 26 * Gs
+
+    d = decode_table_np(ref_codes, ref_zero, G)              # [N, K] int16, half steps
+    sx64 = ref_sx.astype(np.float64)
+    hs64 = 0.5 * ref_step.astype(np.float64)                 # [N, ng]
+
+    def check_block(rows, cols):
+        """GPU accumulators and Y of the block rows x cols (index arrays) against the float64 matmul."""
+        a64 = acc_by_float64_matmul(ref_q[rows], d[cols], G)                 # [r, c, ng]
+        rt, ct = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+        a_gpu = host(acc.index_select(0, rt).index_select(1, ct))
+        assert np.array_equal(a_gpu, a64), "int32 accumulators differ from the exact product"
+        y64 = sx64[rows, None] * np.einsum("mng,ng->mn", a64, hs64[cols])
+        y_gpu = host(Y.index_select(0, rt).index_select(1, ct)).astype(np.float64)
+        return y_gpu, y64
+
+    rms_rows = host(Y.float().square().mean(1).sqrt()).astype(np.float64)   # per token, of the GPU's own Y
+    def check_y(y_gpu, y64, row_rms):
+        bound = 1e-3 * np.maximum(np.abs(y64), 1e-3 * row_rms[:, None] + 1e-30)
+        assert np.all(np.abs(y_gpu - y64) <= bound), "Y out of tolerance"
+
     rng = np.random.default_rng(seed)
-    mi = rng.integers(0, Mq, size=n_samples)
-    ni = rng.integers(0, N, size=n_samples)
-    mi[:4] = [0, Mq - 1, 0, Mq - 1]                 # the corners of the output
+    if whole:
+        nc = max(16, min(N, (1 << 27) // max(1, Mq * (K // Gs)) // 16 * 16))   # ~1 GiB of float64 per chunk
+        y_all = np.empty((Mq, N), np.float64)
+        for n0 in range(0, N, nc):
+            cols = np.arange(n0, min(N, n0 + nc))
+            y_gpu, y64 = check_block(np.arange(Mq), cols)
+            y_all[:, cols] = y64
+            check_y(y_gpu, y64, rms_rows)
+        # the row rms used above is the GPU's: it must agree with the reference's
+        assert np.allclose(rms_rows, np.sqrt(np.mean(y_all ** 2, axis=1)), rtol=1e-2)
+    else:
+        rows = np.unique(np.concatenate([[0, Mq - 1], rng.integers(0, Mq, size=30)]))
+        cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, size=30)]))
+        nc = 4096
+        for n0 in range(0, N, nc):                       # full rows, chunked over N
+            cs = np.arange(n0, min(N, n0 + nc))
+            y_gpu, y64 = check_block(rows, cs)
+            check_y(y_gpu, y64, rms_rows[rows])
+        y_gpu, y64 = check_block(np.arange(Mq), cols)    # full columns
+        check_y(y_gpu, y64, rms_rows)
+    # single outputs by the oracle's own plain loop (the corners among them)
+    ns = min(n_samples, 256) if whole else n_samples
+    mi = rng.integers(0, Mq, size=ns)
+    ni = rng.integers(0, N, size=ns)
+    mi[:4] = [0, Mq - 1, 0, Mq - 1]
     ni[:4] = [0, 0, N - 1, N - 1]
     acc_ref = oracle.int_gemm_sampled(ref_q, oracle.pack_dint4(ref_codes), ref_zero, G, mi, ni)
     acc_gpu = acc[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()]
     assert np.array_equal(host(acc_gpu), acc_ref), "sampled int32 accumulators differ"
-    ng = ref_step.shape[1]
-    y64 = ref_sx[mi].astype(np.float64) * np.sum(
-        0.5 * ref_step[ni].astype(np.float64) * acc_ref.astype(np.float64), axis=1)
+    y64 = sx64[mi] * np.sum(hs64[ni] * acc_ref.astype(np.float64), axis=1)
     y_gpu = host(Y[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()]).astype(np.float64)
-    rms = np.sqrt(np.mean(host(Y[mi[0]]).astype(np.float64) ** 2))
-    assert np.all(np.abs(y_gpu - y64) <= 1e-3 * np.maximum(np.abs(y64), 1e-3 * rms))
-    # properties that hold at any size: |acc| <= 127 * 26 * G, and Y reproduces from the returned
-    # accumulators as sx * sum_g (step / 2) acc
-    assert int(acc.abs().max()) <= 127 * 26 * (G if G else K)
-    rows = torch.from_numpy(np.unique(mi[:8])).cuda()
-    y_from_acc = (acc[rows].double() * (0.5 * step.double())[None]).sum(-1) * sx[rows].double()[:, None]
-    err = (Y[rows].double() - y_from_acc).abs()
-    bound = 1e-3 * torch.maximum(y_from_acc.abs(), torch.full_like(y_from_acc, 1e-3 * rms))
-    assert bool((err <= bound).all())
+    assert np.all(np.abs(y_gpu - y64) <= 1e-3 * np.maximum(np.abs(y64), 1e-3 * rms_rows[mi]))
 
 
 def test_full_size_c2_decode_all_m(lib, oracle):
@@ -340,9 +382,14 @@ def test_full_size_c2_decode_all_m(lib, oracle):
         _full_size_case(lib, oracle, "C2", M=M, seed=M)
 
 
-@pytest.mark.parametrize("name,M", [("C3_up", 2048), ("C3_down", 2048), ("C4_5120x13824", 2048),
-                                    ("C4_13824x5120", 16), ("C4_5120x5120", 512),
-                                    ("C4_5120x5120", 128), ("C4_5120x13824", 1)])
+# the whole LLaMA-13B sweep: three layers x five token counts
+@pytest.mark.parametrize("name", ["C4_5120x5120", "C4_5120x13824", "C4_13824x5120"])
+@pytest.mark.parametrize("M", [1, 16, 128, 512, 2048])
+def test_full_size_llama13b_sweep(lib, oracle, name, M):
+    _full_size_case(lib, oracle, name, M=M, seed=M)
+
+
+@pytest.mark.parametrize("name,M", [("C3_up", 2048), ("C3_down", 2048), ("C4_5120x13824", 64)])
 def test_full_size_llama_shapes(lib, oracle, name, M):
     _full_size_case(lib, oracle, name, M=M, seed=M)
 
@@ -357,7 +404,7 @@ def test_64_token_tiles_on_a_layer_too_large_for_token_blocks(lib, oracle):
 
 def test_full_size_c5_opt66b_end_to_end(lib, oracle):
     """OPT-66B-shaped layer: activation quantization and GEMM back to back on one stream."""
-    _full_size_case(lib, oracle, "C5", n_samples=64, seed=5)
+    _full_size_case(lib, oracle, "C5", whole=False, n_samples=4096, seed=5)
 
 
 def test_measurement_aids_run_and_count_their_work(lib):
