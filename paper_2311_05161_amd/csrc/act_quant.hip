@@ -109,7 +109,55 @@ __device__ __forceinline__ int quant1(float t, float inv)
     return (int)q;
 }
 
+// Eight consecutive elements of a row as they come from memory (16 bytes of a 16-bit type, 32 of
+// binary32), and their exact widening.
+template <typename T> struct Raw8 { uint4 v; };
+template <> struct Raw8<float> { float4 a, b; };
+
+template <typename T>
+__device__ __forceinline__ Raw8<T> load_raw8(const T *p)
+{
+    Raw8<T> r;
+    r.v = *reinterpret_cast<const uint4 *>(p);
+    return r;
+}
+template <>
+__device__ __forceinline__ Raw8<float> load_raw8<float>(const float *p)
+{
+    Raw8<float> r;
+    r.a = *reinterpret_cast<const float4 *>(p);
+    r.b = *reinterpret_cast<const float4 *>(p + 4);
+    return r;
+}
+__device__ __forceinline__ void widen8(const Raw8<float> &r, float (&v)[8])
+{
+    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
+    v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+}
+__device__ __forceinline__ void widen8(const Raw8<__half> &r, float (&v)[8])
+{
+    const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __half2float(__ushort_as_half((uint16_t)(w[i] & 0xffffu)));
+        v[2 * i + 1] = __half2float(__ushort_as_half((uint16_t)(w[i] >> 16)));
+    }
+}
+__device__ __forceinline__ void widen8(const Raw8<bf16_t> &r, float (&v)[8])
+{
+    const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
 // Fast path: K % 8 == 0, 16-byte aligned rows, K <= 256 * 8 * NCH.  Rows r0 .. r0+rows_per_block.
+// What bounds this kernel is memory latency, not bandwidth (a row is only 2 K bytes), so the loads
+// of a workgroup's next row are issued before anything is done with the current one (the first row's
+// before the reciprocal scales are computed; a second row of look-ahead measured the same), and the
+// launch keeps about three workgroups on every CU.
 template <typename T, int NCH, bool ASYM>
 __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
     const T *__restrict__ X, int64_t M, int K, int64_t ldx, const float *__restrict__ s,
@@ -118,6 +166,19 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
     __shared__ float red[8];
     const int tid = threadIdx.x;
     const int nchunks = K / AQ_VEC;
+    const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
+    const int nrows = (int)min((int64_t)rows_per_block, M - row0);   // >= 1 by the grid size
+
+    Raw8<T> cur[NCH], nxt[NCH];   // row m (being processed) and row m + 1 (on its way)
+    auto load_row = [&](int64_t m, Raw8<T>(&dst)[NCH]) {
+        const T *x = X + m * ldx;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int ch = tid + c * AQ_THREADS;
+            if (ch < nchunks) dst[c] = load_raw8<T>(x + (int64_t)ch * AQ_VEC);
+        }
+    };
+    load_row(row0, cur);
 
     float r[NCH][AQ_VEC];
 #pragma unroll
@@ -133,11 +194,9 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
         }
     }
 
-    const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
-    for (int rr = 0; rr < rows_per_block; ++rr) {
+    for (int rr = 0; rr < nrows; ++rr) {
         const int64_t m = row0 + rr;
-        if (m >= M) break;  // uniform over the workgroup
-        const T *x = X + m * ldx;
+        if (rr + 1 < nrows) load_row(m + 1, nxt);   // (uniform over the workgroup)
         float t[NCH][AQ_VEC];
         float a = 0.0f, b = 0.0f;   // symmetric: a = max |t|;  asymmetric: a = max(0, t), b = max(0, -t)
 #pragma unroll
@@ -145,7 +204,7 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
             const int ch = tid + c * AQ_THREADS;
             if (ch < nchunks) {
                 float xv[8];
-                load8<T>(x + (int64_t)ch * AQ_VEC, xv);
+                widen8(cur[c], xv);
 #pragma unroll
                 for (int j = 0; j < AQ_VEC; ++j) {
                     t[c][j] = xv[j] * r[c][j];
@@ -191,6 +250,147 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
                 }
                 *reinterpret_cast<uint2 *>(q + (int64_t)ch * AQ_VEC) = make_uint2(w0, w1);
             }
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) cur[c] = nxt[c];
+    }
+}
+
+// Four rounded codes (the low bytes of q0..q3) packed into one word.
+__device__ __forceinline__ uint32_t pack4_low_bytes(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(q1, q0, 0x0c0c0400u);   // [q0.b0, q1.b0, 0, 0]
+    const uint32_t hi = __builtin_amdgcn_perm(q3, q2, 0x04000c0cu);   // [0, 0, q2.b0, q3.b0]
+    return lo | hi;
+}
+
+// Symmetric form, rne and the conversion to an integer in one binary32 addition: y + 1.5 * 2^23 is
+// 1.5 * 2^23 + rne(y) exactly for |y| <= 2^22 (the sum is rounded to nearest even at unit
+// granularity), so the low byte of its bit pattern is rne(y) in two's complement.  The clamp to
+// +-127 of the definition never changes a value: |t| <= a and inv = fl(127 / a) give
+// |fl(t * inv)| <= 127 (1 + 2^-23), which rounds to 127.  (No contraction in this file: the product
+// is rounded before the addition, as in the definition.)
+__device__ __forceinline__ uint32_t quant1_bits(float t, float inv)
+{
+    return __float_as_uint(t * inv + 12582912.0f);
+}
+
+// One wavefront per token row (rows of up to 512 * NCW elements): no workgroup barrier in the row
+// loop at all.  The lane keeps the scaled row t = x * r (binary32) in registers between the maximum and
+// the rounding, and the raw chunks of the wave's next row, whose loads are issued as soon as the
+// current row has been widened; the reciprocal scales 1 / s[k] are computed once per workgroup into
+// LDS (true IEEE division) and read from there; the row maximum is a data-parallel-primitive
+// reduction.  Rows are addressed through buffer descriptors of exactly one row: chunks beyond a
+// ragged row's end load zeros and their stores are dropped by the bounds check (the whole offset
+// is a vector offset: a scalar offset would not be checked), so the chunk code has no branches.
+constexpr int AQW_WAVES = 4;
+template <typename T, int NCW, bool ASYM>
+__global__ __launch_bounds__(AQW_WAVES *WAVE, 2) void act_quant_wave_kernel(
+    const T *__restrict__ X, int64_t M, int K, int64_t ldx, const float *__restrict__ s,
+    int8_t *__restrict__ Xq, float *__restrict__ sx, int32_t *__restrict__ zx, int rows_per_wave)
+{
+    // [2][NCW * 64] float4: elements 0..3 and 4..7 of every chunk's reciprocals, each half contiguous
+    // over the chunks so that a wave's 16-byte reads are conflict free; zero beyond the row's end
+    extern __shared__ __attribute__((aligned(16))) float r_lds[];
+    constexpr int CHUNKS = NCW * WAVE;
+    constexpr int RAW = (int)sizeof(T) * AQ_VEC;   // bytes of a chunk in X
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nchunks = K / AQ_VEC;
+    const int64_t row0 = ((int64_t)blockIdx.x * AQW_WAVES + wave) * rows_per_wave;
+    const int nrows = (int)max((int64_t)0, min((int64_t)rows_per_wave, M - row0));
+
+    Raw8<T> nxt[NCW];
+    auto load_row = [&](int64_t m) {
+        __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)(X + m * ldx), 0, K * (int)sizeof(T), 0x00020000);
+#pragma unroll
+        for (int c = 0; c < NCW; ++c) {
+            if constexpr (sizeof(T) == 2) {
+                const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW, 0, 0);
+                nxt[c].v = make_uint4(v.x, v.y, v.z, v.w);
+            } else {
+                const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW, 0, 0);
+                const v4u v1 = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW + 16, 0, 0);
+                nxt[c].a = make_float4(__uint_as_float(v0.x), __uint_as_float(v0.y), __uint_as_float(v0.z), __uint_as_float(v0.w));
+                nxt[c].b = make_float4(__uint_as_float(v1.x), __uint_as_float(v1.y), __uint_as_float(v1.z), __uint_as_float(v1.w));
+            }
+        }
+    };
+    if (nrows > 0) load_row(row0);
+
+    for (int ch = tid; ch < CHUNKS; ch += AQW_WAVES * WAVE) {
+        float4 r0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), r1 = r0;
+        if (ch < nchunks) {
+            r0 = r1 = make_float4(1.0f, 1.0f, 1.0f, 1.0f);
+            if (s != nullptr) {
+                float sv[8];
+                load8<float>(s + (int64_t)ch * AQ_VEC, sv);
+                r0 = make_float4(1.0f / sv[0], 1.0f / sv[1], 1.0f / sv[2], 1.0f / sv[3]);
+                r1 = make_float4(1.0f / sv[4], 1.0f / sv[5], 1.0f / sv[6], 1.0f / sv[7]);
+            }
+        }
+        reinterpret_cast<float4 *>(r_lds)[ch] = r0;
+        reinterpret_cast<float4 *>(r_lds)[CHUNKS + ch] = r1;
+    }
+    __syncthreads();
+    const float4 *r_lane = reinterpret_cast<const float4 *>(r_lds) + lane;
+
+    for (int rr = 0; rr < nrows; ++rr) {   // (uniform over the wave)
+        const int64_t m = row0 + rr;
+        float t[NCW][AQ_VEC];
+        float a = 0.0f, b = 0.0f;   // symmetric: a = max |t|;  asymmetric: a = max(0, t), b = max(0, -t)
+        // (the reciprocals are fetched one chunk ahead and no further: left to itself the compiler
+        // reads all of them up front, 8 registers per chunk, and spills the row)
+        float4 r0n = r_lane[0], r1n = r_lane[CHUNKS];
+#pragma unroll
+        for (int c = 0; c < NCW; ++c) {
+            float xv[8];
+            widen8(nxt[c], xv);
+            const float4 r0 = r0n, r1 = r1n;
+            if (c + 1 < NCW) {
+                r0n = r_lane[(c + 1) * WAVE];
+                r1n = r_lane[CHUNKS + (c + 1) * WAVE];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            t[c][0] = xv[0] * r0.x; t[c][1] = xv[1] * r0.y; t[c][2] = xv[2] * r0.z; t[c][3] = xv[3] * r0.w;
+            t[c][4] = xv[4] * r1.x; t[c][5] = xv[5] * r1.y; t[c][6] = xv[6] * r1.z; t[c][7] = xv[7] * r1.w;
+#pragma unroll
+            for (int j = 0; j < AQ_VEC; ++j) {
+                if (ASYM) {
+                    a = fmaxf(a, t[c][j]);
+                    b = fmaxf(b, -t[c][j]);
+                } else {
+                    a = fmaxf(a, fabsf(t[c][j]));
+                }
+            }
+        }
+        // the raw registers are free again: the next row's loads go out before the reduction
+        if (rr + 1 < nrows) load_row(m + 1);
+        float inv = 0.0f;
+        AsymParams ap = {1.0f, 0.0f, 0.0f};
+        a = wave_max(a);
+        if (ASYM) {
+            b = wave_max(b);
+            ap = asym_params(-b, a);   // lo = -max(0, -t) = min(0, t)
+            if (lane == 0) {
+                sx[m] = ap.sx;
+                zx[m] = (int)ap.zf - 128;
+            }
+        } else {
+            const bool zero_row = (a == 0.0f);
+            inv = zero_row ? 0.0f : 127.0f / a;
+            if (lane == 0) sx[m] = zero_row ? 1.0f : a / 127.0f;
+        }
+        __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void *)(Xq + m * (int64_t)K), 0, K, 0x00020000);
+#pragma unroll
+        for (int c = 0; c < NCW; ++c) {
+            uint32_t b8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                b8[j] = ASYM ? (uint32_t)quant1_asym(t[c][j], ap.isx, ap.zf) : quant1_bits(t[c][j], inv);
+            const v2u out = {pack4_low_bytes(b8[0], b8[1], b8[2], b8[3]), pack4_low_bytes(b8[4], b8[5], b8[6], b8[7])};
+            __builtin_amdgcn_raw_buffer_store_b64(out, rq, (lane + c * WAVE) * AQ_VEC, 0, 0);
         }
     }
 }
@@ -251,8 +451,31 @@ static int launch_act_quant_t(const T *X, int64_t M, int64_t K, int64_t ldx, con
                            0, st, X, M, K, ldx, s, Xq, sx, zx);
         return hip_status(hipGetLastError());
     }
-    // enough workgroups to fill 256 CUs twice; each amortizes its 1/s divisions over its rows
-    int rows = (int)((M + 511) / 512);
+    // Rows of up to 5120 16-bit (3072 binary32) elements: one wave per row, the scaled row and the next
+    // row's raw chunks in its registers.
+    const int ncw = (int)((K / AQ_VEC + WAVE - 1) / WAVE);
+    if (ncw <= (sizeof(T) == 2 ? 10 : 6)) {
+        // about eight waves per CU, all resident at once; a workgroup's four waves amortize its 1/s
+        // divisions over their rows
+        int rows = (int)((M + 2047) / 2048);
+        if (rows > 8) rows = 8;
+        const unsigned grid = (unsigned)((M + (int64_t)rows * AQW_WAVES - 1) / ((int64_t)rows * AQW_WAVES));
+        size_t lds = 0;   // reciprocal scales of the instance's NCW * 64 chunks, <= 36 KB
+#define W4A8_AQW_CASE(N_)                                                                          \
+    if (ncw <= N_) {                                                                               \
+        lds = (size_t)N_ * WAVE * AQ_VEC * sizeof(float);                                          \
+        hipLaunchKernelGGL((act_quant_wave_kernel<T, N_, ASYM>), dim3(grid), dim3(AQW_WAVES *WAVE), \
+                           lds, st, X, M, (int)K, ldx, s, Xq, sx, zx, rows);                       \
+        return hip_status(hipGetLastError());                                                      \
+    }
+        W4A8_AQW_CASE(2) W4A8_AQW_CASE(4) W4A8_AQW_CASE(6)
+        if constexpr (sizeof(T) == 2) {
+            W4A8_AQW_CASE(8) W4A8_AQW_CASE(10)
+        }
+#undef W4A8_AQW_CASE
+    }
+    // longer rows: a workgroup of 256 lanes per row; about three workgroups per CU, all resident at once
+    int rows = (int)((M + 767) / 768);
     if (rows < 1) rows = 1;
     if (rows > 16) rows = 16;
     const unsigned grid = (unsigned)((M + rows - 1) / rows);

@@ -44,23 +44,54 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
 }
 
 // ---- wave-level reductions ------------------------------------------------------------------
+// All 64 lanes must be active at the call (every caller reduces in wave-uniform control flow).
+// Data-parallel-primitive operands instead of LDS permutes: the other lane's value comes in as a
+// modifier of the max / min / add itself.  Two quad permutes, then the mirror of each half row and
+// of each row of 16 lanes leave every row's result in all of its lanes; the four rows meet
+// through scalar registers.
+constexpr int DPP_QUAD_XOR1 = 0xB1;        // quad_perm [1, 0, 3, 2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;        // quad_perm [2, 3, 0, 1]
+constexpr int DPP_ROW_HALF_MIRROR = 0x141; // lane i <-> 7 - i within 8 lanes
+constexpr int DPP_ROW_MIRROR = 0x140;      // lane i <-> 15 - i within 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(dpp_i32<CTRL>(__float_as_int(v)));
+}
+__device__ __forceinline__ float lane_f32(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
-    return v;
+    v = fmaxf(v, dpp_f32<DPP_QUAD_XOR1>(v));
+    v = fmaxf(v, dpp_f32<DPP_QUAD_XOR2>(v));
+    v = fmaxf(v, dpp_f32<DPP_ROW_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_f32<DPP_ROW_MIRROR>(v));
+    return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 __device__ __forceinline__ float wave_min(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fminf(v, __shfl_xor(v, off, WAVE));
-    return v;
+    v = fminf(v, dpp_f32<DPP_QUAD_XOR1>(v));
+    v = fminf(v, dpp_f32<DPP_QUAD_XOR2>(v));
+    v = fminf(v, dpp_f32<DPP_ROW_HALF_MIRROR>(v));
+    v = fminf(v, dpp_f32<DPP_ROW_MIRROR>(v));
+    return fminf(fminf(lane_f32(v, 0), lane_f32(v, 16)), fminf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 __device__ __forceinline__ int wave_sum_i32(int v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, WAVE);
-    return v;
+    v += dpp_i32<DPP_QUAD_XOR1>(v);
+    v += dpp_i32<DPP_QUAD_XOR2>(v);
+    v += dpp_i32<DPP_ROW_HALF_MIRROR>(v);
+    v += dpp_i32<DPP_ROW_MIRROR>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+           __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
 }
 
 // ---- dINT4 nibble decode for the int8 matrix cores -----------------------------------------
