@@ -140,6 +140,30 @@ int w4a8_gemm(const int8_t *Xq, const float *sx, int64_t M,
               void *Y, int y_dtype, int64_t ldy,
               int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The whole quantized layer of Eq. 1 in one call, from unquantized activations:
+ *     Y = dequant( Q8(X diag(s)^-1) . dINT4(W diag(s))^T )
+ * i.e. quantize_act_int8 followed by w4a8_gemm, with the same results bit for bit (Xq, sx, the
+ * accumulators, Y).  At most 16 tokens of F16 activations (rows 16-byte aligned: X % 16 == 0,
+ * ldx % 8 == 0) on tiled weights whose K the streaming kernel takes in one range (K <= 5120 with
+ * groups, <= 7168 per channel) run as ONE launch: every workgroup of the streaming kernel
+ * quantizes the activations itself while its first weights are on their way, and the int8
+ * activations never touch memory -- the decode step of the method without a second launch.  Every
+ * other case runs the two steps one after the other on `stream`.
+ *   X, x_dtype, M, K, ldx, s      as in quantize_act_int8
+ *   Wp, layout, step, zero, N, group_size, Y, y_dtype, ldy, acc_out      as in w4a8_gemm
+ *   Xq_out  NULL, or int8 [M, K] (16-byte aligned) that receives the quantized activations
+ *   sx_out  NULL, or float [M] that receives the token scales        (both: checks, not needed for Y)
+ *   workspace / workspace_bytes: at least w4a8_linear_workspace_bytes(...) bytes, 256-byte aligned: the int8
+ *               activations, the token scales and w4a8_gemm's own workspace (untouched by the one-launch
+ *               path, which needs none and accepts NULL).
+ * Shape limits and errors as for quantize_act_int8 and w4a8_gemm; M == 0 or N == 0 is a no-op. */
+size_t w4a8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout);
+int w4a8_linear(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const float *s,
+                const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                int64_t N, int64_t group_size, void *Y, int y_dtype, int64_t ldy,
+                int8_t *Xq_out, float *sx_out, int32_t *acc_out,
+                void *workspace, size_t workspace_bytes, void *stream);
+
 /* w4a8_gemm for callers that cannot allocate device memory or carry a workspace around: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
  * kernels, same results and same argument errors as w4a8_gemm; the workspace is a static device

@@ -6,7 +6,7 @@ from ``csrc/`` by ``python -m paper_2311_05161_amd.build``); this package is its
 from .binding import (  # noqa: F401
     BF16, EXPORTS, F16, F32, LAYOUT_CANONICAL, LAYOUT_TILED, LIB_PATH, W4A8Error,
     gemm_workspace_bytes, load_library, pack_dint4, quantize_act_int8, quantize_weight_dint4,
-    status_string, unpack_dint4, w4a8_gemm, w4a8_gemm_static,
+    status_string, unpack_dint4, w4a8_gemm, w4a8_gemm_static, w4a8_linear,
     dint4_weight_sums, quantize_act_int8_asym, w4a8_gemm_asym, w4a8_gemm_batched,
     quantize_value_dint4,
     FMT_DINT3, FMT_DINT4, FMT_INT4, quantize_weight_format, w4a8_gemm_format, pack_dint3, unpack_dint3, pack_format, unpack_format,

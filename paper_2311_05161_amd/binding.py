@@ -23,7 +23,7 @@ _DTYPES = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 EXPORTS = (
     "quantize_act_int8", "quantize_weight_dint4", "pack_dint4", "unpack_dint4",
     "w4a8_gemm_workspace_bytes", "w4a8_gemm", "w4a8_status_string",
-    "w4a8_gemm_static", "w4a8_gemm_static_scratch_bytes",
+    "w4a8_gemm_static", "w4a8_gemm_static_scratch_bytes", "w4a8_linear", "w4a8_linear_workspace_bytes",
     "quantize_act_int8_asym", "dint4_weight_sums", "w4a8_gemm_asym", "w4a8_gemm_batched",
     "quantize_value_dint4",
     "aqas_search_workspace_bytes", "aqas_channel_absmax", "aqas_scale", "aqas_search",
@@ -70,6 +70,11 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.w4a8_gemm.restype = ci
     lib.w4a8_gemm_static.argtypes = [vp, vp, i64, vp, ci, vp, vp, i64, i64, i64, vp, ci, i64, vp, vp]
     lib.w4a8_gemm_static.restype = ci
+    lib.w4a8_linear_workspace_bytes.argtypes = [i64, i64, i64, i64, ci]
+    lib.w4a8_linear_workspace_bytes.restype = sz
+    lib.w4a8_linear.argtypes = [vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, i64, i64, vp, ci, i64, vp, vp, vp,
+                                vp, sz, vp]
+    lib.w4a8_linear.restype = ci
     lib.w4a8_gemm_static_scratch_bytes.argtypes = []
     lib.w4a8_gemm_static_scratch_bytes.restype = sz
     lib.quantize_act_int8_asym.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp, vp]
@@ -227,6 +232,35 @@ def w4a8_gemm(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.
                                     _DTYPES[Y.dtype], ldy, _ptr(acc_out), _ptr(workspace), ws_bytes,
                                     _stream()), "w4a8_gemm")
     return (Y, acc_out) if want_acc else Y
+
+
+def w4a8_linear(X: torch.Tensor, s, Wp: torch.Tensor, step: torch.Tensor, zero: torch.Tensor, N: int,
+                group_size: int = 0, layout: int = LAYOUT_TILED, out_dtype=torch.float16, Y=None,
+                want_quantized=False, want_acc=False, workspace=None):
+    """The whole layer in one call (one launch for up to 16 tokens of fp16 activations).
+    Returns Y, or (Y, Xq, sx[, acc]) with want_quantized / want_acc."""
+    M, K, ldx = _rows(X, "X")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=out_dtype, device=X.device)
+    G = K if group_size in (0, None) else int(group_size)
+    Xq = torch.empty((M, K), dtype=torch.int8, device=X.device) if want_quantized else None
+    sx = torch.empty((M,), dtype=torch.float32, device=X.device) if want_quantized else None
+    acc = torch.empty((M, N, K // G), dtype=torch.int32, device=X.device) if want_acc else None
+    need = int(load_library().w4a8_linear_workspace_bytes(M, N, K, int(group_size or 0), int(layout)))
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ldy = Y.stride(0) if M > 1 else max(Y.stride(0), N)
+    _check(load_library().w4a8_linear(_ptr(X), _DTYPES[X.dtype], M, K, ldx, _ptr(s), _ptr(Wp), int(layout),
+                                      _ptr(step), _ptr(zero), N, int(group_size or 0), _ptr(Y),
+                                      _DTYPES[Y.dtype], ldy, _ptr(Xq), _ptr(sx), _ptr(acc), _ptr(workspace),
+                                      ws_bytes, _stream()), "w4a8_linear")
+    out = (Y,)
+    if want_quantized:
+        out += (Xq, sx)
+    if want_acc:
+        out += (acc,)
+    return out[0] if len(out) == 1 else out
 
 
 def w4a8_gemm_static(Xq: torch.Tensor, sx: torch.Tensor, Wp: torch.Tensor, step: torch.Tensor,

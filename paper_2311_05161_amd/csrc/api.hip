@@ -305,6 +305,90 @@ int w4a8_gemm_batched(const int8_t *Xq, const float *sx, const int32_t *zx, int6
 }
 
 
+// ---- the whole layer in one call -----------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+
+struct LinearWs {
+    size_t xq, sx, gemm, gemm_bytes, total;
+};
+LinearWs plan_linear(int64_t M, int64_t N, int64_t K, int64_t G, int layout)
+{
+    LinearWs w{};
+    size_t off = 0;
+    w.xq = off;
+    off = align_up(off + (size_t)(M * K));
+    w.sx = off;
+    off = align_up(off + (size_t)M * sizeof(float));
+    w.gemm = off;
+    w.gemm_bytes = plan_workspace(M, N, K, G, layout).total;
+    w.total = off + w.gemm_bytes;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t w4a8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t group_size, int layout)
+{
+    int64_t G = group_size;
+    if (!resolve_group(K, G) || !gemm_shape_ok(M, N, K, G) || !valid_layout(layout) || M == 0 || N == 0)
+        return 0;
+    return plan_linear(M, N, K, G, layout).total;
+}
+
+int w4a8_linear(const void *X, int x_dtype, int64_t M, int64_t K, int64_t ldx, const float *s,
+                const uint8_t *Wp, int layout, const float *step, const uint8_t *zero,
+                int64_t N, int64_t group_size, void *Y, int y_dtype, int64_t ldy,
+                int8_t *Xq_out, float *sx_out, int32_t *acc_out,
+                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(x_dtype) || !valid_layout(layout)) return W4A8_ERR_DTYPE;
+    if (y_dtype != W4A8_F16 && y_dtype != W4A8_BF16) return W4A8_ERR_DTYPE;
+    int64_t G = group_size;
+    if (M < 0 || N < 0 || !resolve_group(K, G)) return W4A8_ERR_SHAPE;
+    if (!gemm_shape_ok(M, N, K, G) || ldy < N || ldx < K) return W4A8_ERR_SHAPE;
+    if (M == 0 || N == 0) return W4A8_OK;
+    if (!X || !Wp || !step || !zero || !Y) return W4A8_ERR_NULL;
+    if ((uintptr_t)Wp % 16 != 0 || (uintptr_t)Y % 2 != 0 || (acc_out && (uintptr_t)acc_out % 4 != 0) ||
+        (Xq_out && (uintptr_t)Xq_out % 16 != 0))
+        return W4A8_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+
+    // At most 16 tokens of fp16 activations on tiled weights whose K the streaming kernel takes in one
+    // range: ONE launch, the activations are quantized inside it.
+    const bool one_launch = M <= 16 && x_dtype == W4A8_F16 && layout == W4A8_LAYOUT_TILED &&
+                            (uintptr_t)X % 16 == 0 && ldx % 8 == 0 && ldx <= (1LL << 24) &&
+                            gemv_can_fuse(M, N, K, G);
+    if (one_launch) {
+        if (acc_out) {  // the compute waves add exact partial sums into it
+            const int rc = launch_fill_i32(acc_out, M * N * (K / G), 0, st);
+            if (rc != W4A8_OK) return rc;
+        }
+        const FusedAct fa = {X, ldx, s, Xq_out, sx_out};
+        return launch_gemv(nullptr, nullptr, ZeroPoint{nullptr, nullptr, nullptr}, M, Wp, step, zero, N, K, G,
+                           Y, y_dtype, ldy, acc_out, nullptr, 1, st, 0, &fa);
+    }
+    // Otherwise the two steps one after the other, the int8 activations and token scales in the workspace
+    // (or where the caller wants to see them).
+    const LinearWs w = plan_linear(M, N, K, G, layout);
+    if (!workspace || workspace_bytes < w.total || (uintptr_t)workspace % WS_ALIGN != 0) return W4A8_ERR_WORKSPACE;
+    uint8_t *wsb = (uint8_t *)workspace;
+    int8_t *Xq = Xq_out ? Xq_out : (int8_t *)(wsb + w.xq);
+    float *sx = sx_out ? sx_out : (float *)(wsb + w.sx);
+    // (all of the GEMM's own checks before anything is launched)
+    int rc = gemm_common(Xq, sx, nullptr, M, Wp, layout, step, zero, nullptr, nullptr, N, K, group_size, Y,
+                         y_dtype, ldy, acc_out, w.gemm_bytes ? wsb + w.gemm : nullptr, w.gemm_bytes, stream,
+                         W4A8_FMT_DINT4, true);
+    if (rc != W4A8_OK) return rc;
+    rc = launch_act_quant(X, x_dtype, M, K, ldx, s, Xq, sx, nullptr, st);
+    if (rc != W4A8_OK) return rc;
+    return gemm_common(Xq, sx, nullptr, M, Wp, layout, step, zero, nullptr, nullptr, N, K, group_size, Y,
+                       y_dtype, ldy, acc_out, w.gemm_bytes ? wsb + w.gemm : nullptr, w.gemm_bytes, stream);
+}
+
 // ---- w4a8_gemm for callers that cannot allocate: the workspace is a static device array ----------
 }  // extern "C"
 

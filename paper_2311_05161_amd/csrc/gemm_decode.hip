@@ -43,6 +43,9 @@ constexpr int GV_LDS_BUDGET = 128 * 1024;         // bytes of decode records per
 constexpr int GV_OOB = 0x7fff0000;                // buffer offset beyond any buffer: loads return 0
 constexpr int GV_RED_BYTES = 2 * GV_CW * 256 * 4; // partial sums of the compute waves, double buffered
 constexpr int GV_MAX_LDS = GV_RED_BYTES + GV_LDS_BUDGET;
+constexpr int GV_LDS_LIMIT = 160 * 1024;          // LDS of a CU: what a kernel may opt into
+constexpr int GV_FUSED_STAGE = 8;                 // decode records such an instance's thread prepares at most
+constexpr int GV_FUSED_MAX_AT = 7;                // k-tiles per wave of the instances that quantize the activations themselves
 
 __device__ __forceinline__ void lds_barrier()
 {
@@ -93,6 +96,13 @@ struct GemvArgs {
     int vec_store;         // Y and ldy allow 8-byte stores of four outputs
     int token_blocks;      // blockIdx.z: 16-token blocks of one problem (shared weights) instead of problems
     int part_rows;         // token rows of one K-range's slab of `partial` (all blocks' rows)
+    // FUSED instances: the activations come unquantized and every workgroup quantizes them itself
+    const void *X;         // [M, ldx] fp16
+    const float *s;        // [K] AQAS scale or null
+    int64_t ldx;
+    int fused_lds_off;     // byte offset of the reciprocal scales [K] (then the row maxima [8][16]) in LDS
+    int8_t *Xq_out;        // test hooks (workgroup 0 writes them) or null
+    float *sx_out;
 };
 
 // GROUPED: one (step, zero) per k-tile or coarser group, rescaled per tile.  !GROUPED: per channel.
@@ -102,7 +112,17 @@ struct GemvArgs {
 // the exact term zx * (sum of the weights) is taken out in int32, per tile (GROUPED) or once per
 // output after the waves' int32 sums have been added (!GROUPED) -- never in floating point, where
 // the two large terms would cancel badly.
-template <bool GROUPED, int AT, int D, bool ACC_OUT, bool ASYM>
+// FUSED: the step before the product runs inside the launch (Eq. 1, factor Q(diag(s)^-1 X), per-token
+// absmax INT8): Xq and sx are not read but made here from X and s, by every workgroup for itself --
+// at <= 16 tokens that costs each workgroup about as much as waiting for another launch's result
+// would, and saves the launch.  The weight ring is issued first (it does not depend on X); then the
+// 512 compute lanes put the reciprocals 1 / s[k] into LDS (true divisions), load their own k-tiles'
+// rows of X in the pattern of the int8 fragments (a quad of lanes reads 2 x 128 contiguous bytes of a
+// row), take the row maxima of t = x * r (quad reduction, then the 8 waves' partial maxima meet in
+// LDS) and round t * (127 / a) into the very registers the int8 fragments would have been loaded
+// into.  Every floating-point step is the single binary32 operation of the definition, so Xq and sx
+// have the bits quantize_act_int8 gives.  One K range only (every workgroup sees whole rows).
+template <bool GROUPED, int AT, int D, bool ACC_OUT, bool ASYM, bool FUSED = false>
 __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 {
     // blockIdx.z: independent problems of one shape, densely stacked (batched launch), or the
@@ -161,8 +181,9 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     // later.  Quotients by multiplication with an approximate reciprocal: exact here, since
     // (e + 0.5) / d is at least 1 / (2 d) away from any integer and e < 2^13, d <= 64, against
     // a relative error below 2^-21.
-    int st_z[GV_STAGE], st_t[GV_STAGE];
-    float st_s[GV_STAGE];
+    constexpr int STAGES = FUSED ? GV_FUSED_STAGE : GV_STAGE;
+    int st_z[STAGES], st_t[STAGES];
+    float st_s[STAGES];
     const int n_rec = my_nt * 16 * recs_per_nt;
     const float inv_recs = __builtin_amdgcn_rcpf((float)recs_per_nt);
     auto issue_params = [&]() {
@@ -172,7 +193,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             __builtin_amdgcn_make_buffer_rsrc((void *)a.zero, 0, N * a.ng, 0x00020000);
         const float inv_tpg = __builtin_amdgcn_rcpf((float)a.tiles_per_group);
 #pragma unroll
-        for (int i = 0; i < GV_STAGE; ++i) {
+        for (int i = 0; i < STAGES; ++i) {
             // (a stage that is skipped leaves its registers unset: write_records skips it too)
             if (i * GV_REC_THREADS >= n_rec) break;   // (uniform; one taken branch ends the stages)
             {
@@ -190,7 +211,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     };
     auto write_records = [&]() {
 #pragma unroll
-        for (int i = 0; i < GV_STAGE; ++i) {
+        for (int i = 0; i < STAGES; ++i) {
             if (i * GV_REC_THREADS >= n_rec) break;   // (uniform; one taken branch ends the stages)
             {
                 const int e = (int)threadIdx.x + i * GV_REC_THREADS;
@@ -207,7 +228,46 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         }
     };
 
+    // ---- FUSED: the unquantized activations of this wave's k-tiles and the AQAS scales, requested
+    // before anything else: they are needed first (the row maxima), the parameters next, the weights last.
+    // Raw rows: lane (row = lane / 4, q = lane % 4) holds columns 16 q .. + 15 and 64 + 16 q .. + 15 of
+    // each of its k-tiles as four 16-byte pieces -- the columns its int8 fragments a0 / a1 cover.
+    constexpr int NS = GV_FUSED_MAX_AT * 2;   // scales per thread: K <= 8 * 128 * GV_FUSED_MAX_AT, 512 threads
+    v4u xr[FUSED ? AT : 1][4];
+    float sv[FUSED ? NS : 1];
+    float *r_lds = reinterpret_cast<float *>(smem + (FUSED ? a.fused_lds_off : 0));   // [K], then maxima [8][16]
+    const int xcol = (lane & 3) * 16;   // first column of the lane's first half within a k-tile
+    if (FUSED && wave < GV_CW) {
+        const int tpw_x = (KTs - wave + GV_CW - 1) / GV_CW;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int k = (int)threadIdx.x + i * GV_REC_THREADS;
+            sv[i] = (a.s != nullptr && k < K) ? a.s[k] : 1.0f;
+        }
+        __amdgpu_buffer_rsrc_t rxx = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)a.X, 0, (int)((((int64_t)M - 1) * a.ldx + K) * 2), 0x00020000);
+        const int voff_raw = ((lane >> 2) * (int)a.ldx + xcol) * 2;
+#pragma unroll
+        for (int u = 0; u < AT; ++u) {
+            const int vo = u < tpw_x ? voff_raw + (wave + u * GV_CW) * (TILE_K * 2) : GV_OOB;
+            xr[u][0] = __builtin_amdgcn_raw_buffer_load_b128(rxx, vo, 0, 0);
+            xr[u][1] = __builtin_amdgcn_raw_buffer_load_b128(rxx, vo + 16, 0, 0);
+            xr[u][2] = __builtin_amdgcn_raw_buffer_load_b128(rxx, vo + 128, 0, 0);
+            xr[u][3] = __builtin_amdgcn_raw_buffer_load_b128(rxx, vo + 144, 0, 0);
+        }
+        order_fence();
+    }
     if (wave < GV_CW) issue_params();
+    if (FUSED && wave < GV_CW) {
+        // the reciprocals (true divisions) go to LDS as soon as the scales are there (the first loads issued)
+        order_fence();
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int k = (int)threadIdx.x + i * GV_REC_THREADS;
+            if (k < K) r_lds[k] = 1.0f / sv[i];
+        }
+        order_fence();
+    }
 
     if (wave == GV_CW) {
         // ================= helper wave: reduction across the compute waves + output ============
@@ -217,7 +277,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         // their int32 accumulators; the sum is exact, then zero-point term, step / 8, token scale.
         const int hm = lane >> 2, hc = (lane & 3) * 4;
         const bool final_out = a.partial == nullptr;
-        const float sxm = (final_out && hm < M) ? a.sx[hm] : 0.f;
+        float sxm = (!FUSED && final_out && hm < M) ? a.sx[hm] : 0.f;
         const bool zp = ASYM && !GROUPED && final_out;
         const int zxm = (zp && hm < M) ? a.zx[hm] : 0;
         const v4i zero4i = {0, 0, 0, 0};
@@ -229,6 +289,15 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         v4i wn = zp ? load_wn(0) : zero4i;
         lds_barrier();   // every wave's parameter loads are under way
         lds_barrier();   // the records are complete
+        if (FUSED) {
+            lds_barrier();   // the compute waves have published their row maxima
+            const float *mx = reinterpret_cast<const float *>(smem + a.fused_lds_off) + K;
+            float am = 0.f;
+#pragma unroll
+            for (int w = 0; w < GV_CW; ++w) am = fmaxf(am, mx[w * 16 + hm]);
+            sxm = am == 0.f ? 1.0f : am / 127.0f;
+            if (a.sx_out != nullptr && blk == 0 && (lane & 3) == 0 && hm < M) a.sx_out[hm] = sxm;
+        }
         for (int j = 0; j < my_nt; ++j) {
             lds_barrier();  // the compute waves have published their partial sums of n-tile j
             const v4i wn_next = (zp && j + 1 < my_nt) ? load_wn(j + 1) : zero4i;
@@ -317,18 +386,109 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 #pragma unroll
     for (int u = 0; u < AT; ++u) {
         // slots without a k-tile hold zero activations, so whatever is computed there adds nothing
-        const int vo = u < tpw ? voff_x + (wave + u * GV_CW) * TILE_K : GV_OOB;
-        a0[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, 0, 0);
-        a1[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo + 64, 0, 0);
+        if (!FUSED) {
+            const int vo = u < tpw ? voff_x + (wave + u * GV_CW) * TILE_K : GV_OOB;
+            a0[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, 0, 0);
+            a1[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo + 64, 0, 0);
+        }
         p[0][u] = load_w(0, u);
     }
+    if (!FUSED) {
 #pragma unroll
-    for (int d = 1; d < DR; ++d)
+        for (int d = 1; d < DR; ++d)
 #pragma unroll
-        for (int u = 0; u < AT; ++u) p[d][u] = load_w(d, u);
+            for (int u = 0; u < AT; ++u) p[d][u] = load_w(d, u);
+    }
     order_fence();
     write_records();
-    lds_barrier();   // the records are complete
+
+    // FUSED: the deeper ring rows are requested only now, into the registers the parameter staging held
+    if (FUSED) {
+        order_fence();
+#pragma unroll
+        for (int d = 1; d < DR; ++d)
+#pragma unroll
+            for (int u = 0; u < AT; ++u) p[d][u] = load_w(d, u);
+        order_fence();
+    }
+    lds_barrier();   // the records (and the reciprocal scales) are complete
+
+    // eight elements of one 16-byte piece, widened exactly and scaled: t = x * (1 / s)
+    auto scaled8 = [&](const v4u &raw, const float *rk, float (&t)[8]) __attribute__((always_inline)) {
+        const v4f r0 = *reinterpret_cast<const v4f *>(rk);
+        const v4f r1 = *reinterpret_cast<const v4f *>(rk + 4);
+        const uint32_t wd[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float lo, hi;
+            // (fp16 only: with a run-time choice between two widenings inside this loop the compiler
+            // keeps both variants' operands alive and every instance beyond one k-tile per wave spills)
+            lo = __half2float(__ushort_as_half((uint16_t)(wd[i] & 0xffffu)));
+            hi = __half2float(__ushort_as_half((uint16_t)(wd[i] >> 16)));
+            const float ra = i < 2 ? r0[2 * i] : r1[2 * i - 4];
+            const float rb = i < 2 ? r0[2 * i + 1] : r1[2 * i - 3];
+            t[2 * i] = __fmul_rn(lo, ra);
+            t[2 * i + 1] = __fmul_rn(hi, rb);
+        }
+    };
+    float q_inv = 0.f;   // 127 / (row maximum), 0 for an all-zero row
+    // slot u: raw pieces -> int8 fragments.  rne and the conversion are one addition: y + 1.5 * 2^23
+    // holds rne(y) in its low bits (|y| <= 127 (1 + 2^-23): the clamp of the definition never acts).
+    auto quantize_slot = [&](int u) __attribute__((always_inline)) {
+        const float *rk = r_lds + (wave + u * GV_CW) * TILE_K + xcol;
+        uint32_t o[8];
+#pragma unroll
+        for (int pc = 0; pc < 4; ++pc) {
+            float t[8];
+            // (slots without a k-tile hold zeros; their reciprocals are read from the last k-tile's place)
+            scaled8(xr[u][pc], (u < tpw ? rk : r_lds) + (pc >> 1) * 64 + (pc & 1) * 8, t);
+            uint32_t b[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(__fadd_rn(__fmul_rn(t[i], q_inv), 12582912.0f));
+            o[2 * pc] = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u) | __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
+            o[2 * pc + 1] = __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u) | __builtin_amdgcn_perm(b[7], b[6], 0x04000c0cu);
+            __builtin_amdgcn_sched_barrier(0);   // (piece by piece, as above)
+        }
+        a0[u] = v4u{o[0], o[1], o[2], o[3]};
+        a1[u] = v4u{o[4], o[5], o[6], o[7]};
+        if (a.Xq_out != nullptr && blk == 0 && u < tpw && (lane >> 2) < M) {   // test hook
+            int8_t *qo = a.Xq_out + (int64_t)(lane >> 2) * K + (wave + u * GV_CW) * TILE_K + xcol;
+            *reinterpret_cast<v4u *>(qo) = a0[u];
+            *reinterpret_cast<v4u *>(qo + 64) = a1[u];
+        }
+    };
+    if (FUSED) {
+        float am = 0.f;
+#pragma unroll
+        for (int u = 0; u < AT; ++u) {
+            const float *rk = r_lds + (wave + u * GV_CW) * TILE_K + xcol;
+#pragma unroll
+            for (int pc = 0; pc < 4; ++pc) {
+                float t[8];
+                scaled8(xr[u][pc], (u < tpw ? rk : r_lds) + (pc >> 1) * 64 + (pc & 1) * 8, t);
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) am = fmaxf(fmaxf(am, fabsf(t[i])), fabsf(t[i + 1]));
+                // (piece by piece: scheduled freely, all reciprocals are read and all pieces widened
+                // up front -- some 80 registers per slot -- and the wave spills)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // (the rounding pass widens the raw pieces again: kept widened from here they would be 32
+        // registers per slot)
+#pragma unroll
+        for (int u = 0; u < AT; ++u)
+            asm volatile("" : "+v"(xr[u][0]), "+v"(xr[u][1]), "+v"(xr[u][2]), "+v"(xr[u][3]));
+        // the row's four lanes, then the eight waves through LDS
+        am = fmaxf(am, dpp_f32<DPP_QUAD_XOR1>(am));
+        am = fmaxf(am, dpp_f32<DPP_QUAD_XOR2>(am));
+        float *mx = r_lds + K;
+        if ((lane & 3) == 0) mx[wave * 16 + (lane >> 2)] = am;
+        lds_barrier();   // the row maxima are complete
+        float arow = 0.f;
+#pragma unroll
+        for (int w = 0; w < GV_CW; ++w) arow = fmaxf(arow, mx[w * 16 + (lane >> 2)]);
+        q_inv = arow == 0.f ? 0.f : 127.0f / arow;
+    }
 
     // fragments -> operand layout: lane (ln, kb) takes bytes kb*32 .. +32 of row ln, i.e. the
     // 16-byte pieces 2 (kb % 2) and 2 (kb % 2) + 1 that lanes 4 ln + .. loaded, from the first
@@ -355,7 +515,10 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
 
     if (D != 0) {
 #pragma unroll
-        for (int u = 0; u < AT; ++u) to_operand_layout(u);
+        for (int u = 0; u < AT; ++u) {
+            if (FUSED) quantize_slot(u);
+            to_operand_layout(u);
+        }
     }
 
     const v4i zero4 = {0, 0, 0, 0};
@@ -371,7 +534,10 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     auto step_ntile = [&](int j, int d, bool refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < AT; ++u) {
-            if (D == 0) to_operand_layout(u);
+            if (D == 0) {
+                if (FUSED) quantize_slot(u);
+                to_operand_layout(u);
+            }
             // the record of the next slot is fetched one slot ahead
             v4u rn = r;
             if (u + 1 < AT) {
@@ -543,20 +709,22 @@ GemvPlan plan_gemv(int64_t M, int64_t N, int64_t K, int64_t G, int64_t batch)
     return pl;
 }
 
-template <bool GROUPED, bool ACC_OUT, bool ASYM>
+template <bool GROUPED, bool ACC_OUT, bool ASYM, bool FUSED = false>
 static int launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hipStream_t st)
 {
     const dim3 grid((unsigned)pl.blocks_per_split, (unsigned)pl.splits, (unsigned)batch);
+    // FUSED: the reciprocal scales [K] and the waves' row maxima [8][16] follow the decode records
+    const int lds_bytes = pl.lds_bytes + (FUSED ? ga.K * 4 + GV_CW * 16 * 4 : 0);
     // more than 64 KB of dynamic LDS has to be opted into, once per instance and device
 #define W4A8_GV_LAUNCH(AT_, D_)                                                                  \
     do {                                                                                         \
         static std::atomic<uint64_t> lds_opted{0};                                               \
-        if (pl.lds_bytes > 64 * 1024 &&                                                          \
-            opt_in_dynamic_lds((const void *)gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>,       \
-                               GV_MAX_LDS, lds_opted) != W4A8_OK)                                \
+        if (lds_bytes > 64 * 1024 &&                                                             \
+            opt_in_dynamic_lds((const void *)gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM, FUSED>, \
+                               GV_LDS_LIMIT, lds_opted) != W4A8_OK)                              \
             return W4A8_ERR_HIP;                                                                 \
-        hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM>), grid,                 \
-                           dim3(GV_THREADS), pl.lds_bytes, st, ga);                              \
+        hipLaunchKernelGGL((gemv_kernel<GROUPED, AT_, D_, ACC_OUT, ASYM, FUSED>), grid,          \
+                           dim3(GV_THREADS), lds_bytes, st, ga);                                 \
     } while (0)
     // ring depth: 8 - 10 KB per wave in flight, within the register budget of 9 waves per CU;
     // no ring when every workgroup has a single n-tile (the accumulator hook keeps the ring form)
@@ -577,9 +745,17 @@ static int launch_gemv_at(const GemvPlan &pl, const GemvArgs &ga, int batch, hip
                 switch (pl.at) {
                     W4A8_GV_CASE(6, 1);
                     W4A8_GV_CASE(7, 1);
-                    W4A8_GV_CASE(8, 1);
-                    W4A8_GV_CASE(9, 1);
-                    default: return W4A8_ERR_SHAPE;
+                    default:
+                        if constexpr (!FUSED) {
+                            switch (pl.at) {
+                                W4A8_GV_CASE(8, 1);
+                                W4A8_GV_CASE(9, 1);
+                                default: return W4A8_ERR_SHAPE;
+                            }
+                        } else {
+                            return W4A8_ERR_SHAPE;
+                        }
+                        break;
                 }
             } else {
                 return W4A8_ERR_SHAPE;
@@ -606,11 +782,22 @@ int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G)
     return nb;
 }
 
+bool gemv_can_fuse(int64_t M, int64_t N, int64_t K, int64_t G)
+{
+    if (M < 1 || M > 16 || N < TILE_N || K < TILE_K) return false;
+    const GemvPlan pl = plan_gemv(M, N, K, G, 1);
+    // (8 and 9 k-tiles per wave would spill: 16 registers of raw activations per k-tile)
+    const int recs = (G != K) ? pl.kt_per_split : 1;   // decode records per channel
+    return pl.splits == 1 && pl.at <= GV_FUSED_MAX_AT && pl.q * 16 * recs <= GV_FUSED_STAGE * GV_REC_THREADS &&
+           pl.lds_bytes + (int)K * 4 + GV_CW * 16 * 4 <= GV_LDS_LIMIT;
+}
+
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
                 int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
-                hipStream_t st, int plain)
+                hipStream_t st, int plain, const FusedAct *fused)
 {
+    if (fused != nullptr && (batch != 1 || zp.zx != nullptr || !gemv_can_fuse(M, N, K, G))) return W4A8_ERR_SHAPE;
     // 16 < M <= 128 where gemv_token_blocks says so: one launch over the 16-token blocks (batch must be 1)
     const int token_blocks = M > 16 ? gemv_token_blocks(M, N, K, G) : 0;
     if (M > 16 && (token_blocks == 0 || batch != 1)) return W4A8_ERR_SHAPE;
@@ -631,8 +818,22 @@ int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, cons
     ga.part_rows = (int)M;
     ga.plain = plain;
     ga.vec_store = ((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0);
+    ga.X = nullptr; ga.s = nullptr; ga.ldx = 0; ga.Xq_out = nullptr; ga.sx_out = nullptr;
+    ga.fused_lds_off = pl.lds_bytes;
     const bool asym = zp.zx != nullptr;
     int rc;
+    if (fused != nullptr) {
+        ga.X = fused->X; ga.s = fused->s; ga.ldx = fused->ldx;
+        ga.Xq_out = fused->Xq_out; ga.sx_out = fused->sx_out;
+        if (grouped) {
+            if (acc_out) rc = launch_gemv_at<true, true, false, true>(pl, ga, 1, st);
+            else rc = launch_gemv_at<true, false, false, true>(pl, ga, 1, st);
+        } else {
+            if (acc_out) rc = launch_gemv_at<false, true, false, true>(pl, ga, 1, st);
+            else rc = launch_gemv_at<false, false, false, true>(pl, ga, 1, st);
+        }
+        return rc;
+    }
     if (grouped) {
         // the per-tile zero-point term only exists in its own instances (asymmetric, grouped)
         if (asym) {

@@ -260,10 +260,24 @@ struct ZeroPoint {
 // 16 < M <= 128: the number of 16-token blocks that launch_gemv runs as one launch over shared weights
 // where that is faster than the tile kernel (K within one K-range, few blocks or a small layer); else 0
 int gemv_token_blocks(int64_t M, int64_t N, int64_t K, int64_t G);
+// Unquantized activations for the streaming kernel's instances that quantize them in the launch
+// (M <= 16, one K range of at most 7168 columns, symmetric form): X fp16 rows ldx elements apart
+// (16-byte aligned), s the AQAS scale or null; Xq_out / sx_out: null, or where workgroup 0 leaves what
+// it made (test hooks).
+struct FusedAct {
+    const void *X;
+    int64_t ldx;
+    const float *s;
+    int8_t *Xq_out;
+    float *sx_out;
+};
+// whether a shape can take those instances (they need K in one range and room in LDS for 1 / s)
+bool gemv_can_fuse(int64_t M, int64_t N, int64_t K, int64_t G);
+// fused != null: Xq and sx are ignored
 int launch_gemv(const int8_t *Xq, const float *sx, ZeroPoint zp, int64_t M, const uint8_t *Wt,
                 const float *step, const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y,
                 int y_dtype, int64_t ldy, int32_t *acc_out, float *partial, int64_t batch,
-                hipStream_t st, int plain = 0);
+                hipStream_t st, int plain = 0, const FusedAct *fused = nullptr);
 // Y = cast(sx * sum over splits of partial).  int_step != null: the partials are int32
 // accumulators of a per-channel launch, scaled by int_step[n] / 8 after the exact zero-point term.
 int launch_gemv_combine(const float *partial, const float *sx, const float *int_step, ZeroPoint zp,

@@ -280,6 +280,24 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert c.w4a8_measure_mfma_i8((1 << 24) + 1, Z, Z, Z) == b.ERR_SHAPE
 
 
+def test_linear_argument_errors_before_any_launch(lib):
+    """w4a8_linear: every call here is rejected (or is a no-op) on the host; nothing is launched."""
+    import ctypes
+    L = lib.load_library()
+    P, Z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    F16 = lib.F16
+    def call(X=P, dt=F16, M=4, K=128, ldx=128, N=16, G=0, layout=1, Y=P, ydt=F16, ldy=16, ws=Z, wsb=0, Xq=Z):
+        return L.w4a8_linear(X, dt, M, K, ldx, Z, P, layout, P, P, N, G, Y, ydt, ldy, Xq, Z, Z, ws, wsb, Z)
+    assert call(M=0) == 0
+    assert call(dt=7) == 3 and call(ydt=lib.F32) == 3 and call(layout=5) == 3
+    assert call(N=24) == 2 and call(K=192) == 2 and call(ldx=64) == 2 and call(ldy=8) == 2
+    assert call(X=Z) == 1 and call(Y=Z) == 1
+    assert call(Xq=ctypes.c_void_p(0x1004)) == 2
+    assert call(M=40) == 4                       # two steps: workspace needed
+    assert call(dt=lib.BF16) == 4
+    assert call(M=40, ws=ctypes.c_void_p(0x10000), wsb=100) == 4
+
+
 def test_product_path_has_no_cpu_fallback(lib, tmp_path):
     with pytest.raises(FileNotFoundError):
         lib.load_library(str(tmp_path / "missing_libw4a8.so"))

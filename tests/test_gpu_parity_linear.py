@@ -1,0 +1,138 @@
+"""w4a8_linear -- the whole layer in one call, one launch for up to 16 tokens -- against the CPU oracle
+and against the two-call path (quantize_act_int8 + w4a8_gemm), through the C ABI.
+
+The one-launch instances quantize the activations inside the streaming kernel; what they make (Xq, sx,
+through the entry point's check outputs), the int32 accumulators and Y must be what the two kernels
+give: bit for bit, Y included (the same reduction order from the same operands).
+"""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as syn
+from gpu_util import assert_y_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2311_05161_amd as w
+    w.load_library()  # raises if the HIP library has not been built: no fallback
+    assert torch.cuda.is_available()
+    return w
+
+
+def _case(lib, oracle, seed, M, K, N, G, x_dtype="f16", use_s=True, pad=0, layout=1, zero_row=True):
+    X, W, s = syn.random_layer(seed, M, K, N, x_dtype="f32" if x_dtype == "f32" else "f16")
+    if zero_row and M > 2:
+        X[1] = 0          # an all-zero token
+    if x_dtype == "bf16":
+        Xt = torch.from_numpy(X.astype(np.float32)).to(torch.bfloat16)
+        Xh = Xt.float().numpy()
+    else:
+        Xt = torch.from_numpy(X)
+        Xh = X
+    buf = torch.zeros((M, K + pad), dtype=Xt.dtype, device="cuda")
+    buf[:, :K] = Xt.cuda()
+    Xd = buf[:, :K]
+    sd = dev(s) if use_s else None
+    r = oracle.linear_w4a8(Xh.astype(np.float32), W, s if use_s else None, G)
+    codes, step, zero = lib.quantize_weight_dint4(dev(W), sd, G)
+    assert np.array_equal(host(codes), r["codes"])
+    Wp = lib.pack_dint4(codes, layout)
+    Y, Xq, sx, acc = lib.w4a8_linear(Xd, sd, Wp, step, zero, N, G, layout=layout, want_quantized=True,
+                                     want_acc=True)
+    assert np.array_equal(host(sx).view(np.uint32), r["sx"].view(np.uint32)), "token scales differ"
+    assert np.array_equal(host(Xq), r["Xq"]), "int8 activations differ"
+    assert np.array_equal(host(acc), r["acc"]), "int32 accumulators differ"
+    assert_y_close(host(Y), r["Y64"])
+    # the production form (no check outputs, no hook) and the two-call path: the same Y, bit for bit
+    Y1 = lib.w4a8_linear(Xd, sd, Wp, step, zero, N, G, layout=layout)
+    Xq2, sx2 = lib.quantize_act_int8(Xd, sd)
+    Y2 = lib.w4a8_gemm(Xq2, sx2, Wp, step, zero, N, K, G, layout=layout)
+    assert torch.equal(Y1, Y) and torch.equal(Y2, Y)
+    return r
+
+
+ONE_LAUNCH = [
+    # name, M, K, N, G -- all fp16, tiled weights, K in one range of the streaming kernel
+    ("c2_m16", 16, 4096, 4096, 128),
+    ("c2_m1", 1, 4096, 4096, 128),
+    ("c2_m5", 5, 4096, 4096, 128),
+    ("one_tile", 3, 128, 16, 128),
+    ("ring_one_ktile_per_wave", 16, 512, 9232, 128),
+    ("ring_five_ktiles_per_wave", 16, 5120, 5136, 128),
+    ("group256_ragged", 7, 1280, 400, 256),
+    ("per_channel_k_tail", 16, 1152, 272, 0),
+    ("per_channel_three_ktiles_ring", 9, 3072, 8208, 0),
+    ("per_channel_seven_ktiles_ragged", 16, 6784, 48, 0),
+    ("per_channel_seven_ktiles_ring", 2, 7168, 4640, 0),
+    ("c1_shape_fp16", 16, 768, 768, 0),
+]
+
+
+@pytest.mark.parametrize("case", ONE_LAUNCH, ids=[c[0] for c in ONE_LAUNCH])
+def test_linear_one_launch(lib, oracle, case):
+    name, M, K, N, G = case
+    assert lib.load_library().w4a8_linear_workspace_bytes(M, N, K, G, 1) >= M * K + 4 * M
+    _case(lib, oracle, 40 + len(name), M, K, N, G)
+
+
+def test_linear_one_launch_variants(lib, oracle):
+    _case(lib, oracle, 1, 16, 1024, 272, 128, use_s=False)           # s = NULL
+    _case(lib, oracle, 2, 11, 1024, 272, 0, pad=8)                   # rows 16-byte aligned in a wider buffer
+    _case(lib, oracle, 3, 2, 512, 64, 128, zero_row=False)
+
+
+TWO_STEP = [
+    # name, M, K, N, G, x_dtype, pad, layout -- what the one-launch instances do not take
+    ("bf16_activations", 16, 1024, 272, 128, "bf16", 0, 1),
+    ("fp32_activations_c1", 16, 768, 768, 0, "f32", 0, 1),
+    ("nine_ktiles_per_wave", 9, 9216, 272, 0, "f16", 0, 1),
+    ("k_in_two_ranges", 16, 9216, 48, 128, "f16", 0, 1),
+    ("unaligned_rows", 5, 512, 64, 128, "f16", 3, 1),
+    ("canonical_layout", 9, 256, 32, 128, "f16", 0, 0),
+    ("token_blocks_m40", 40, 512, 256, 128, "f16", 0, 1),
+    ("tile_kernel_m300", 300, 768, 1040, 0, "f16", 0, 1),
+    ("tile_kernel_k_ranges", 130, 1024, 304, 128, "f16", 0, 1),
+]
+
+
+@pytest.mark.parametrize("case", TWO_STEP, ids=[c[0] for c in TWO_STEP])
+def test_linear_two_steps(lib, oracle, case):
+    name, M, K, N, G, x_dtype, pad, layout = case
+    _case(lib, oracle, 60 + len(name), M, K, N, G, x_dtype=x_dtype, pad=pad, layout=layout)
+
+
+def test_linear_full_size_c4_up_projection(lib, oracle):
+    """The decode object of bench.py at its real size: LLaMA-13B up-projection, 16 tokens, one launch."""
+    X, W, s, G = syn.make_layer("C4_5120x13824", M=16)
+    K, N = X.shape[1], W.shape[0]
+    r = oracle.linear_w4a8(X, W, s, G)
+    codes, step, zero = lib.quantize_weight_dint4(dev(W), dev(s), G)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    Y, Xq, sx, acc = lib.w4a8_linear(dev(X), dev(s), Wp, step, zero, N, G, want_quantized=True, want_acc=True)
+    assert np.array_equal(host(Xq), r["Xq"]) and np.array_equal(host(sx), r["sx"])
+    assert np.array_equal(host(acc), r["acc"])
+    assert_y_close(host(Y), r["Y64"])
+    assert torch.equal(lib.w4a8_linear(dev(X), dev(s), Wp, step, zero, N, G), Y)
+
+
+def test_linear_exact_output_of_the_plain_one_launch_instances(lib, oracle):
+    """Bit-exact Y without any hook (see test_gpu_parity_exact.py for the construction): the activations
+    are small integers whose row maximum is exactly 127, so the quantizer reproduces them (scale 1)."""
+    from test_gpu_parity_exact import _exact_operands
+    for (M, K, N, G) in ((16, 4096, 4096, 128), (16, 5120, 5136, 128), (9, 3072, 8208, 0), (7, 6656, 48, 0)):
+        Xq, _, codes, zero, step = _exact_operands(300 + M + N, M, K, N, G)
+        Xq[:, 0], Xq[:, K // 2] = 127, -127       # a mirrored pair: it cancels like every other column
+        sx = np.ones(M, np.float32)
+        acc = oracle.int_gemm(Xq, oracle.pack_dint4(codes), zero, G)
+        y32, y64 = oracle.dequant_epilogue(acc, sx, step)
+        assert np.array_equal(y32.astype(np.float64), y64) and np.array_equal(y32.astype(np.float16), y32)
+        ref_q, ref_sx = oracle.quantize_act_int8(Xq.astype(np.float32), None)
+        assert np.array_equal(ref_q, Xq) and np.array_equal(ref_sx, sx)      # premise: the quantizer is the identity here
+        Wp = lib.pack_dint4(dev(codes), lib.LAYOUT_TILED)
+        Y = lib.w4a8_linear(dev(Xq.astype(np.float16)), None, Wp, dev(step), dev(zero), N, G)
+        got = host(Y).astype(np.float32)
+        assert np.array_equal(got, y32), f"{(got != y32).sum()} outputs differ from the exact result"
