@@ -36,10 +36,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
-# HBM bytes per launch of the two roofline kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (--pmc-calibration scales the counters by a 256 MiB copy); see profiles/*_hbm_traffic.md.
-# None until measured on the kernels as they are now.
-TRAFFIC_BYTES = {"gemm_kernel_C5": None, "gemv_kernel_C4": None}
+# HBM-side bytes per launch of the two roofline kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script on the kernels as they are (--pmc-calibration scales the counters by 256 MiB copies):
+# profiles/gemm_kernel_C5_and_gemv_kernel_C4_hbm_traffic.md.  C5 tile kernel: 1,360,788,070 read (re-reads of
+# the activations per group of channel tiles, served by the last-level cache) + 301,989,888 written.
+TRAFFIC_BYTES = {"gemm_kernel_C5": 1662777958, "gemv_kernel_C4": 39475200}
 
 
 def decode_bytes(M, N, K, G):
@@ -154,6 +155,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": "gemm_kernel<256, 2, 4, per-channel> (w4a8_gemm, M > 16)",
                 "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": TRAFFIC_BYTES["gemm_kernel_C5"],
+                "algorithmic_bytes": M * K + N * K // 2 + 5 * N + 4 * M + 2 * M * N,
                 "ops_per_launch": ops, "avg_launch_us": round(gemm_avg_ms * 1e3, 2),
                 "median_launch_us": round(float(np.median(gemm_ms)) * 1e3, 2),
                 "launches_timed": len(gemm_ms),
