@@ -544,16 +544,17 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     // activation ring as [token][256 channels] fp16 -- 16-byte columns XOR-swizzled with the row
     // so that the 8-byte writes of 32 different rows spread over the banks -- and written out row
     // by row, 32 lanes x 16 bytes = one whole 512-byte row segment per half wave.
-    // Everything uniform (output type, destination) is decided once, outside the loops, and the
+    // Everything uniform (output type, destination, token zero-points or none) is decided once, outside the loops, and the
     // channel parameters of four outputs come with one 16-byte LDS read, reused over the wave's
     // token blocks: as a single loop with those decisions per element the compiler produced one
     // LDS read, one wait and several branches per output (17 us per 256 x 256 tile).
     uint8_t *ytile = lds_raw;                                         // [BM][512]
     enum { TO_PARTIAL = 0, TO_TILE = 1, TO_Y = 2 };
-    auto epilogue = [&](auto f16_tag, auto dest_tag, auto full_tag) __attribute__((always_inline)) {
+    auto epilogue = [&](auto f16_tag, auto dest_tag, auto full_tag, auto zp_tag) __attribute__((always_inline)) {
         constexpr bool F16 = decltype(f16_tag)::value;
         constexpr int DEST = decltype(dest_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;   // the tile lies inside Y: no range checks
+        constexpr bool ZP = decltype(zp_tag)::value;       // per-channel weights with token zero-points
 #pragma unroll
         for (int ns = 0; ns < GM_NS; ++ns) {
             if (!FULL && !ns_valid[ns]) continue;   // uniform over the wave
@@ -591,8 +592,8 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
                                 if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
                                 else acc_out[(int64_t)m * N + nn + r] = v >> 2;
                             }
-                            // (the accumulator hook keeps the raw sum; without token zero-points both factors are 0)
-                            v = __mul24(nzx4_a[ms], sw4[r]) + v;
+                            // (the accumulator hook keeps the raw sum)
+                            if (ZP) v = __mul24(nzx4_a[ms], sw4[r]) + v;
                             yv = es4[r] * (float)v;
                         }
                         part[r] = yv;
@@ -630,12 +631,16 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     using std::integral_constant;
     const bool staged = partial == nullptr && (vec_store & 2) != 0;   // uniform
     const bool full = m0 + BM <= M && nb0 + GM_BN <= N;                // uniform
+    auto epilogue_zp = [&](auto f16_tag, auto dest_tag, auto full_tag) __attribute__((always_inline)) {
+        if (asym) epilogue(f16_tag, dest_tag, full_tag, integral_constant<bool, true>{});
+        else epilogue(f16_tag, dest_tag, full_tag, integral_constant<bool, false>{});
+    };
     auto epilogue_for = [&](auto f16_tag, auto dest_tag) __attribute__((always_inline)) {
-        if (full) epilogue(f16_tag, dest_tag, integral_constant<bool, true>{});
-        else epilogue(f16_tag, dest_tag, integral_constant<bool, false>{});
+        if (full) epilogue_zp(f16_tag, dest_tag, integral_constant<bool, true>{});
+        else epilogue_zp(f16_tag, dest_tag, integral_constant<bool, false>{});
     };
     if (partial != nullptr) {
-        epilogue(integral_constant<bool, true>{}, integral_constant<int, TO_PARTIAL>{}, integral_constant<bool, false>{});
+        epilogue_zp(integral_constant<bool, true>{}, integral_constant<int, TO_PARTIAL>{}, integral_constant<bool, false>{});
     } else if (y_dtype == W4A8_F16) {
         if (staged) epilogue_for(integral_constant<bool, true>{}, integral_constant<int, TO_TILE>{});
         else epilogue_for(integral_constant<bool, true>{}, integral_constant<int, TO_Y>{});
@@ -702,6 +707,363 @@ static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, 
 #undef W4A8_GM2
 }
 
+// ---- group-128 weights at a few hundred tokens ---------------------------------------------------
+// Between the streaming kernel (<= 16 tokens per pass over the weights) and the tile kernel at full
+// occupancy lies the ridge of the roofline (M ~ 156): a 128-token tile kernel has only N / 256 tiles for
+// 256 CUs there, and cutting K into ranges over more workgroups moves more fp32 partial sums through
+// memory than the layer has weights.  This kernel cuts K inside the workgroup instead.  A workgroup
+// owns 128 tokens x 64 channels; its 8 waves are 2 (channel halves of 32) x 4 (K phases): phase q takes
+// the k-tiles kt = 4 i + q -- with 128-wide groups each k-tile is one whole group, so a wave decodes,
+// multiplies and rescales complete groups exactly like the tile kernel does, and no group is shared.
+// The four k-tiles of a super-step are consumed concurrently from four LDS slots while the next four
+// land in the other four (global -> LDS copies, issued right behind the barrier that frees the slots):
+// one barrier per FOUR k-tiles.  At the end the phases' fp32 sums meet through LDS in a fixed order
+// ((q0 + q1) + (q2 + q3)), and the two phase-0 waves apply the token scale and store.  N / 64 workgroups
+// per 128 tokens, no workspace, no second launch.
+constexpr int MD_BM = 128, MD_BN = 64, MD_KQ = 4, MD_THREADS = 512;
+constexpr int MD_TILE = MD_BM * TILE_K;   // bytes of one activation k-tile in LDS
+
+template <bool ACC_OUT>
+__global__ __launch_bounds__(MD_THREADS, 2) void gemm_mid_kernel(
+    const int8_t *__restrict__ Xq, const float *__restrict__ sx, int M, const uint8_t *__restrict__ Wt,
+    const float *__restrict__ step, const uint8_t *__restrict__ zero, int N, int K,
+    uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store, int32_t *__restrict__ acc_out,
+    int grid_m, int plain)
+{
+    constexpr int MS = MD_BM / 32;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];   // [2 * MD_KQ][MD_TILE]
+    __shared__ __attribute__((aligned(16))) float s_ges[4 * MD_KQ][MD_BN];   // step / 8 per k-tile (= group) of four super-steps, and channel
+    __shared__ int s_gz[4 * MD_KQ][MD_BN];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1;      // channel half
+    const int kq = wave >> 1;     // K phase
+    const int r32 = lane & 31;
+    const int kh = lane >> 5;
+    const int KT = K / TILE_K;    // = number of groups
+    const int SS = (KT + MD_KQ - 1) / MD_KQ;
+    const int bm = blockIdx.x % grid_m, bn = blockIdx.x / grid_m;
+    const int m0 = bm * MD_BM;
+    const int nb0 = bn * MD_BN;
+    const int n0 = nb0 + wn * 32;
+
+    __amdgpu_buffer_rsrc_t rw =
+        __builtin_amdgcn_make_buffer_rsrc((void *)Wt, 0, (int)((int64_t)N * K / 2), 0x00020000);
+    const uint64_t xq_addr = (uint64_t)Xq;
+    const v4i rx = {(int)(uint32_t)xq_addr, (int)((xq_addr >> 32) & 0xffffu), (int)((int64_t)M * K), 0x00020000};
+
+    // weights of this wave's 32 channels (see gemm_kernel): one 16-byte load covers two k-steps
+    const bool lane_ok = n0 + r32 < N;
+    const int wvoff = lane_ok ? (r32 >> 4) * KT * TILE_BYTES + ((r32 & 15) + 16 * kh) * 16 : GM_OOB;
+    const int wsoff = n0 < N ? (n0 / TILE_N) * KT * TILE_BYTES : 0;
+    auto load_b = [&](int kt, v4u(&dst)[2]) {
+        const int ktc = min(kt, KT - 1);
+        dst[0] = __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff, wsoff + ktc * TILE_BYTES, 0);
+        dst[1] = __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff + 512, wsoff + ktc * TILE_BYTES, 0);
+    };
+
+    // activation k-tile -> LDS slot: 16 blocks of 8 rows, two per wave (swizzle as in gemm_kernel)
+    int avoff[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = (i * 8 + wave) * 8 + (lane >> 3);
+        avoff[i] = (m0 + row) * K + (((lane & 7) ^ ((row >> 1) & 7)) << 4);
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw;
+    // this wave's share of the four k-tiles of super-step ss (into the slots of its parity): eight copies
+    // of 1 KB, c = 2 j + i for block i of k-tile j
+    auto dma_one = [&](int ss, int c) {
+        const int j = c >> 1, i = c & 1;
+        const int kt = min(ss * MD_KQ + j, KT - 1);
+        const int slot = (ss & 1) * MD_KQ + j;
+        dma_b128(rx, avoff[i], kt * TILE_K, lds_base + (uint32_t)(slot * MD_TILE + (i * 8 + wave) * 1024));
+    };
+    auto dma_super_step = [&](int ss) {
+#pragma unroll
+        for (int c = 0; c < 2 * MD_KQ; ++c) dma_one(ss, c);
+    };
+    // group parameters of a super-step: thread (j = tid / 64, ch = tid % 64), tid < 256
+    float gp_es = 0.f;
+    int gp_z = 0;
+    auto fetch_params = [&](int ss) {
+        if (tid < MD_KQ * MD_BN) {
+            const int kt = min(ss * MD_KQ + (tid >> 6), KT - 1);
+            const int nn = nb0 + (tid & 63) < N ? nb0 + (tid & 63) : 0;
+            gp_es = step[(int64_t)nn * KT + kt];   // (used only in publish_params: nothing here waits for the load)
+            gp_z = zero[(int64_t)nn * KT + kt];
+        }
+    };
+    auto publish_params = [&](int ss) {
+        if (tid < MD_KQ * MD_BN) {
+            s_ges[(ss & 3) * MD_KQ + (tid >> 6)][tid & 63] = gp_es * 0.125f;
+            s_gz[(ss & 3) * MD_KQ + (tid >> 6)][tid & 63] = gp_z;
+        }
+    };
+
+    v16i acc[MS];
+    float y[MS][16];
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[ms][r] = 0.f;
+
+    int frag_off[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int chunk = 2 * (2 * (s4 >> 1) + kh) + (s4 & 1);
+        frag_off[s4] = r32 * TILE_K + ((chunk ^ ((r32 >> 1) & 7)) << 4);
+    }
+    auto read_a = [&](int slot, int ms, int s4) {   // fragment of token block ms, k-step s4
+        return *reinterpret_cast<const v4i *>(&lds_raw[slot * MD_TILE + ms * (32 * TILE_K) + frag_off[s4]]);
+    };
+    SignedLut slut;
+    auto decode_step = [&](const v4u(&pk)[2], int s4, v4i &dst) {
+        const int sp = s4 >> 1, h = s4 & 1;
+        const uint32_t q0 = h ? pk[sp].z : pk[sp].x;
+        const uint32_t q1 = h ? pk[sp].w : pk[sp].y;
+        int a, b, c, d;
+        decode_word_signed(q0, slut, a, b);
+        decode_word_signed(q1, slut, c, d);
+        dst = v4i{a, b, c, d};
+    };
+    // y += (step / 8) * acc for accumulator registers 4 b .. 4 b + 3 of token block ms (group kt)
+    v4f es4[4];   // step / 8 of this lane's 16 channels for the group in the accumulators
+    auto flush_quarter = [&](int ms, int b, int kt) {
+        const int m = m0 + ms * 32 + r32;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int v = acc[ms][4 * b + r];
+            y[ms][4 * b + r] = __builtin_fmaf(es4[b][r], (float)v, y[ms][4 * b + r]);
+            if (ACC_OUT && m < M) {
+                const int nn = nb0 + wn * 32 + 8 * b + 4 * kh + r;
+                if (nn < N) acc_out[((int64_t)m * N + nn) * KT + kt] = v >> 2;
+            }
+        }
+    };
+
+    // ---- prologue: super-steps 0 and 1 on their way, this wave's first four k-tiles of weights, the
+    // group parameters of super-steps 0 and 1 published and those of 2 requested
+    v4u pw[4][2];   // packed weights of this wave's next four k-tiles (the weights come from HBM, read once)
+    dma_super_step(0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_b(i * MD_KQ + kq, pw[i]);
+    fetch_params(0);
+    publish_params(0);
+    fetch_params(min(1, SS - 1));
+    publish_params(1);
+    fetch_params(min(2, SS - 1));
+    asm volatile("" : "+v"(pw[0][0]), "+v"(pw[0][1]), "+v"(pw[1][0]), "+v"(pw[1][1]));
+    wait_copies<0>();
+    __syncthreads();
+
+    v4i w[4], af[4];   // decoded weights of the four k-steps of the current k-tile; activation fragments
+    slut = make_signed_lut(s_gz[kq][wn * 32 + r32], plain != 0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) decode_step(pw[0], k, w[k]);
+    bool pending = false;   // (uniform) accumulators of token block 3 of the previous k-tile wait for their rescale
+
+    // One super-step of this wave: k-tile kt = 4 ss + q (= one group) from LDS slot (ss parity, q).
+    // The MFMAs run token block by token block (four k-steps each), so that the rescale of block ms - 1
+    // -- whose group sum is complete -- and, under the last block, the decode of the NEXT k-tile (each
+    // w[k] is free once the last MFMA that reads it has issued) sit between the MFMAs of block ms:
+    // a wave overlaps its own vector and matrix work instead of relying on its SIMD neighbour.
+    // The last block's rescale is deferred to the start of the next super-step, where it covers the
+    // latency of the first fragment reads.
+    // P: packed weights of this k-tile, refilled for the wave's k-tile four super-steps on; PN: those of
+    // the next super-step (decoded here); PNN: those of the one after (completed here, see below).
+    // Order of the memory accesses of a wave (vmcnt retires in this order):
+    //   behind barrier(ss - 1): [2 parameter loads of ss + 2]
+    //   in super-step ss:       8 copies of super-step ss + 1 (their slots were freed by barrier(ss - 1))
+    //   at the end of ss:       2 weight loads for ss + 4
+    // so "at most 2 outstanding" at the end of super-step ss means the copies of ss + 1 have landed and
+    // every older weight load is complete; the barrier then publishes the copies and frees the slots
+    // of ss for ss + 2.  Group parameters: ring of four super-steps, published two ahead (the decode of
+    // the next k-tile needs its zero-points before the next barrier).
+    auto super_step = [&](v4u(&P)[2], v4u(&PN)[2], v4u(&PNN)[2], int ss) __attribute__((always_inline)) {
+        const int kt = ss * MD_KQ + kq;
+        const int slot = (ss & 1) * MD_KQ + kq;
+        const int pslot = (ss & 3) * MD_KQ + kq;
+        const int pslot_next = ((ss + 1) & 3) * MD_KQ + kq;
+        const bool live = kt < KT;   // (uniform over the wave; live k-tiles come first)
+        if (live) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) af[k] = read_a(slot, 0, k);
+        }
+        if (pending) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) flush_quarter(3, b, kt - MD_KQ);
+            pending = false;
+        }
+        if (live) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                es4[b] = *reinterpret_cast<const v4f *>(&s_ges[pslot][wn * 32 + 8 * b + 4 * kh]);
+            int z_next = s_gz[pslot_next][wn * 32 + r32];
+            const v16i z16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms) {
+                if (ms == 1) {
+                    // the scales and the next zero-point are in registers from here on (their reads were
+                    // issued before the first block's MFMAs; without this the reads sink to their uses)
+                    asm volatile("" : "+v"(es4[0]), "+v"(es4[1]), "+v"(es4[2]), "+v"(es4[3]), "+v"(z_next));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (k == 0) acc[ms] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[0], af[0], z16, 0, 0, 0);
+                    else acc[ms] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[k], af[k], acc[ms], 0, 0, 0);
+                    if (ms + 1 < MS) af[k] = read_a(slot, ms + 1, k);
+                    // the copies of the next super-step, two per MFMA of the first block: issued in one burst
+                    // by all eight waves they fill the address queue of the CU and hold every wave up
+                    if (ms == 0) {
+                        dma_one(ss + 1, 2 * k);
+                        dma_one(ss + 1, 2 * k + 1);
+                    }
+                    if (ms > 0) flush_quarter(ms - 1, k, kt);
+                    if (ms + 1 == MS) {
+                        if (k == 0) slut = make_signed_lut(z_next, plain != 0);
+                        decode_step(PN, k, w[k]);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (ms + 1 < MS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (ms + 1 == MS) __builtin_amdgcn_sched_group_barrier(0x002, 32, 0);
+                    else if (ms > 0) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                }
+            }
+            pending = true;
+        } else {
+            dma_super_step(ss + 1);
+        }
+        gm_order_fence();
+        load_b((ss + 4) * MD_KQ + kq, P);
+        gm_order_fence();
+        wait_copies<2>();
+        // (a use in every lane, outside any branch: all waits for the parameter loads and for PNN happen
+        // here, none behind the copies issued below)
+        asm volatile("" : "+v"(PNN[0]), "+v"(PNN[1]), "+v"(gp_es), "+v"(gp_z));
+        publish_params(ss + 2);   // (fetched behind the last barrier)
+        __syncthreads();
+        fetch_params(min(ss + 3, SS - 1));
+        gm_order_fence();
+    };
+
+    {
+        int ss = 0;
+        for (; ss + 4 <= SS; ss += 4) {
+            super_step(pw[0], pw[1], pw[2], ss);
+            super_step(pw[1], pw[2], pw[3], ss + 1);
+            super_step(pw[2], pw[3], pw[0], ss + 2);
+            super_step(pw[3], pw[0], pw[1], ss + 3);
+        }
+        if (ss < SS) super_step(pw[0], pw[1], pw[2], ss);
+        if (ss + 1 < SS) super_step(pw[1], pw[2], pw[3], ss + 1);
+        if (ss + 2 < SS) super_step(pw[2], pw[3], pw[0], ss + 2);
+        if (pending) {   // the last live k-tile of this wave: 4 (SS - 1) + q, or the one before
+            const int kt_last = (SS - 1) * MD_KQ + kq;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) flush_quarter(3, b, kt_last < KT ? kt_last : kt_last - MD_KQ);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // ---- the four phases' sums meet in LDS: (q0 + q1) + (q2 + q3)
+    float *red = reinterpret_cast<float *>(lds_raw);   // [..][64 lanes][64 floats], 16 KB per wave
+    auto red_ptr = [&](int slot) { return red + ((size_t)slot * 64 + lane) * 64; };
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int r = 0; r < 16; r += 4)
+                *reinterpret_cast<v4f *>(red_ptr(slot) + ((ms * 16 + r) ^ ((lane & 15) << 2))) =
+                    v4f{y[ms][r], y[ms][r + 1], y[ms][r + 2], y[ms][r + 3]};
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) {
+                const v4f t = *reinterpret_cast<const v4f *>(red_ptr(slot) + ((ms * 16 + r) ^ ((lane & 15) << 2)));
+                y[ms][r] += t.x; y[ms][r + 1] += t.y; y[ms][r + 2] += t.z; y[ms][r + 3] += t.w;
+            }
+    };
+    if (kq & 1) put((kq >> 1) * 2 + wn);          // q1 -> slots 0, 1; q3 -> slots 2, 3
+    __syncthreads();
+    if (!(kq & 1)) add((kq >> 1) * 2 + wn);       // q0 += q1, q2 += q3
+    __syncthreads();
+    if (kq == 2) put(wn);
+    __syncthreads();
+    if (kq != 0) return;
+    add(wn);
+
+    // ---- epilogue (phase-0 waves): Y[m, n .. n+3] = cast(sx[m] * y)
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) {
+        const int m = m0 + ms * 32 + r32;
+        if (m >= M) continue;
+        const float sxm = sx[m];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int nn = nb0 + wn * 32 + 8 * b + 4 * kh;
+            if (nn >= N) continue;   // (N % 16 == 0: four channels are valid together)
+            uint16_t hh[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float out = sxm * y[ms][4 * b + r];   // binary32 product, then the cast (see gemm_kernel)
+                asm volatile("" : "+v"(out));
+                hh[r] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+            }
+            uint16_t *yp = Y + (int64_t)m * ldy + nn;
+            if (vec_store & 1) {
+                *reinterpret_cast<uint2 *>(yp) = make_uint2((uint32_t)hh[0] | ((uint32_t)hh[1] << 16),
+                                                            (uint32_t)hh[2] | ((uint32_t)hh[3] << 16));
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) yp[r] = hh[r];
+            }
+        }
+    }
+}
+
+// Whether a shape takes gemm_mid_kernel: 128-wide groups, symmetric activations, 65 .. 256 tokens, and a
+// grid of at most one workgroup per CU.  Measured against the tile kernel with K cut into ranges (which
+// is what these shapes would otherwise run): ahead wherever the grid covers at least half the CUs
+// (LLaMA-13B up-projection at 128 tokens: 39 -> 26 us; 4096 x 4096 at 256: 29 -> 22 us), behind on long K
+// with few workgroups (13824 -> 5120 at 128 tokens: 80 workgroups, 27 super-steps, 45 against 37 us) and
+// with more than one workgroup per CU.
+bool gemm_mid_applies(int64_t M, int64_t N, int64_t K, int64_t G, bool asym)
+{
+    if (asym || G != TILE_K || G == K || M <= 64 || M > 256) return false;
+    const int64_t wgs = (M + MD_BM - 1) / MD_BM * ((N + MD_BN - 1) / MD_BN);
+    const int64_t KT = K / TILE_K;
+    return KT >= 8 && wgs <= 256 && (wgs >= 128 || KT <= 48);
+}
+
+static int launch_gemm_mid(const int8_t *Xq, const float *sx, int64_t M, const uint8_t *Wt, const float *step,
+                           const uint8_t *zero, int64_t N, int64_t K, void *Y, int y_dtype, int64_t ldy,
+                           int32_t *acc_out, hipStream_t st, int plain)
+{
+    const int grid_m = (int)((M + MD_BM - 1) / MD_BM);
+    const int grid_n = (int)((N + MD_BN - 1) / MD_BN);
+    const int vec_store = (((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0)) ? 1 : 0;
+    constexpr int lds_bytes = 2 * MD_KQ * MD_TILE;   // 128 KB
+#define W4A8_MD(AO_)                                                                                      \
+    do {                                                                                                  \
+        static std::atomic<uint64_t> lds_opted{0};                                                        \
+        if (opt_in_dynamic_lds((const void *)gemm_mid_kernel<AO_>, lds_bytes, lds_opted) != W4A8_OK)      \
+            return W4A8_ERR_HIP;                                                                          \
+        hipLaunchKernelGGL((gemm_mid_kernel<AO_>), dim3((unsigned)(grid_m * grid_n)), dim3(MD_THREADS),   \
+                           lds_bytes, st, Xq, sx, (int)M, Wt, step, zero, (int)N, (int)K, (uint16_t *)Y,  \
+                           y_dtype, ldy, vec_store, acc_out, grid_m, plain);                              \
+    } while (0)
+    if (acc_out) W4A8_MD(true);
+    else W4A8_MD(false);
+#undef W4A8_MD
+    return hip_status(hipGetLastError());
+}
+
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
 {
     GemmPlan pl{};
@@ -754,6 +1116,8 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
     const bool grouped = G != K;
     if ((M + 63) / 64 * ((N + 255) / 256) * 64 > 0x7fffffLL || M * K > 0x7fffffffLL)
         return W4A8_ERR_SHAPE;
+    if (gemm_mid_applies(M, N, K, G, zp.zx != nullptr))
+        return launch_gemm_mid(Xq, sx, M, Wt, step, zero, N, K, Y, y_dtype, ldy, acc_out, st, plain);
     const GemmPlan pl = plan_gemm(M, N, K, G);
     if (!grouped) {
         const int64_t segs = M * pl.splits;

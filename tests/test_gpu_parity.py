@@ -191,6 +191,13 @@ PREFILL_CASES = [
     ("m113_eight_blocks_small_layer", 113, 640, 528, 128),
     ("m100_ragged", 100, 640, 528, 0),
     ("m130_g128", 130, 1024, 304, 128),
+    # group-128 weights, 129 .. 256 tokens, few output tiles: the kernel that cuts K into four phases
+    # inside the workgroup -- super-steps of four k-tiles with a ragged last one (11, 18 k-tiles), exactly
+    # two super-steps, a ragged 64-channel tile, one and two token tiles
+    ("m130_k_phases_11_ktiles_g128", 130, 1408, 80, 128),
+    ("m256_k_phases_18_ktiles_g128", 256, 2304, 1040, 128),
+    ("m129_k_phases_two_super_steps_g128", 129, 1024, 64, 128),
+    ("m200_k_phases_40_ktiles_g128", 200, 5120, 336, 128),
     ("m300", 300, 768, 1040, 0),
     ("m300_g256", 300, 768, 512, 256),
     ("m600_multi_block", 600, 1024, 784, 0),
