@@ -434,7 +434,11 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
     float q_inv = 0.f;   // 127 / (row maximum), 0 for an all-zero row
     // slot u: raw pieces -> int8 fragments.  rne and the conversion are one addition: y + 1.5 * 2^23
     // holds rne(y) in its low bits (|y| <= 127 (1 + 2^-23): the clamp of the definition never acts).
+    // The product y = t * (127 / a) is rounded to binary32 BEFORE that addition, as in the definition:
+    // fused into one multiply-add, a product just below a tie (x = a / 2 gives 63.5 - eps for about half
+    // of all a) would round down where the definition's rounded product, the tie itself, goes to even.
     auto quantize_slot = [&](int u) __attribute__((always_inline)) {
+#pragma clang fp contract(off)
         const float *rk = r_lds + (wave + u * GV_CW) * TILE_K + xcol;
         uint32_t o[8];
 #pragma unroll
@@ -444,7 +448,11 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             scaled8(xr[u][pc], (u < tpw ? rk : r_lds) + (pc >> 1) * 64 + (pc & 1) * 8, t);
             uint32_t b[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(__fadd_rn(__fmul_rn(t[i], q_inv), 12582912.0f));
+            for (int i = 0; i < 8; ++i) {
+                float yq = t[i] * q_inv;
+                asm volatile("" : "+v"(yq));   // (belt and braces: the rounded product is a value of its own)
+                b[i] = __float_as_uint(yq + 12582912.0f);
+            }
             o[2 * pc] = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u) | __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
             o[2 * pc + 1] = __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u) | __builtin_amdgcn_perm(b[7], b[6], 0x04000c0cu);
             __builtin_amdgcn_sched_barrier(0);   // (piece by piece, as above)

@@ -136,3 +136,47 @@ def test_linear_exact_output_of_the_plain_one_launch_instances(lib, oracle):
         Y = lib.w4a8_linear(dev(Xq.astype(np.float16)), None, Wp, dev(step), dev(zero), N, G)
         got = host(Y).astype(np.float32)
         assert np.array_equal(got, y32), f"{(got != y32).sum()} outputs differ from the exact result"
+
+
+def test_product_is_rounded_before_the_tie_break(lib, oracle):
+    """Per-token INT8 rounding is rne(fl32(t * fl32(127 / a))): two binary32 roundings, then the tie
+    break.  For a token whose maximum is a and that also holds a / 2, the exact product is 63.5 - eps
+    for about half of all a (127 / a rounded down), the rounded product is the tie 63.5 itself: the
+    definition gives 64, a multiply-add fused with the rounding step would give 63.  Both GPU paths
+    (quantize_act_int8 and the one-launch w4a8_linear, which rounds inside the streaming kernel) must
+    give the definition's value."""
+    halves = np.arange(0x3c00, 0x7800, dtype=np.uint16).view(np.float16).astype(np.float32)   # fp16 in [1, 32768)
+    inv = np.float32(127.0) / halves
+    t = (halves * np.float32(0.5)).astype(np.float32)              # a / 2: exact in fp16 (normal range)
+    y32 = (t * inv).astype(np.float32)
+    exact = t.astype(np.float64) * inv.astype(np.float64)
+    witness = halves[(y32 == np.float32(63.5)) & (exact < 63.5)]
+    assert witness.size > 1000                                     # the premise: such maxima are common
+    rng = np.random.default_rng(5)
+    M, K, N, G = 16, 1024, 272, 128
+    X = (rng.standard_normal((M, K)) * 0.25).astype(np.float16).astype(np.float32)
+    a = rng.choice(witness[witness < 2048], size=M, replace=False)
+    cols = rng.choice(np.arange(1, K), size=(M, 24), replace=True)
+    for m in range(M):
+        X[m, 0] = a[m]
+        X[m, cols[m]] = np.where(rng.random(24) < 0.5, 0.5, -0.5) * a[m]
+    X16 = X.astype(np.float16)
+    assert np.array_equal(X16.astype(np.float32), X)
+    ref_q, ref_sx = oracle.quantize_act_int8(X, None)
+    for m in range(M):
+        assert set(np.abs(ref_q[m, cols[m]]).tolist()) == {64}     # the definition: ties to even
+        fused = np.rint(X[m, cols[m]].astype(np.float64) * np.float64(np.float32(127.0) / np.float32(a[m])))
+        assert set(np.abs(fused).tolist()) == {63}                 # what a fused multiply-add would give
+    Xd = dev(X16)
+    q2, sx2 = lib.quantize_act_int8(Xd, None)
+    assert np.array_equal(host(q2), ref_q) and np.array_equal(host(sx2), ref_sx)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    codes, step, zero = lib.quantize_weight_dint4(dev(W), None, G)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    Y, Xq, sx, acc = lib.w4a8_linear(Xd, None, Wp, step, zero, N, G, want_quantized=True, want_acc=True)
+    assert np.array_equal(host(sx), ref_sx)
+    bad = host(Xq) != ref_q
+    assert not bad.any(), f"{bad.sum()} int8 activations differ from the definition, first at {np.argwhere(bad)[0]}"
+    Y1 = lib.w4a8_linear(Xd, None, Wp, step, zero, N, G)
+    Y2 = lib.w4a8_gemm(q2, sx2, Wp, step, zero, N, K, G)
+    assert torch.equal(Y1, Y2)
