@@ -239,6 +239,31 @@ def test_activation_properties(oracle):
     assert np.array_equal(a, c) and np.array_equal(b, d)
 
 
+def test_activation_rounding_is_two_binary32_steps_then_ties_to_even(oracle):
+    """The precision of the decision (a reading of the token-wise 8-bit quantizer, App. A.1): the code is
+    rne(fl32(t * fl32(127 / a))).  With x = a / 2 the exact product is 63.5 - eps whenever fl32(127 / a)
+    was rounded down and its rounded value is the tie 63.5 itself, which goes to the even code 64; a
+    version that rounds the exact product (one fused step) would give 63.  Checked against exact
+    rational arithmetic on the float64 product (35 significant bits: exact)."""
+    a = np.arange(0x3c00, 0x7800, dtype=np.uint16).view(np.float16).astype(np.float32)
+    inv = np.float32(127.0) / a
+    half = (a * np.float32(0.5)).astype(np.float32)
+    exact = half.astype(np.float64) * inv.astype(np.float64)
+    below = a[((half * inv).astype(np.float32) == np.float32(63.5)) & (exact < 63.5)]
+    above = a[((half * inv).astype(np.float32) == np.float32(63.5)) & (exact > 63.5)]
+    assert below.size > 1000 and above.size > 1000
+    for arr, fused in ((below[:200], 63), (above[:200], 64)):
+        X = np.stack([arr, 0.5 * arr, -0.5 * arr], axis=1).astype(np.float32)
+        Xq, sx = oracle.quantize_act_int8(X, None)
+        assert np.array_equal(Xq[:, 0], np.full(arr.size, 127, np.int8))
+        assert np.all(Xq[:, 1] == 64) and np.all(Xq[:, 2] == -64)          # ties to even, both signs
+        assert np.all(np.rint(0.5 * arr.astype(np.float64) * (np.float32(127.0) / arr).astype(np.float64)) == fused)
+    # a tie that goes DOWN to even: x = a * 125 / 254 would be 62.5 -> 62; use exact small integers instead
+    X = np.array([[127.0, 62.5, 61.5, -62.5, 0.5, 1.5, 2.5]], np.float32)   # a = 127: inv = 1 exactly
+    Xq, _ = oracle.quantize_act_int8(X, None)
+    assert Xq[0].tolist() == [127, 62, 62, -62, 0, 2, 2]
+
+
 # ------------------------------------------------------------------ P9 GEMM identities
 @pytest.mark.parametrize("G", [0, 128])
 def test_int_gemm_equals_float64_matmul(oracle, G):
