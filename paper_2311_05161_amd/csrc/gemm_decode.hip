@@ -427,8 +427,11 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             hi = __half2float(__ushort_as_half((uint16_t)(wd[i] >> 16)));
             const float ra = i < 2 ? r0[2 * i] : r1[2 * i - 4];
             const float rb = i < 2 ? r0[2 * i + 1] : r1[2 * i - 3];
-            t[2 * i] = __fmul_rn(lo, ra);
-            t[2 * i + 1] = __fmul_rn(hi, rb);
+            // (x * r + 0: the same single rounding of the exact product as x * r -- only the sign of a zero
+            // can differ, which neither the maximum nor the code sees --, but the widening folds into it:
+            // one mixed-precision multiply-add instead of a conversion and a multiply)
+            t[2 * i] = __builtin_fmaf(lo, ra, 0.0f);
+            t[2 * i + 1] = __builtin_fmaf(hi, rb, 0.0f);
         }
     };
     float q_inv = 0.f;   // 127 / (row maximum), 0 for an all-zero row
