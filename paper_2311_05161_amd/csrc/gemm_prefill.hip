@@ -655,8 +655,10 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
             const int c16 = lane & 31;
             const int m = m0 + r, nn = nb0 + c16 * 8;
             if (m < M && nn < N) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(ytile + r * 512 + ((c16 ^ (r & 15)) << 4));
-                *reinterpret_cast<uint4 *>(Y + (int64_t)m * ldy + nn) = v;
+                const v4u v = *reinterpret_cast<const v4u *>(ytile + r * 512 + ((c16 ^ (r & 15)) << 4));
+                // (streaming stores: nobody in this launch reads Y, and the caches are what serves the
+                // re-reads of the activations and weights by the other tiles)
+                __builtin_nontemporal_store(v, reinterpret_cast<v4u *>(Y + (int64_t)m * ldy + nn));
             }
         }
     }
