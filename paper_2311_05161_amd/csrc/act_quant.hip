@@ -118,15 +118,19 @@ template <typename T>
 __device__ __forceinline__ Raw8<T> load_raw8(const T *p)
 {
     Raw8<T> r;
-    r.v = *reinterpret_cast<const uint4 *>(p);
+    // (streaming loads: the unquantized activations are read exactly once)
+    const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
+    r.v = make_uint4(t.x, t.y, t.z, t.w);
     return r;
 }
 template <>
 __device__ __forceinline__ Raw8<float> load_raw8<float>(const float *p)
 {
     Raw8<float> r;
-    r.a = *reinterpret_cast<const float4 *>(p);
-    r.b = *reinterpret_cast<const float4 *>(p + 4);
+    const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+    const v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p + 4));
+    r.a = make_float4(a.x, a.y, a.z, a.w);
+    r.b = make_float4(b.x, b.y, b.z, b.w);
     return r;
 }
 __device__ __forceinline__ void widen8(const Raw8<float> &r, float (&v)[8])
@@ -307,11 +311,11 @@ __global__ __launch_bounds__(AQW_WAVES *WAVE, 2) void act_quant_wave_kernel(
 #pragma unroll
         for (int c = 0; c < NCW; ++c) {
             if constexpr (sizeof(T) == 2) {
-                const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW, 0, 0);
+                const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW, 0, 2);   // (aux 2: non-temporal)
                 nxt[c].v = make_uint4(v.x, v.y, v.z, v.w);
             } else {
-                const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW, 0, 0);
-                const v4u v1 = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW + 16, 0, 0);
+                const v4u v0 = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW, 0, 2);   // (aux 2: non-temporal)
+                const v4u v1 = __builtin_amdgcn_raw_buffer_load_b128(rx, (lane + c * WAVE) * RAW + 16, 0, 2);
                 nxt[c].a = make_float4(__uint_as_float(v0.x), __uint_as_float(v0.y), __uint_as_float(v0.z), __uint_as_float(v0.w));
                 nxt[c].b = make_float4(__uint_as_float(v1.x), __uint_as_float(v1.y), __uint_as_float(v1.z), __uint_as_float(v1.w));
             }
