@@ -25,12 +25,12 @@ __global__ __launch_bounds__(SR_THREADS) void stream_read_kernel(const v4u *__re
     for (; i + (SR_UNROLL - 1) * stride < n16; i += SR_UNROLL * stride) {
         v4u v[SR_UNROLL];
 #pragma unroll
-        for (int u = 0; u < SR_UNROLL; ++u) v[u] = src[i + u * stride];
+        for (int u = 0; u < SR_UNROLL; ++u) v[u] = __builtin_nontemporal_load(&src[i + u * stride]);   // (streaming, as the decode kernel's weight loads)
 #pragma unroll
         for (int u = 0; u < SR_UNROLL; ++u) fold ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < n16; i += stride) {
-        const v4u v = src[i];
+        const v4u v = __builtin_nontemporal_load(&src[i]);
         fold ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     if (fold == 0x9e3779b9u && sink != nullptr) sink[0] = fold;
