@@ -216,6 +216,20 @@ def test_gemm_prefill_parity(lib, oracle, case):
     _gemm_case(lib, oracle, 23 + len(name), M, K, N, G)
 
 
+# The K-phase kernel's edges: 65 / 128 / 129 / 256 tokens (above the token blocks' reach only where the
+# layer is large or M > 128: the small ones here run M > 128), every residue of the k-tile count modulo
+# the four phases and modulo the four weight register sets (8 .. 15 k-tiles: one to four super-steps, ragged
+# and full), one 64-channel tile, a ragged one, and -- on layers beyond the token blocks' 48 Mi weights -- 65 and
+# 128 tokens with a grid of 128 / 129 workgroups and 50 k-tiles (the other arm of the dispatch rule).
+K_PHASE_EDGES = [(129 + 9 * kt, 128 * kt, 16 * (1 + kt % 7)) for kt in range(8, 16)] + [
+    (256, 1024, 64), (255, 1152, 4096 + 16), (129, 6144, 48), (65, 6400, 8192), (128, 6400, 8192 + 64)]
+
+
+@pytest.mark.parametrize("M,K,N", K_PHASE_EDGES)
+def test_gemm_k_phase_kernel_edges(lib, oracle, M, K, N):
+    _gemm_case(lib, oracle, M + K + N, M, K, N, 128)
+
+
 def test_gemm_bf16_output_and_canonical_layout(lib, oracle):
     _gemm_case(lib, oracle, 5, 12, 512, 64, 128, out_dtype="bf16")
     _gemm_case(lib, oracle, 6, 40, 512, 64, 0, out_dtype="bf16")
