@@ -32,6 +32,7 @@
  * examples of Eq. 5, brute-force nearest-level search in float64, a float64
  * matmul of dequantized operands, exhaustive product tables).
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -59,8 +60,10 @@ int oracle_num_threads(void)
  *   r[k]   = 1 / s[k]                 (1 if s == NULL)
  *   t[m,k] = X[m,k] * r[k]
  *   a[m]   = max_k |t[m,k]|
- *   a == 0 : sx[m] = 1, Xq[m,:] = 0
- *   else   : sx[m] = a / 127 ; inv = 127 / a
+ *   inv    = 127 / a
+ *   inv not finite (a == 0, or a below 127 / FLT_MAX ~ 3.7e-37, where the reciprocal scale
+ *   overflows binary32 and t * inv would be inf or nan): sx[m] = 1, Xq[m,:] = 0
+ *   else   : sx[m] = a / 127
  *            Xq[m,k] = clamp(rne(t * inv), -127, 127)
  *
  * rbuf: caller-provided scratch of K floats.  Returns 0, or 1 on bad arguments.
@@ -81,13 +84,13 @@ int oracle_quantize_act_int8(const float *X, int64_t M, int64_t K, int64_t ldx,
             if (at > a) a = at;
         }
         int8_t *q = Xq + m * K;
-        if (a == 0.0f) {
+        float inv = 127.0f / a;
+        if (!(inv <= FLT_MAX)) {   /* a == 0 or vanishingly small: no information at 8 bits */
             sx[m] = 1.0f;
             for (int64_t k = 0; k < K; ++k) q[k] = 0;
             continue;
         }
         sx[m] = a / 127.0f;
-        float inv = 127.0f / a;
         for (int64_t k = 0; k < K; ++k) {
             float t = x[k] * rbuf[k];
             float v = nearbyintf(t * inv);
@@ -345,8 +348,10 @@ int oracle_dequant_epilogue(const int32_t *acc, const float *sx, const float *st
  *
  *   t[m,k] = X[m,k] * r[k]                           r[k] = 1 / s[k]
  *   lo = min(0, min_k t), hi = max(0, max_k t)
- *   hi == lo : sx = 1, zx = 0, Q[m,:] = 0
- *   else     : sx = (hi - lo) / 255 ; isx = 1 / sx
+ *   sx = (hi - lo) / 255 ; isx = 1 / sx
+ *   isx not finite (hi == lo, or a range so small that the reciprocal overflows binary32):
+ *              sx = 1, zx = 0, Q[m,:] = 0
+ *   else     :
  *              zx = clamp(rne(-lo * isx), 0, 255)
  *              Q[m,k] = clamp(rne(t * isx) + zx, 0, 255)      (codes 0..255)
  *   dequantized value: (Q - zx) * sx
@@ -368,15 +373,15 @@ int oracle_quantize_act_uint8_asym(const float *X, int64_t M, int64_t K, int64_t
             if (t > hi) hi = t;
         }
         uint8_t *q = Q + m * K;
-        if (hi == lo) {
+        float range = hi - lo;
+        float st = range / 255.0f;
+        float isx = 1.0f / st;
+        if (!(isx <= FLT_MAX)) {   /* all-zero token, or a vanishing range */
             sx[m] = 1.0f;
             zx[m] = 0;
             for (int64_t k = 0; k < K; ++k) q[k] = 0;
             continue;
         }
-        float range = hi - lo;
-        float st = range / 255.0f;
-        float isx = 1.0f / st;
         float zf = nearbyintf(-lo * isx);
         if (zf < 0.0f) zf = 0.0f;
         if (zf > 255.0f) zf = 255.0f;

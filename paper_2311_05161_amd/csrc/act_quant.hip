@@ -13,6 +13,8 @@
 
 namespace w4a8 {
 
+constexpr float AQ_FLT_MAX = 3.402823466e+38f;   // a token whose 127 / max|t| is not finite counts as all-zero
+
 constexpr int AQ_THREADS = 256;
 constexpr int AQ_VEC = 8;
 
@@ -91,13 +93,13 @@ struct AsymParams {
 __device__ __forceinline__ AsymParams asym_params(float lo, float hi)
 {
     AsymParams p;
-    if (hi == lo) {   // all-zero token
-        p.sx = 1.0f; p.isx = 0.0f; p.zf = 0.0f;
-        return p;
-    }
     const float range = hi - lo;
     p.sx = range / 255.0f;
     p.isx = 1.0f / p.sx;
+    if (!(p.isx <= AQ_FLT_MAX)) {   // all-zero token, or a range so small that the reciprocal scale overflows
+        p.sx = 1.0f; p.isx = 0.0f; p.zf = 0.0f;
+        return p;
+    }
     p.zf = fminf(fmaxf(__builtin_rintf(-lo * p.isx), 0.0f), 255.0f);
     return p;
 }
@@ -235,8 +237,9 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
             }
         } else {
             a = block_max(a, red);
-            const bool zero_row = (a == 0.0f);
-            inv = zero_row ? 0.0f : 127.0f / a;
+            const float inv0 = 127.0f / a;
+            const bool zero_row = !(inv0 <= AQ_FLT_MAX);   // a == 0, or so small that 127 / a overflows
+            inv = zero_row ? 0.0f : inv0;
             if (tid == 0) sx[m] = zero_row ? 1.0f : a / 127.0f;
         }
         int8_t *q = Xq + m * (int64_t)K;
@@ -382,8 +385,9 @@ __global__ __launch_bounds__(AQW_WAVES *WAVE, 2) void act_quant_wave_kernel(
                 zx[m] = (int)ap.zf - 128;
             }
         } else {
-            const bool zero_row = (a == 0.0f);
-            inv = zero_row ? 0.0f : 127.0f / a;
+            const float inv0 = 127.0f / a;
+            const bool zero_row = !(inv0 <= AQ_FLT_MAX);   // a == 0, or so small that 127 / a overflows
+            inv = zero_row ? 0.0f : inv0;
             if (lane == 0) sx[m] = zero_row ? 1.0f : a / 127.0f;
         }
         __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void *)(Xq + m * (int64_t)K), 0, K, 0x00020000);
@@ -430,8 +434,9 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_generic_kernel(
         }
     } else {
         a = block_max(a, red);
-        const bool zero_row = (a == 0.0f);
-        inv = zero_row ? 0.0f : 127.0f / a;
+        const float inv0 = 127.0f / a;
+        const bool zero_row = !(inv0 <= AQ_FLT_MAX);   // a == 0, or so small that 127 / a overflows
+        inv = zero_row ? 0.0f : inv0;
         if (threadIdx.x == 0) sx[m] = zero_row ? 1.0f : a / 127.0f;
     }
     int8_t *q = Xq + m * K;

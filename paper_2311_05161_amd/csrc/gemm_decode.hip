@@ -295,7 +295,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
             float am = 0.f;
 #pragma unroll
             for (int w = 0; w < GV_CW; ++w) am = fmaxf(am, mx[w * 16 + hm]);
-            sxm = am == 0.f ? 1.0f : am / 127.0f;
+            sxm = !(127.0f / am <= 3.402823466e+38f) ? 1.0f : am / 127.0f;   // (all-zero or vanishing token: as in the quantizer kernels)
             if (a.sx_out != nullptr && blk == 0 && (lane & 3) == 0 && hm < M) a.sx_out[hm] = sxm;
         }
         for (int j = 0; j < my_nt; ++j) {
@@ -502,7 +502,8 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(const GemvArgs args)
         float arow = 0.f;
 #pragma unroll
         for (int w = 0; w < GV_CW; ++w) arow = fmaxf(arow, mx[w * 16 + (lane >> 2)]);
-        q_inv = arow == 0.f ? 0.f : 127.0f / arow;
+        q_inv = 127.0f / arow;
+        if (!(q_inv <= 3.402823466e+38f)) q_inv = 0.f;   // all-zero token, or one so small that 127 / a overflows
     }
 
     // fragments -> operand layout: lane (ln, kb) takes bytes kb*32 .. +32 of row ln, i.e. the

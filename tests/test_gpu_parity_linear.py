@@ -180,3 +180,38 @@ def test_product_is_rounded_before_the_tie_break(lib, oracle):
     Y1 = lib.w4a8_linear(Xd, None, Wp, step, zero, N, G)
     Y2 = lib.w4a8_gemm(q2, sx2, Wp, step, zero, N, K, G)
     assert torch.equal(Y1, Y2)
+
+
+def test_vanishing_tokens_are_quantized_as_all_zero(lib, oracle):
+    """Tokens whose 127 / max|t| (255 / range for the asymmetric form) overflows binary32 -- below about 3.7e-37,
+    reachable from fp32 activations or through a huge AQAS scale -- take the all-zero rule on both sides: scale 1,
+    codes 0; subnormal scales just above that are kept bit for bit."""
+    rng = np.random.default_rng(11)
+    M, K, N, G = 16, 1024, 272, 128
+    scale = np.array([1e-38, 3e-39, 1e-41, 1e-44, 1.0, 1e-30, 6e-8, 1e-45, 1.2e-37, 3.8e-37, 1e-36, 1e-35,
+                      0.0, 2.0, 1e-20, 5e-37], np.float32)
+    X32 = (rng.standard_normal((M, K)).astype(np.float32) * scale[:, None]).astype(np.float32)
+    s = rng.uniform(0.5, 2.0, K).astype(np.float32)
+    ref_q, ref_sx = oracle.quantize_act_int8(X32, s)
+    assert (ref_sx == 1.0).sum() >= 6 and (ref_sx < np.finfo(np.float32).tiny).sum() >= 1   # dead rows, and a subnormal scale that is kept
+    q, sx = lib.quantize_act_int8(dev(X32), dev(s))
+    assert np.array_equal(host(sx).view(np.uint32), ref_sx.view(np.uint32)) and np.array_equal(host(q), ref_q)
+    Q, sa, zx = oracle.quantize_act_uint8_asym(X32, s)
+    qa, sxa, zxa = lib.quantize_act_int8_asym(dev(X32), dev(s))
+    assert np.array_equal(host(sxa).view(np.uint32), sa.view(np.uint32))
+    assert np.array_equal(host(zxa).astype(np.int64) + 128, zx.astype(np.int64))
+    assert np.array_equal(host(qa).astype(np.int16) + 128, Q.astype(np.int16))
+    # fp16 activations with a huge AQAS scale: through both quantizer paths of the layer
+    Xh = (rng.standard_normal((M, K)) * np.where(np.arange(M)[:, None] % 2, 1.0, 1e-3)).astype(np.float16)
+    s_big = np.full(K, 3e38, np.float32)
+    s_big[::3] = 1e35
+    ref_q, ref_sx = oracle.quantize_act_int8(Xh.astype(np.float32), s_big)
+    assert 0 < (ref_sx == 1.0).sum() < M
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    codes, step, zero = lib.quantize_weight_dint4(dev(W), None, G)
+    Wp = lib.pack_dint4(codes, lib.LAYOUT_TILED)
+    Y, Xq, sxl, acc = lib.w4a8_linear(dev(Xh), dev(s_big), Wp, step, zero, N, G, want_quantized=True, want_acc=True)
+    assert np.array_equal(host(sxl).view(np.uint32), ref_sx.view(np.uint32)) and np.array_equal(host(Xq), ref_q)
+    q2, sx2 = lib.quantize_act_int8(dev(Xh), dev(s_big))
+    assert np.array_equal(host(sx2).view(np.uint32), ref_sx.view(np.uint32)) and np.array_equal(host(q2), ref_q)
+    assert torch.isfinite(Y.float()).all()

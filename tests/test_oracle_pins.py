@@ -264,6 +264,31 @@ def test_activation_rounding_is_two_binary32_steps_then_ties_to_even(oracle):
     assert Xq[0].tolist() == [127, 62, 62, -62, 0, 2, 2]
 
 
+def test_vanishing_token_counts_as_all_zero(oracle):
+    """A reading for a case the paper does not treat: when 127 / max|t| is not a finite binary32 number
+    (max|t| = 0, or below 127 / FLT_MAX ~ 3.7e-37) the products t * inv would be inf or nan; such a token
+    is quantized like the all-zero token (scale 1, codes 0).  Just above the threshold the ordinary rule
+    applies; subnormal scales a / 127 are kept."""
+    thr = np.float32(127.0) / np.finfo(np.float32).max            # 3.73e-37
+    K = 64
+    X = np.zeros((6, K), np.float32)
+    X[0, :3] = [1e-38, -3e-39, 2e-40]                             # max below the threshold
+    X[1, :3] = [np.float32(thr) * np.float32(0.999), 1e-40, 0]    # just below
+    X[2, :3] = [np.float32(thr) * np.float32(1.01), -np.float32(thr) * np.float32(0.505), 1e-39]   # just above
+    X[3, :3] = [1e-30, -5e-31, 2.6e-31]                           # small but ordinary: sx = 7.9e-33
+    X[4, :2] = [1e-45, -1e-45]                                    # the smallest subnormals
+    Xq, sx = oracle.quantize_act_int8(X, None)
+    for m in (0, 1, 4, 5):
+        assert sx[m] == 1.0 and not Xq[m].any()
+    assert sx[2] == np.float32(X[2, 0]) / np.float32(127.0) and Xq[2, :3].tolist() == [127, -64, 0]
+    assert sx[3] == np.float32(1e-30) / np.float32(127.0) and Xq[3, :3].tolist() == [127, -64, 33]
+    # the asymmetric form: the same rule on 255 / (hi - lo)
+    Q, sa, zx = oracle.quantize_act_uint8_asym(X, None)
+    for m in (0, 1, 4, 5):
+        assert sa[m] == 1.0 and zx[m] == 0 and not Q[m].any()
+    assert sa[3] == (np.float32(1e-30) + np.float32(5e-31)) / np.float32(255.0) and 0 < zx[3] < 255
+
+
 # ------------------------------------------------------------------ P9 GEMM identities
 @pytest.mark.parametrize("G", [0, 128])
 def test_int_gemm_equals_float64_matmul(oracle, G):
