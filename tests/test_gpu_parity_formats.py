@@ -27,6 +27,7 @@ CASES = [
     ("decode_k_split", 3, 9216, 48, 128),
     ("prefill_per_channel", 300, 768, 1040, 0),
     ("prefill_grouped", 130, 1024, 304, 256),
+    ("prefill_grouped_128_k_phases", 130, 1408, 80, 128),   # the kernel that cuts K into phases inside the workgroup
     ("prefill_64_rows", 40, 512, 256, 128),
 ]
 
