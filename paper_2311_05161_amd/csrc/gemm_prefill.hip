@@ -1029,6 +1029,241 @@ __global__ __launch_bounds__(MD_THREADS, 2) void gemm_mid_kernel(
     }
 }
 
+// The same decomposition for per-channel weights: no group parameters and no rescale per group -- the
+// int32 accumulators run over all of a phase's k-tiles (biased decode, 7 instead of 11 operations per
+// eight weights), the four phases' int32 sums are added exactly through LDS, and the phase-0 waves remove
+// the decode bias with the token's row-sum (rs[m], from rowsum_kernel), scale and store.
+// A super-step of this kernel is short (8 MFMAs per wave), far shorter than the time a copy of
+// activations needs to arrive when every workgroup asks for the same k-tiles at the same moment, so the
+// tile is 64 tokens (8 KB per k-tile) and LDS holds FOUR super-steps: the copies of super-step ss + 3 are
+// issued during ss.  Every memory access of the loop is issued by hand (the copies, and the weight
+// loads as plain buffer loads into registers), in a fixed order, so that one explicit wait per
+// super-step is exact: at its end everything up to the copies of ss + 1 must have landed, and the
+// accesses issued after those are 2 + 4 + 2 + 4 + 2 = 14 (weights of ss + 2, copies of ss + 2, weights of
+// ss + 3, copies of ss + 3, weights of ss + 4).
+constexpr int MP_BM = 64, MP_RING = 4;
+constexpr int MP_TILE = MP_BM * TILE_K;   // 8 KB
+
+__device__ __forceinline__ void load_b128_by_hand(v4u &dst, v4i rsrc, int voff, int soff)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(dst) : "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
+template <bool ACC_OUT>
+__global__ __launch_bounds__(MD_THREADS, 2) void gemm_mid_pc_kernel(
+    const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ rs, int M,
+    const uint8_t *__restrict__ Wt, const float *__restrict__ step, const uint8_t *__restrict__ zero, int N,
+    int K, uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store, int32_t *__restrict__ acc_out,
+    int grid_m, int plain)
+{
+    constexpr int MS = MP_BM / 32;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];   // [MP_RING * MD_KQ][MP_TILE]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1;      // channel half
+    const int kq = wave >> 1;     // K phase
+    const int r32 = lane & 31;
+    const int kh = lane >> 5;
+    const int KT = K / TILE_K;
+    const int SS = (KT + MD_KQ - 1) / MD_KQ;
+    const int bm = blockIdx.x % grid_m, bn = blockIdx.x / grid_m;
+    const int m0 = bm * MP_BM;
+    const int nb0 = bn * MD_BN;
+    const int n0 = nb0 + wn * 32;
+
+    const uint64_t wt_addr = (uint64_t)Wt;
+    const v4i rwv = {(int)(uint32_t)wt_addr, (int)((wt_addr >> 32) & 0xffffu), (int)((int64_t)N * K / 2), 0x00020000};
+    const uint64_t xq_addr = (uint64_t)Xq;
+    const v4i rx = {(int)(uint32_t)xq_addr, (int)((xq_addr >> 32) & 0xffffu), (int)((int64_t)M * K), 0x00020000};
+
+    // the decode table of this lane's channel (one zero-point for all of K); loaded before anything is
+    // issued by hand, so that the compiler's wait for it covers nothing else
+    const bool lane_ok = n0 + r32 < N;
+    const DecodeLut lut = make_decode_lut(zero[lane_ok ? n0 + r32 : 0], plain != 0);
+
+    const int wvoff = lane_ok ? (r32 >> 4) * KT * TILE_BYTES + ((r32 & 15) + 16 * kh) * 16 : GM_OOB;
+    const int wsoff = n0 < N ? (n0 / TILE_N) * KT * TILE_BYTES : 0;
+    auto load_b = [&](int kt, v4u(&dst)[2]) {
+        const int ktc = min(kt, KT - 1);
+        load_b128_by_hand(dst[0], rwv, wvoff, wsoff + ktc * TILE_BYTES);
+        load_b128_by_hand(dst[1], rwv, wvoff + 512, wsoff + ktc * TILE_BYTES);
+    };
+    // activation k-tile (64 rows) -> LDS slot: 8 blocks of 8 rows, one per wave (swizzle as in gemm_kernel)
+    const int arow = wave * 8 + (lane >> 3);
+    const int avoff = (m0 + arow) * K + (((lane & 7) ^ ((arow >> 1) & 7)) << 4);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_raw;
+    auto dma_one = [&](int ss, int j) {   // this wave's block of k-tile j of super-step ss
+        const int kt = min(ss * MD_KQ + j, KT - 1);
+        const int slot = (ss & (MP_RING - 1)) * MD_KQ + j;
+        dma_b128(rx, avoff, kt * TILE_K, lds_base + (uint32_t)(slot * MP_TILE + wave * 1024));
+    };
+
+    v16i acc[MS];
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ms][r] = 0;
+
+    int frag_off[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int chunk = 2 * (2 * (s4 >> 1) + kh) + (s4 & 1);
+        frag_off[s4] = r32 * TILE_K + ((chunk ^ ((r32 >> 1) & 7)) << 4);
+    }
+    auto read_a = [&](int slot, int s4, v4i(&dst)[MS]) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+            dst[ms] = *reinterpret_cast<const v4i *>(&lds_raw[slot * MP_TILE + ms * (32 * TILE_K) + frag_off[s4]]);
+    };
+    auto decode_step = [&](const v4u(&pk)[2], int s4, v4i &dst) {
+        const int sp = s4 >> 1, h = s4 & 1;
+        const uint32_t q0 = h ? pk[sp].z : pk[sp].x;
+        const uint32_t q1 = h ? pk[sp].w : pk[sp].y;
+        int a, b, c, d;
+        decode_word(q0, lut, a, b);
+        decode_word(q1, lut, c, d);
+        dst = v4i{a, b, c, d};
+    };
+
+    // ---- prologue, in the order the loop continues: copies of super-steps 0, 1, 2 and the weights of this
+    // wave's first four k-tiles (every access unconditional: k-tiles past the end are clamped)
+    v4u pw[4][2];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (the zero-point above)
+#pragma unroll
+    for (int j = 0; j < MD_KQ; ++j) dma_one(0, j);
+    load_b(kq, pw[0]);
+    load_b(MD_KQ + kq, pw[1]);
+#pragma unroll
+    for (int j = 0; j < MD_KQ; ++j) dma_one(1, j);
+    load_b(2 * MD_KQ + kq, pw[2]);
+#pragma unroll
+    for (int j = 0; j < MD_KQ; ++j) dma_one(2, j);
+    load_b(3 * MD_KQ + kq, pw[3]);
+    // super-step 0's copies and weights: everything but the 4 + 2 + 4 + 2 + 2 accesses issued behind them
+    // (weights of 1 were issued together with those of 0: waited for as well)
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(pw[0][0]), "+v"(pw[0][1]), "+v"(pw[1][0]), "+v"(pw[1][1]) :: "memory");
+    __syncthreads();
+
+    // One super-step: k-tile kt = 4 ss + q from slot (ss mod 4, q); P: its packed weights (complete since
+    // the previous super-step's wait), refilled at the end for ss + 4; PN: the next super-step's.
+    auto super_step = [&](v4u(&P)[2], v4u(&PN)[2], int ss, bool drain) __attribute__((always_inline)) {
+        const int kt = ss * MD_KQ + kq;
+        const int slot = (ss & (MP_RING - 1)) * MD_KQ + kq;
+        if (kt < KT) {   // (uniform over the wave; live k-tiles come first)
+            v4i af[2][MS], w[2];
+            read_a(slot, 0, af[0]);
+            decode_step(P, 0, w[0]);
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                if (s4 < 3) {
+                    read_a(slot, s4 + 1, af[(s4 + 1) & 1]);
+                    decode_step(P, s4 + 1, w[(s4 + 1) & 1]);
+                }
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+                    acc[ms] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[s4 & 1], af[s4 & 1][ms], acc[ms], 0, 0, 0);
+                dma_one(ss + 3, s4);   // (the slots of ss + 3 = those of ss - 1: freed by the last barrier)
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < MD_KQ; ++j) dma_one(ss + 3, j);
+        }
+        // (P's last read, by the decode above, comes before its refill: both are pinned in program order)
+        asm volatile("" : "+v"(P[0]), "+v"(P[1]) :: "memory");
+        load_b((ss + 4) * MD_KQ + kq, P);
+        // (the waits name no register: a choice between two statements that do would make the compiler
+        // merge register sets behind them, with copies; the use of PN that follows is what keeps the
+        // next super-step's decode behind the wait)
+        if (drain) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the loop's last super-step
+        else asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+        asm volatile("" : "+v"(PN[0]), "+v"(PN[1]) :: "memory");
+        __syncthreads();
+    };
+    // The loop body is four super-steps (the four weight register sets take turns without copies) and is
+    // the ONLY code between the prologue and the reduction: super-steps past the last one have no live
+    // k-tile and only keep the order of the accesses (clamped copies and loads).  A separate tail would
+    // have the compiler move the weight registers between their homes of the loop and those of the tail
+    // while loads that it cannot see are still writing them.  For the same reason the loop's last
+    // super-step waits for everything: behind the loop no register or LDS slot has a load on its way.
+    for (int ss = 0; ss < SS; ss += 4) {
+        super_step(pw[0], pw[1], ss, false);
+        super_step(pw[1], pw[2], ss + 1, false);
+        super_step(pw[2], pw[3], ss + 2, false);
+        super_step(pw[3], pw[0], ss + 3, ss + 4 >= SS);
+    }
+
+    // ---- the four phases' int32 sums meet in LDS (exact: the order does not matter)
+    int *red = reinterpret_cast<int *>(lds_raw);   // [..][64 lanes][32 ints], 8 KB per wave
+    auto red_ptr = [&](int slot) { return red + ((size_t)slot * 64 + lane) * (MS * 16); };
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int r = 0; r < 16; r += 4)
+                *reinterpret_cast<v4i *>(red_ptr(slot) + ((ms * 16 + r) ^ ((lane & 7) << 2))) =
+                    v4i{acc[ms][r], acc[ms][r + 1], acc[ms][r + 2], acc[ms][r + 3]};
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) {
+                const v4i t = *reinterpret_cast<const v4i *>(red_ptr(slot) + ((ms * 16 + r) ^ ((lane & 7) << 2)));
+                acc[ms][r] += t.x; acc[ms][r + 1] += t.y; acc[ms][r + 2] += t.z; acc[ms][r + 3] += t.w;
+            }
+    };
+    if (kq & 1) put((kq >> 1) * 2 + wn);
+    __syncthreads();
+    if (!(kq & 1)) add((kq >> 1) * 2 + wn);
+    __syncthreads();
+    if (kq == 2) put(wn);
+    __syncthreads();
+    if (kq != 0) return;
+    add(wn);
+
+    // ---- epilogue (phase-0 waves): remove the decode bias, scale, store
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int nn = nb0 + wn * 32 + 8 * b + 4 * kh;
+        if (nn >= N) continue;   // (N % 16 == 0: four channels are valid together)
+        float es[4];
+        int nbq[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int z = zero[nn + r];
+            es[r] = step[nn + r] * 0.125f;
+            nbq[r] = -(8 * z + ((~z & 1) << 2));   // - 4 beta
+        }
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) {
+            const int m = m0 + ms * 32 + r32;
+            if (m >= M) continue;
+            const float sxm = sx[m];
+            const int rsm = rs[m];
+            uint16_t hh[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // 4 sum Xq d = acc - 4 beta * rowsum (exact; 24-bit multiply: 4 beta <= 124, |row-sum| <= 2^23)
+                const int v = __mul24(nbq[r], rsm) + acc[ms][4 * b + r];
+                if (ACC_OUT) acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                float out = sxm * (es[r] * (float)v);   // binary32 products, then the cast (see gemm_kernel)
+                asm volatile("" : "+v"(out));
+                hh[r] = (y_dtype == W4A8_F16) ? f32_to_f16_bits(out) : f32_to_bf16_bits(out);
+            }
+            uint16_t *yp = Y + (int64_t)m * ldy + nn;
+            if (vec_store & 1) {
+                *reinterpret_cast<uint2 *>(yp) = make_uint2((uint32_t)hh[0] | ((uint32_t)hh[1] << 16),
+                                                            (uint32_t)hh[2] | ((uint32_t)hh[3] << 16));
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) yp[r] = hh[r];
+            }
+        }
+    }
+}
+
 // Whether a shape takes gemm_mid_kernel: 128-wide groups, symmetric activations, 65 .. 256 tokens, and a
 // grid of at most one workgroup per CU.  Measured against the tile kernel with K cut into ranges (which
 // is what these shapes would otherwise run): ahead wherever the grid covers at least half the CUs
@@ -1063,6 +1298,41 @@ static int launch_gemm_mid(const int8_t *Xq, const float *sx, int64_t M, const u
     if (acc_out) W4A8_MD(true);
     else W4A8_MD(false);
 #undef W4A8_MD
+    return hip_status(hipGetLastError());
+}
+
+// The per-channel variant (gemm_mid_pc_kernel), same token range and grid condition.
+bool gemm_mid_pc_applies(int64_t M, int64_t N, int64_t K, int64_t G, bool asym)
+{
+    if (asym || G != K || M <= 64 || M > 256) return false;
+    const int64_t wgs = (M + MP_BM - 1) / MP_BM * ((N + MD_BN - 1) / MD_BN);
+    const int64_t KT = K / TILE_K;
+    return KT >= 8 && wgs <= 256;
+}
+
+static int launch_gemm_mid_pc(const int8_t *Xq, const float *sx, int32_t *rs, int64_t M, const uint8_t *Wt,
+                              const float *step, const uint8_t *zero, int64_t N, int64_t K, void *Y, int y_dtype,
+                              int64_t ldy, int32_t *acc_out, hipStream_t st, int plain)
+{
+    // the tokens' row-sums over all of K (bias removal in the epilogue)
+    hipLaunchKernelGGL(rowsum_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, Xq, M, (int)K, 1, (int)K, rs);
+    if (hipGetLastError() != hipSuccess) return W4A8_ERR_HIP;
+    const int grid_m = (int)((M + MP_BM - 1) / MP_BM);
+    const int grid_n = (int)((N + MD_BN - 1) / MD_BN);
+    const int vec_store = (((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0)) ? 1 : 0;
+    constexpr int lds_bytes = MP_RING * MD_KQ * MP_TILE;   // 128 KB
+#define W4A8_MDP(AO_)                                                                                     \
+    do {                                                                                                  \
+        static std::atomic<uint64_t> lds_opted{0};                                                        \
+        if (opt_in_dynamic_lds((const void *)gemm_mid_pc_kernel<AO_>, lds_bytes, lds_opted) != W4A8_OK)   \
+            return W4A8_ERR_HIP;                                                                          \
+        hipLaunchKernelGGL((gemm_mid_pc_kernel<AO_>), dim3((unsigned)(grid_m * grid_n)), dim3(MD_THREADS), \
+                           lds_bytes, st, Xq, sx, rs, (int)M, Wt, step, zero, (int)N, (int)K, (uint16_t *)Y, \
+                           y_dtype, ldy, vec_store, acc_out, grid_m, plain);                              \
+    } while (0)
+    if (acc_out) W4A8_MDP(true);
+    else W4A8_MDP(false);
+#undef W4A8_MDP
     return hip_status(hipGetLastError());
 }
 
@@ -1120,6 +1390,8 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
         return W4A8_ERR_SHAPE;
     if (gemm_mid_applies(M, N, K, G, zp.zx != nullptr))
         return launch_gemm_mid(Xq, sx, M, Wt, step, zero, N, K, Y, y_dtype, ldy, acc_out, st, plain);
+    if (gemm_mid_pc_applies(M, N, K, G, zp.zx != nullptr))
+        return launch_gemm_mid_pc(Xq, sx, rs, M, Wt, step, zero, N, K, Y, y_dtype, ldy, acc_out, st, plain);
     const GemmPlan pl = plan_gemm(M, N, K, G);
     if (!grouped) {
         const int64_t segs = M * pl.splits;

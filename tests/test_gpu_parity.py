@@ -198,6 +198,11 @@ PREFILL_CASES = [
     ("m256_k_phases_18_ktiles_g128", 256, 2304, 1040, 128),
     ("m129_k_phases_two_super_steps_g128", 129, 1024, 64, 128),
     ("m200_k_phases_40_ktiles_g128", 200, 5120, 336, 128),
+    # the same decomposition for per-channel weights (int32 phase sums, bias removal with the row-sums)
+    ("m130_k_phases_11_ktiles_per_channel", 130, 1408, 80, 0),
+    ("m256_k_phases_18_ktiles_per_channel", 256, 2304, 1040, 0),
+    ("m129_k_phases_two_super_steps_per_channel", 129, 1024, 64, 0),
+    ("m200_k_phases_86_ktiles_per_channel", 200, 11008, 336, 0),
     ("m300", 300, 768, 1040, 0),
     ("m300_g256", 300, 768, 512, 256),
     ("m600_multi_block", 600, 1024, 784, 0),
@@ -225,9 +230,10 @@ K_PHASE_EDGES = [(129 + 9 * kt, 128 * kt, 16 * (1 + kt % 7)) for kt in range(8, 
     (256, 1024, 64), (255, 1152, 4096 + 16), (129, 6144, 48), (65, 6400, 8192), (128, 6400, 8192 + 64)]
 
 
+@pytest.mark.parametrize("G", [128, 0])
 @pytest.mark.parametrize("M,K,N", K_PHASE_EDGES)
-def test_gemm_k_phase_kernel_edges(lib, oracle, M, K, N):
-    _gemm_case(lib, oracle, M + K + N, M, K, N, 128)
+def test_gemm_k_phase_kernel_edges(lib, oracle, M, K, N, G):
+    _gemm_case(lib, oracle, M + K + N + G, M, K, N, G)
 
 
 def test_gemm_bf16_output_and_canonical_layout(lib, oracle):

@@ -112,11 +112,14 @@ EXACT_CASES = [
     ("tile_128_rows_group256_ragged", 270, 1024, 400, 256),
     ("tile_128_rows_group128_many_tiles", 1100, 512, 4112, 128),
     ("tile_k_ranges_group256", 130, 2048, 304, 256),
-    ("tile_k_ranges_per_channel", 200, 2048, 304, 0),
+    ("tile_k_ranges_per_channel", 300, 2048, 304, 0),
     # K in four phases inside the workgroup (group-128, 129 .. 256 tokens, few output tiles)
     ("k_phases_group128", 130, 2048, 304, 128),
     ("k_phases_group128_ragged_last_super_step", 256, 2816, 1040, 128),
     ("k_phases_group128_40_ktiles", 130, 5120, 1040, 128),
+    ("k_phases_per_channel", 130, 2048, 304, 0),
+    ("k_phases_per_channel_ragged_last_super_step", 256, 2816, 1040, 0),
+    ("k_phases_per_channel_86_ktiles", 200, 11008, 336, 0),
 ]
 
 
