@@ -107,14 +107,16 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const int8_t *__restrict__ 
 // WM wave rows x WN wave columns (8 waves for BM >= 128: every SIMD hosts two, so one wave's
 // MFMAs cover the other's LDS and decode latency); a wave owns BM / WM token rows of 256 / WN output
 // channels.  WN = 4 (64 channels per wave) suits the per-channel kernel; group-wise weights take
-// WN = 8, WM = 1 (128 tokens x 32 channels per wave): every decoded weight then feeds twice as
-// many MFMAs, and instruction issue -- decode plus the per-group rescale -- is what bounds them.
+// 128 tokens x 32 channels per wave: every decoded weight then feeds twice as many MFMAs, and
+// instruction issue -- decode plus the per-group rescale -- is what bounds them.  BN is the tile's
+// width in channels: 256, or 128 for the group-wise 128-token tile (WM = 1, WN = 4, two workgroups
+// per CU that share no barrier).
 // Token zero-points zx (asymmetric activations; codes and zx stored offset by -128): the exact
 // term zx * (sum of the weights) leaves the int32 accumulators before any floating-point step --
 // per group in the flush (GROUPED; its own instances, ASYM) or once in the epilogue (!GROUPED,
 // decided at run time by zx != null).
-template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TWO>
-__global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
+template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TWO, int BN>
+__global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : (BN < GM_BN ? 2 : 1)) void gemm_kernel(
     const int8_t *__restrict__ Xq, const float *__restrict__ sx, const int32_t *__restrict__ zx,
     const int32_t *__restrict__ wsum, const int32_t *__restrict__ tsum,
     const int32_t *__restrict__ rs, int M,
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     float *__restrict__ partial, int plain)
 {
     constexpr int GM_THREADS = WM * WN * 64;
-    constexpr int GM_NS = GM_BN / (WN * 32);       // 32-channel sub-tiles per wave
+    constexpr int GM_NS = BN / (WN * 32);       // 32-channel sub-tiles per wave
     constexpr int WROWS = BM / WM;                 // token rows per wave
     constexpr int MS = WROWS / 32;                 // 32-token sub-tiles per wave
     constexpr int NW = WM * WN;                    // waves
@@ -133,9 +135,9 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     uint8_t(*lds)[BM * TILE_K] = reinterpret_cast<uint8_t(*)[BM * TILE_K]>(lds_raw);   // [GM_RING][BM * 128]
     // group-wise weights: step / 8 and zero-point of the workgroup's 256 channels, a ring of four groups
-    __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 4 : 1][GROUPED ? GM_BN : 4];
-    __shared__ int s_gz[GROUPED ? 4 : 1][GROUPED ? GM_BN : 4];
-    __shared__ __attribute__((aligned(16))) int s_gw[GROUPED && ASYM ? 4 : 1][GROUPED && ASYM ? GM_BN : 4];
+    __shared__ __attribute__((aligned(16))) float s_ges[GROUPED ? 4 : 1][GROUPED ? BN : 4];
+    __shared__ int s_gz[GROUPED ? 4 : 1][GROUPED ? BN : 4];
+    __shared__ __attribute__((aligned(16))) int s_gw[GROUPED && ASYM ? 4 : 1][GROUPED && ASYM ? BN : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     const int bn = pr / ph;
     const int bm = panel * GM_PANEL + pr - bn * ph;
     const int m0 = bm * BM;
-    const int nb0 = bn * GM_BN;                        // first output channel of the workgroup
+    const int nb0 = bn * BN;                        // first output channel of the workgroup
     const int wn = wave % WN;                          // wave column
     const int wr0 = (wave / WN) * WROWS;               // first token row of this wave within the tile
     const int n0 = nb0 + wn * (GM_NS * 32);            // first output channel of this wave
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     float gp_es = 0.f;
     int gp_z = 0, gp_w = 0;
     auto fetch_group = [&](int g) {
-        if (tid < GM_BN) {
+        if (tid < BN) {
             const int nn = nb0 + tid < N ? nb0 + tid : 0;
             gp_es = step[(int64_t)nn * ng + g] * 0.125f;
             gp_z = zero[(int64_t)nn * ng + g];
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
         }
     };
     auto publish_group = [&](int g) {
-        if (tid < GM_BN) {
+        if (tid < BN) {
             s_ges[g & 3][tid] = gp_es;
             s_gz[g & 3][tid] = gp_z;
             if (ASYM) s_gw[g & 3][tid] = gp_w;
@@ -509,11 +511,11 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     }
 
     // epilogue parameters of the workgroup's 256 channels
-    __shared__ __attribute__((aligned(16))) int s_epi[3 * GM_BN];
+    __shared__ __attribute__((aligned(16))) int s_epi[3 * BN];
     float *s_es = reinterpret_cast<float *>(&s_epi[0]);           // step / 8
-    int *s_bq = &s_epi[GM_BN];                                    // 4 beta
+    int *s_bq = &s_epi[BN];                                    // 4 beta
     if (!GROUPED) {
-        if (tid < GM_BN) {
+        if (tid < BN) {
             const int nn = nb0 + tid < N ? nb0 + tid : 0;
             const int z = zero[(int64_t)nn * ng];
             s_es[tid] = step[(int64_t)nn * ng] * 0.125f;
@@ -523,9 +525,9 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     }
     // per-channel weights with token zero-points: sums of each channel's weights over this
     // workgroup's K-range (all of K: the group sum; a K-split: its k-tiles added up)
-    int *s_w = &s_epi[2 * GM_BN];
+    int *s_w = &s_epi[2 * BN];
     if (asym) {
-        if (tid < GM_BN) {
+        if (tid < BN) {
             const int nn = nb0 + tid < N ? nb0 + tid : 0;
             int w = 0;
             if (partial == nullptr) {
@@ -548,7 +550,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     // channel parameters of four outputs come with one 16-byte LDS read, reused over the wave's
     // token blocks: as a single loop with those decisions per element the compiler produced one
     // LDS read, one wait and several branches per output (17 us per 256 x 256 tile).
-    uint8_t *ytile = lds_raw;                                         // [BM][512]
+    uint8_t *ytile = lds_raw;                                         // [BM][2 BN]
     enum { TO_PARTIAL = 0, TO_TILE = 1, TO_Y = 2 };
     auto epilogue = [&](auto f16_tag, auto dest_tag, auto full_tag, auto zp_tag) __attribute__((always_inline)) {
         constexpr bool F16 = decltype(f16_tag)::value;
@@ -613,7 +615,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
                     if (DEST == TO_TILE) {
                         const int rl = wr0 + ms * 32 + r32;   // row within the tile
                         const int c8 = nl >> 2;               // 8-byte column within the row
-                        *reinterpret_cast<uint2 *>(ytile + rl * 512 +
+                        *reinterpret_cast<uint2 *>(ytile + rl * (2 * BN) +
                                                    ((((c8 >> 1) ^ (rl & 15)) << 4) | ((c8 & 1) << 3))) = h4;
                     } else if (row_ok) {
                         uint16_t *yp = Y + (int64_t)m * ldy + nn;
@@ -630,7 +632,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     };
     using std::integral_constant;
     const bool staged = partial == nullptr && (vec_store & 2) != 0;   // uniform
-    const bool full = m0 + BM <= M && nb0 + GM_BN <= N;                // uniform
+    const bool full = m0 + BM <= M && nb0 + BN <= N;                // uniform
     auto epilogue_zp = [&](auto f16_tag, auto dest_tag, auto full_tag) __attribute__((always_inline)) {
         if (asym) epilogue(f16_tag, dest_tag, full_tag, integral_constant<bool, true>{});
         else epilogue(f16_tag, dest_tag, full_tag, integral_constant<bool, false>{});
@@ -651,11 +653,13 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     if (staged) {
         __syncthreads();
         constexpr int NWV = WM * WN;
-        for (int r = wave * 2 + (lane >> 5); r < BM; r += NWV * 2) {
-            const int c16 = lane & 31;
+        constexpr int LPR = BN / 8;       // lanes per row of the tile (16 bytes each)
+        constexpr int RPW = 64 / LPR;     // rows per wave and store instruction
+        for (int r = wave * RPW + lane / LPR; r < BM; r += NWV * RPW) {
+            const int c16 = lane % LPR;
             const int m = m0 + r, nn = nb0 + c16 * 8;
             if (m < M && nn < N) {
-                const v4u v = *reinterpret_cast<const v4u *>(ytile + r * 512 + ((c16 ^ (r & 15)) << 4));
+                const v4u v = *reinterpret_cast<const v4u *>(ytile + r * (2 * BN) + ((c16 ^ (r & 15)) << 4));
                 // (streaming stores: nobody in this launch reads Y, and the caches are what serves the
                 // re-reads of the activations and weights by the other tiles)
                 __builtin_nontemporal_store(v, reinterpret_cast<v4u *>(Y + (int64_t)m * ldy + nn));
@@ -664,24 +668,24 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : 1) void gemm_kernel(
     }
 }
 
-template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TWO>
+template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TWO, int BN>
 static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                           const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                           const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
                           int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain)
 {
     const int grid_m = (int)((M + BM - 1) / BM);
-    const int grid_n = (int)((N + GM_BN - 1) / GM_BN);
+    const int grid_n = (int)((N + BN - 1) / BN);
     // bit 0: 8-byte stores of four outputs are aligned; bit 1: 16-byte stores of eight are
     const int vec_store = ((((uintptr_t)Y % 8 == 0) && (ldy % 4 == 0)) ? 1 : 0) |
                           ((((uintptr_t)Y % 16 == 0) && (ldy % 8 == 0)) ? 2 : 0);
     constexpr int lds_bytes = GM_RING * BM * TILE_K;
     static std::atomic<uint64_t> lds_opted{0};
     if (lds_bytes > 48 * 1024 &&
-        opt_in_dynamic_lds((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>, lds_bytes,
+        opt_in_dynamic_lds((const void *)gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO, BN>, lds_bytes,
                            lds_opted) != W4A8_OK)
         return W4A8_ERR_HIP;
-    hipLaunchKernelGGL((gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO>),
+    hipLaunchKernelGGL((gemm_kernel<BM, WM, WN, GROUPED, ACC_OUT, ASYM, TWO, BN>),
                        dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * WN * 64), lds_bytes, st,
                        Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,
                        (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
@@ -689,7 +693,7 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
     return hip_status(hipGetLastError());
 }
 
-template <int BM, int WM, int WN, bool GROUPED, bool TWO = false>
+template <int BM, int WM, int WN, bool GROUPED, bool TWO = false, int BN = GM_BN>
 static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                          const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                          const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
@@ -698,7 +702,7 @@ static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, 
     // The accumulator test hook is a separate instance so that the fast path carries none of it;
     // so is the per-group zero-point term of group-wise weights.
 #define W4A8_GM2(AO_, AS_)                                                                       \
-    return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_, TWO>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
+    return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_, TWO, BN>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
                                                      G, Y, y_dtype, ldy, acc_out, partial, st, plain)
     if (GROUPED && zp.zx != nullptr) {
         if (acc_out) W4A8_GM2(true, GROUPED);
@@ -1358,14 +1362,15 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
         pl.bm = rounds128 < 0.95 * rounds256 ? 128 : 256;
     }
     // too few output tiles for 256 CUs: split K as well (whole groups, at least 4 k-tiles each)
-    const int64_t tiles = (M + pl.bm - 1) / pl.bm * gn;
+    const bool half = grouped && pl.bm == 128;   // 128-channel tiles, two workgroups per CU
+    const int64_t tiles = (M + pl.bm - 1) / pl.bm * (half ? (N + 127) / 128 : gn);
     const int KT = (int)(K / TILE_K), tpg = (int)(G / TILE_K);
     pl.splits = 1;
     pl.kt_per_split = KT;
-    if (tiles < 128 && KT >= 8) {
+    if (tiles < (half ? 256 : 128) && KT >= 8) {
         // (rounded down: a few workgroups beyond 256 make a second generation that costs as much as
         // the first)
-        const int want = (int)(256 / tiles);
+        const int want = (int)((half ? 512 : 256) / tiles);
         int unit = grouped ? tpg : 1;           // k-tiles that must stay together
         while (unit < 4) unit += grouped ? tpg : 1;
         int kps = (KT + want - 1) / want;
@@ -1406,8 +1411,13 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
     // more workgroups than CUs: the 128-token per-channel tile in its two-per-CU form
     const int64_t wgs = (M + pl.bm - 1) / pl.bm * ((N + GM_BN - 1) / GM_BN) * pl.splits;
     if (grouped) {
+        // 128-token group-wise tiles are 128 channels wide, four waves of 128 x 32, two workgroups per CU:
+        // the same two waves per SIMD as one 256-channel workgroup, but from workgroups that do not share
+        // a barrier, so that one's rescale (vector ALU only) drifts under the other's MFMAs
         if (pl.bm == 64) W4A8_GM(64, 1, 4, true, false);
-        else W4A8_GM(128, 1, 8, true, false);
+        else
+            rc = launch_gemm_t<128, 1, 4, true, false, 128>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype,
+                                                            ldy, acc_out, partial, st, plain);
     } else {
         if (pl.bm == 128 && wgs > 256) W4A8_GM(128, 1, 8, false, true);
         else if (pl.bm == 128) W4A8_GM(128, 1, 8, false, false);
