@@ -24,6 +24,7 @@
 // When the output has too few tiles to occupy 256 CUs (mid-size M) K is cut into ranges as well:
 // each workgroup writes an fp32 partial of its range and a small kernel adds the ranges in a fixed
 // order, applies the token scale and casts (deterministic; the int32 hook uses exact atomic adds).
+#include <algorithm>
 #include <type_traits>
 
 #include "w4a8_common.hpp"
@@ -124,8 +125,10 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : (BN < GM_BN ? 2 : 1)) void 
     const uint8_t *__restrict__ zero, int N, int K, int tiles_per_group, int ng,
     uint16_t *__restrict__ Y, int y_dtype, int64_t ldy, int vec_store,
     int32_t *__restrict__ acc_out, int grid_m, int grid_n, int kt_per_split,
-    float *__restrict__ partial, int plain)
+    float *__restrict__ partial, int plain, int acc_ld)
 {
+    // (acc_ld: channels per token row of acc_out -- N, or the whole layer's when this launch covers a
+    // range of its channels)
     constexpr int GM_THREADS = WM * WN * 64;
     constexpr int GM_NS = BN / (WN * 32);       // 32-channel sub-tiles per wave
     constexpr int WROWS = BM / WM;                 // token rows per wave
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : (BN < GM_BN ? 2 : 1)) void 
                         yr = __builtin_fmaf(es[r], (float)vz, yr);
                         if (ACC_OUT && m < M) {
                             const int nn = nb0 + nl + r;
-                            if (nn < N) acc_out[((int64_t)m * N + nn) * ng + g] = v >> 2;
+                            if (nn < N) acc_out[((int64_t)m * acc_ld + nn) * ng + g] = v >> 2;
                         }
                     }
                 }
@@ -591,8 +594,8 @@ __global__ __launch_bounds__(WM * WN * 64, TWO ? 4 : (BN < GM_BN ? 2 : 1)) void 
                             // (24-bit multiplies: 4 beta <= 124, |row-sum| <= 2^23, |weight sum| < 2^23)
                             int v = __mul24(nbq4[r], rs_a[ms]) + acc[ms][ns][4 * b + r];
                             if (ACC_OUT && row_ok) {
-                                if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * N + nn + r], v >> 2);
-                                else acc_out[(int64_t)m * N + nn + r] = v >> 2;
+                                if (partial != nullptr) atomicAdd(&acc_out[(int64_t)m * acc_ld + nn + r], v >> 2);
+                                else acc_out[(int64_t)m * acc_ld + nn + r] = v >> 2;
                             }
                             // (the accumulator hook keeps the raw sum)
                             if (ZP) v = __mul24(nzx4_a[ms], sw4[r]) + v;
@@ -672,7 +675,7 @@ template <int BM, int WM, int WN, bool GROUPED, bool ACC_OUT, bool ASYM, bool TW
 static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                           const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                           const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                          int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain)
+                          int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain, int64_t acc_ld)
 {
     const int grid_m = (int)((M + BM - 1) / BM);
     const int grid_n = (int)((N + BN - 1) / BN);
@@ -689,7 +692,8 @@ static int launch_gemm_t2(const GemmPlan &pl, const int8_t *Xq, const float *sx,
                        dim3((unsigned)(grid_m * grid_n * pl.splits)), dim3(WM * WN * 64), lds_bytes, st,
                        Xq, sx, zp.zx, zp.wsum, zp.tsum, rs, (int)M, Wt, step, zero, (int)N, (int)K,
                        (int)(G / TILE_K), (int)(K / G), (uint16_t *)Y, y_dtype, ldy, vec_store,
-                       acc_out, grid_m, grid_n, pl.kt_per_split, pl.splits > 1 ? partial : nullptr, plain);
+                       acc_out, grid_m, grid_n, pl.kt_per_split, pl.splits > 1 ? partial : nullptr, plain,
+                       (int)(acc_ld > 0 ? acc_ld : N));
     return hip_status(hipGetLastError());
 }
 
@@ -697,13 +701,14 @@ template <int BM, int WM, int WN, bool GROUPED, bool TWO = false, int BN = GM_BN
 static int launch_gemm_t(const GemmPlan &pl, const int8_t *Xq, const float *sx, ZeroPoint zp,
                          const int32_t *rs, int64_t M, const uint8_t *Wt, const float *step,
                          const uint8_t *zero, int64_t N, int64_t K, int64_t G, void *Y, int y_dtype,
-                         int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain)
+                         int64_t ldy, int32_t *acc_out, float *partial, hipStream_t st, int plain,
+                         int64_t acc_ld = 0)
 {
     // The accumulator test hook is a separate instance so that the fast path carries none of it;
     // so is the per-group zero-point term of group-wise weights.
 #define W4A8_GM2(AO_, AS_)                                                                       \
     return launch_gemm_t2<BM, WM, WN, GROUPED, AO_, AS_, TWO, BN>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, \
-                                                     G, Y, y_dtype, ldy, acc_out, partial, st, plain)
+                                                     G, Y, y_dtype, ldy, acc_out, partial, st, plain, acc_ld)
     if (GROUPED && zp.zx != nullptr) {
         if (acc_out) W4A8_GM2(true, GROUPED);
         W4A8_GM2(false, GROUPED);
@@ -1382,6 +1387,33 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G)
     }
     pl.rs_bytes = grouped ? 0 : (size_t)pl.splits * M * sizeof(int32_t);
     pl.partial_bytes = pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
+    // More than one round of 512 resident 128 x 128 tiles with the last round at most half full: a round
+    // costs the same however full it is, so the channels of the last round become a launch of their own
+    // with K cut into ranges over (about) 512 workgroups, and a combine pass over that slice of Y.
+    // (Per-channel layers do not gain: their rounds are short against the partial sums' traffic.)
+    if (half && pl.splits == 1 && tiles > 512) {
+        const int64_t gm = (M + 127) / 128, gn128 = (N + 127) / 128;
+        const int64_t gn_main = tiles / 512 * 512 / gm;   // whole channel tiles that fill whole rounds
+        const int64_t rem_tiles = (gn128 - gn_main) * gm;
+        int unit = tpg;
+        while (unit < 4) unit += tpg;
+        // (measured: it pays where a round is long against the two extra launches and the partial sums --
+        // K >= 5120 with the last round under a third full, K >= 10240 with it up to half full;
+        // at K = 2048 it costs 20 %)
+        const bool pays = (KT >= 40 && rem_tiles <= 160) || (KT >= 80 && rem_tiles <= 256);
+        if (gn_main > 0 && rem_tiles > 0 && pays && KT >= 2 * unit) {
+            const int want = (int)std::min<int64_t>(512 / rem_tiles, 4);
+            int kps = (KT + want - 1) / want;
+            kps = (kps + unit - 1) / unit * unit;
+            const int sp = (KT + kps - 1) / kps;
+            if (sp >= 2) {
+                pl.rem_n = (int)(N - gn_main * 128);
+                pl.rem_splits = sp;
+                pl.rem_kt_per_split = kps;
+                pl.partial_bytes = (size_t)sp * M * pl.rem_n * sizeof(float);
+            }
+        }
+    }
     return pl;
 }
 
@@ -1414,10 +1446,37 @@ int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, in
         // 128-token group-wise tiles are 128 channels wide, four waves of 128 x 32, two workgroups per CU:
         // the same two waves per SIMD as one 256-channel workgroup, but from workgroups that do not share
         // a barrier, so that one's rescale (vector ALU only) drifts under the other's MFMAs
-        if (pl.bm == 64) W4A8_GM(64, 1, 4, true, false);
-        else
+        if (pl.bm == 64) {
+            W4A8_GM(64, 1, 4, true, false);
+        } else if (pl.rem_n == 0) {
             rc = launch_gemm_t<128, 1, 4, true, false, 128>(pl, Xq, sx, zp, rs, M, Wt, step, zero, N, K, G, Y, y_dtype,
                                                             ldy, acc_out, partial, st, plain);
+        } else {
+            // whole rounds of tiles first, then the last channels with K in ranges (plan_gemm); every
+            // parameter array is per output channel, the tiled weights are channel-tile major
+            const int64_t n1 = N - pl.rem_n, ng = K / G, KT = K / TILE_K;
+            GemmPlan p1 = pl;
+            p1.splits = 1;
+            p1.kt_per_split = (int)KT;
+            rc = launch_gemm_t<128, 1, 4, true, false, 128>(p1, Xq, sx, zp, rs, M, Wt, step, zero, n1, K, G, Y, y_dtype,
+                                                            ldy, acc_out, nullptr, st, plain, N);
+            if (rc != W4A8_OK) return rc;
+            GemmPlan p2 = pl;
+            p2.splits = pl.rem_splits;
+            p2.kt_per_split = pl.rem_kt_per_split;
+            ZeroPoint zp2 = zp;
+            if (zp.zx != nullptr) {
+                zp2.wsum = zp.wsum + n1 * ng;
+                zp2.tsum = zp.tsum + n1 * KT;
+            }
+            uint16_t *y2 = (uint16_t *)Y + n1;
+            rc = launch_gemm_t<128, 1, 4, true, false, 128>(
+                p2, Xq, sx, zp2, rs, M, Wt + n1 / TILE_N * KT * TILE_BYTES, step + n1 * ng, zero + n1 * ng, pl.rem_n, K, G,
+                y2, y_dtype, ldy, acc_out ? acc_out + n1 * ng : nullptr, partial, st, plain, N);
+            if (rc != W4A8_OK) return rc;
+            return launch_gemv_combine(partial, sx, nullptr, ZeroPoint{nullptr, nullptr, nullptr}, M, pl.rem_n,
+                                       pl.rem_splits, y2, y_dtype, ldy, st);
+        }
     } else {
         if (pl.bm == 128 && wgs > 256) W4A8_GM(128, 1, 8, false, true);
         else if (pl.bm == 128) W4A8_GM(128, 1, 8, false, false);

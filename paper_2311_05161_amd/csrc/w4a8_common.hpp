@@ -290,6 +290,12 @@ struct GemmPlan {
     int kt_per_split;
     size_t rs_bytes;       // int32 row-sums [splits][M] (per-channel weights only)
     size_t partial_bytes;  // fp32 partial sums [splits][M][N] when splits > 1
+    // Last round of tiles at most half full (group-wise 128 x 128 tiles, more than one round): the
+    // channels of that round run as a launch of their own with K cut into rem_splits ranges
+    // (0: no such remainder).  partial_bytes is then [rem_splits][M][rem_n].
+    int rem_n;             // output channels of the remainder launch (the last ones)
+    int rem_splits;
+    int rem_kt_per_split;
 };
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t G);
 int launch_gemm(const int8_t *Xq, const float *sx, ZeroPoint zp, int32_t *rs, int64_t M,

@@ -74,6 +74,10 @@ def test_workspace_sizes(lib):
     assert lib.gemm_workspace_bytes(64, 5120, 13824, 128, lib.LAYOUT_TILED) == 3 * 64 * 5120 * 4
     assert lib.gemm_workspace_bytes(128, 4096, 4096, 128, lib.LAYOUT_TILED) == 0
     assert lib.gemm_workspace_bytes(128, 4096, 4096, 0, lib.LAYOUT_TILED) == 0
+    # group-wise tiles of 128 x 128, 512 resident at a time: 16 x 40 tiles are one round and a quarter, so the
+    # last 8 channel tiles (1024 channels) run with K in four ranges: their fp32 partial sums
+    assert lib.gemm_workspace_bytes(2048, 5120, 5120, 128, lib.LAYOUT_TILED) == 4 * 2048 * 1024 * 4
+    assert lib.gemm_workspace_bytes(2048, 4096, 4096, 128, lib.LAYOUT_TILED) == 0   # exactly one round
     # empty or invalid shapes size to nothing (and divide by nothing): an empty dimension, a K or a
     # group that is no multiple of 128, a channel count that is no multiple of 16
     L = lib.load_library()

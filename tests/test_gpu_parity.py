@@ -429,6 +429,16 @@ def test_64_token_tiles_on_a_layer_too_large_for_token_blocks(lib, oracle):
     _full_size_case(lib, oracle, "C4_5120x13824", M=64, N=24832, seed=64)
 
 
+def test_last_round_of_group_wise_tiles_runs_with_k_in_ranges(lib, oracle):
+    """More than one round of 512 resident 128 x 128 group-wise tiles with a nearly empty last round (here 9 x 61
+    tiles, ragged in both directions): the channels of the last round run as a launch of their own with K cut
+    into ranges, and a combine pass over that slice of Y.  (The 2048-token cells of the LLaMA-13B sweep on the
+    5120-channel layers take the same path.)"""
+    # (the workspace tells: four K-ranges of fp32 partial sums for the last 528 channels)
+    assert lib.gemm_workspace_bytes(1100, 7696, 5120, 128, lib.LAYOUT_TILED) == 4 * 1100 * 528 * 4
+    _full_size_case(lib, oracle, "C4_5120x5120", M=1100, N=7696, seed=61)
+
+
 def test_full_size_c5_opt66b_end_to_end(lib, oracle):
     """OPT-66B-shaped layer: activation quantization and GEMM back to back on one stream."""
     _full_size_case(lib, oracle, "C5", whole=False, n_samples=4096, seed=5)

@@ -111,6 +111,7 @@ EXACT_CASES = [
     ("tile_128_rows_group128", 300, 768, 512, 128),
     ("tile_128_rows_group256_ragged", 270, 1024, 400, 256),
     ("tile_128_rows_group128_many_tiles", 1100, 512, 4112, 128),
+    ("tile_128_rows_group128_last_round_k_ranges", 1100, 5120, 7696, 128),
     ("tile_k_ranges_group256", 130, 2048, 304, 256),
     ("tile_k_ranges_per_channel", 300, 2048, 304, 0),
     # K in four phases inside the workgroup (group-128, 129 .. 256 tokens, few output tiles)
