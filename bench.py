@@ -40,7 +40,7 @@ METRIC = "W4A8 GEMM TOPS (prefill) + weight GB/s (decode), % of MI355X roofline"
 # this script on the kernels as they are (--pmc-calibration scales the counters by 256 MiB copies):
 # profiles/gemm_kernel_C5_and_gemv_kernel_C4_hbm_traffic.md.  C5 tile kernel: 1,360,788,070 read (re-reads of
 # the activations per group of channel tiles, served by the last-level cache) + 301,989,888 written.
-TRAFFIC_BYTES = {"gemm_kernel_C5": 1662722560, "gemv_kernel_C4": 39486464}
+TRAFFIC_BYTES = {"gemm_kernel_C5": 1662722048, "gemv_kernel_C4": 39479296}
 
 
 def decode_bytes(M, N, K, G):
