@@ -159,6 +159,25 @@ __device__ __forceinline__ void widen8(const Raw8<bf16_t> &r, float (&v)[8])
     }
 }
 
+// Four rounded codes (the low bytes of q0..q3) packed into one word.
+__device__ __forceinline__ uint32_t pack4_low_bytes(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(q1, q0, 0x0c0c0400u);   // [q0.b0, q1.b0, 0, 0]
+    const uint32_t hi = __builtin_amdgcn_perm(q3, q2, 0x04000c0cu);   // [0, 0, q2.b0, q3.b0]
+    return lo | hi;
+}
+
+// Symmetric form, rne and the conversion to an integer in one binary32 addition: y + 1.5 * 2^23 is
+// 1.5 * 2^23 + rne(y) exactly for |y| <= 2^22 (the sum is rounded to nearest even at unit
+// granularity), so the low byte of its bit pattern is rne(y) in two's complement.  The clamp to
+// +-127 of the definition never changes a value: |t| <= a and inv = fl(127 / a) give
+// |fl(t * inv)| <= 127 (1 + 2^-23), which rounds to 127.  (No contraction in this file: the product
+// is rounded before the addition, as in the definition.)
+__device__ __forceinline__ uint32_t quant1_bits(float t, float inv)
+{
+    return __float_as_uint(t * inv + 12582912.0f);
+}
+
 // Fast path: K % 8 == 0, 16-byte aligned rows, K <= 256 * 8 * NCH.  Rows r0 .. r0+rows_per_block.
 // What bounds this kernel is memory latency, not bandwidth (a row is only 2 K bytes), so the loads
 // of a workgroup's next row are issued before anything is done with the current one (the first row's
@@ -248,12 +267,20 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
             const int ch = tid + c * AQ_THREADS;
             if (ch < nchunks) {
                 uint32_t w0 = 0, w1 = 0;
+                if (ASYM) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int q0 = ASYM ? quant1_asym(t[c][j], ap.isx, ap.zf) : quant1(t[c][j], inv);
-                    const int q1 = ASYM ? quant1_asym(t[c][j + 4], ap.isx, ap.zf) : quant1(t[c][j + 4], inv);
-                    w0 |= (uint32_t)(q0 & 0xff) << (8 * j);
-                    w1 |= (uint32_t)(q1 & 0xff) << (8 * j);
+                    for (int j = 0; j < 4; ++j) {
+                        const int q0 = quant1_asym(t[c][j], ap.isx, ap.zf);
+                        const int q1 = quant1_asym(t[c][j + 4], ap.isx, ap.zf);
+                        w0 |= (uint32_t)(q0 & 0xff) << (8 * j);
+                        w1 |= (uint32_t)(q1 & 0xff) << (8 * j);
+                    }
+                } else {   // rounding and conversion in one addition, four codes packed by two byte permutes
+                    uint32_t b[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) b[j] = quant1_bits(t[c][j], inv);
+                    w0 = pack4_low_bytes(b[0], b[1], b[2], b[3]);
+                    w1 = pack4_low_bytes(b[4], b[5], b[6], b[7]);
                 }
                 *reinterpret_cast<uint2 *>(q + (int64_t)ch * AQ_VEC) = make_uint2(w0, w1);
             }
@@ -261,25 +288,6 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_rows_kernel(
 #pragma unroll
         for (int c = 0; c < NCH; ++c) cur[c] = nxt[c];
     }
-}
-
-// Four rounded codes (the low bytes of q0..q3) packed into one word.
-__device__ __forceinline__ uint32_t pack4_low_bytes(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3)
-{
-    const uint32_t lo = __builtin_amdgcn_perm(q1, q0, 0x0c0c0400u);   // [q0.b0, q1.b0, 0, 0]
-    const uint32_t hi = __builtin_amdgcn_perm(q3, q2, 0x04000c0cu);   // [0, 0, q2.b0, q3.b0]
-    return lo | hi;
-}
-
-// Symmetric form, rne and the conversion to an integer in one binary32 addition: y + 1.5 * 2^23 is
-// 1.5 * 2^23 + rne(y) exactly for |y| <= 2^22 (the sum is rounded to nearest even at unit
-// granularity), so the low byte of its bit pattern is rne(y) in two's complement.  The clamp to
-// +-127 of the definition never changes a value: |t| <= a and inv = fl(127 / a) give
-// |fl(t * inv)| <= 127 (1 + 2^-23), which rounds to 127.  (No contraction in this file: the product
-// is rounded before the addition, as in the definition.)
-__device__ __forceinline__ uint32_t quant1_bits(float t, float inv)
-{
-    return __float_as_uint(t * inv + 12582912.0f);
 }
 
 // One wavefront per token row (rows of up to 512 * NCW elements): no workgroup barrier in the row
