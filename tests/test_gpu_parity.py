@@ -421,6 +421,13 @@ def test_full_size_llama_shapes(lib, oracle, name, M):
     _full_size_case(lib, oracle, name, M=M, seed=M)
 
 
+@pytest.mark.parametrize("M", [130, 256])
+def test_k_phase_kernel_per_channel_on_a_full_size_layer(lib, oracle, M):
+    """65 .. 256 tokens on the per-channel 11008 -> 4096 layer (LLaMA-7B down-projection): 64-token x 64-channel
+    workgroups with K in four phases (at most one per CU), whole-matrix accumulators and Y."""
+    _full_size_case(lib, oracle, "C3_down", M=M, seed=300 + M)
+
+
 def test_64_token_tiles_on_a_layer_too_large_for_token_blocks(lib, oracle):
     """64 tokens on 24832 x 5120 group-128 weights: four 16-token blocks would need more than two
     generations of workgroups, so this runs on the tile kernel's 64-row instance."""
