@@ -533,9 +533,24 @@ def side_measurements(torch, w, lib, syn, dev, stream, st, P, e0, e1):
     e1.record(stream)
     torch.cuda.synchronize()
     mfma_ms = e0.elapsed_time(e1) / 5
+    # the group-wise k-tile's instruction mix (16 MFMAs, 96 + 128 vector instructions per wave), operands in
+    # registers / second MFMA operand read from LDS as in the kernel: ns per k-tile of a wave pair
+    mix = {}
+    mix_iters = 4000
+    for label, frags in (("registers_only", 0), ("with_lds_fragment_reads", 1)):
+        assert lib.w4a8_measure_ktile_mix(mix_iters, frags, P(sink), st) == 0
+        torch.cuda.synchronize()
+        e0.record(stream)
+        lib.w4a8_measure_ktile_mix(mix_iters, frags, P(sink), st)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        mix[label] = round(e0.elapsed_time(e1) * 1e6 / mix_iters, 1)
     ceilings = {"what": "measured on this box in this run: a plain streaming read of as many bytes as the decode "
-                        "shapes move (each launch from HBM) and a register-resident v_mfma_i32_32x32x32_i8 loop",
-                "stream_read": reads, "mfma_i8_loop_TOPS": round(ops.value / (mfma_ms * 1e-3) / 1e12, 1)}
+                        "shapes move (each launch from HBM), a register-resident v_mfma_i32_32x32x32_i8 loop, and the "
+                        "instruction mix of one k-tile of the group-wise tile kernel (two workgroups of four waves per "
+                        "CU) with and without its LDS fragment reads",
+                "stream_read": reads, "mfma_i8_loop_TOPS": round(ops.value / (mfma_ms * 1e-3) / 1e12, 1),
+                "groupwise_ktile_mix_ns": mix}
 
     # ---- the other decode shapes
     decode_side = []

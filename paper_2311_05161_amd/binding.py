@@ -32,7 +32,7 @@ EXPORTS = (
     "unpack_format",
     "dint_error_terms_workspace_bytes", "dint_error_terms",
     "expand_special_value", "w4a8_gemm_special_workspace_bytes", "w4a8_gemm_special",
-    "w4a8_measure_stream_read", "w4a8_measure_mfma_i8",
+    "w4a8_measure_stream_read", "w4a8_measure_mfma_i8", "w4a8_measure_ktile_mix",
 )
 FMT_DINT4, FMT_INT4, FMT_DINT3, FMT_DINT4_C4, FMT_DINT4_C8 = 0, 1, 2, 3, 4
 
@@ -121,6 +121,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.w4a8_measure_stream_read.restype = ci
     lib.w4a8_measure_mfma_i8.argtypes = [i64, vp, vp, vp]
     lib.w4a8_measure_mfma_i8.restype = ci
+    lib.w4a8_measure_ktile_mix.argtypes = [i64, ci, vp, vp]
+    lib.w4a8_measure_ktile_mix.restype = ci
     lib.pack_dint3.argtypes = [vp, i64, i64, vp, vp]
     lib.pack_dint3.restype = ci
     lib.unpack_dint3.argtypes = [vp, i64, i64, vp, vp]

@@ -145,6 +145,12 @@ int w4a8_measure_mfma_i8(int64_t iters, uint32_t *sink, int64_t *ops, void *stre
     return launch_mfma_i8_loop(iters, sink, ops, (hipStream_t)stream);
 }
 
+int w4a8_measure_ktile_mix(int64_t iters, int fragment_reads, uint32_t *sink, void *stream)
+{
+    if (iters < 0 || iters > (1LL << 24)) return W4A8_ERR_SHAPE;
+    return launch_ktile_mix(iters, fragment_reads, sink, (hipStream_t)stream);
+}
+
 const char *w4a8_status_string(int status)
 {
     switch (status) {

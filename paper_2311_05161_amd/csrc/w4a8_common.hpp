@@ -238,6 +238,7 @@ int launch_repeat_activations(const int8_t *Xq, int64_t M, int64_t K, int8_t *ou
 // measured ceilings (ceilings.hip): a streaming read of `bytes` bytes; `iters` rounds of the int8 MFMA loop
 int launch_stream_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t st);
 int launch_mfma_i8_loop(int64_t iters, uint32_t *sink, int64_t *ops, hipStream_t st);
+int launch_ktile_mix(int64_t iters, int fragment_reads, uint32_t *sink, hipStream_t st);
 // Launch shape of the decode GEMV for a problem size (also sizes its K-split workspace).
 struct GemvPlan {
     int splits;            // K is cut into this many ranges, each handled by its own workgroups

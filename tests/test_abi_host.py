@@ -282,6 +282,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert c.w4a8_measure_stream_read(P, 0, Z, Z) == b.OK
     assert c.w4a8_measure_mfma_i8(-1, Z, Z, Z) == b.ERR_SHAPE
     assert c.w4a8_measure_mfma_i8((1 << 24) + 1, Z, Z, Z) == b.ERR_SHAPE
+    assert c.w4a8_measure_ktile_mix(-1, 0, Z, Z) == b.ERR_SHAPE
+    assert c.w4a8_measure_ktile_mix((1 << 24) + 1, 1, Z, Z) == b.ERR_SHAPE
 
 
 def test_linear_argument_errors_before_any_launch(lib):

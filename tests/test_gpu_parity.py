@@ -463,6 +463,9 @@ def test_measurement_aids_run_and_count_their_work(lib):
     assert L.w4a8_measure_stream_read(buf.data_ptr() + 16, 4096 + 16, sink.data_ptr(), st) == 0   # ragged tail
     ops = ctypes.c_int64(0)
     assert L.w4a8_measure_mfma_i8(3, sink.data_ptr(), ctypes.byref(ops), st) == 0
+    # the k-tile instruction mix, with its operands in registers and with the fragment reads from LDS
+    assert L.w4a8_measure_ktile_mix(5, 0, sink.data_ptr(), st) == 0
+    assert L.w4a8_measure_ktile_mix(5, 1, sink.data_ptr(), st) == 0
     torch.cuda.synchronize()
     assert ops.value == 512 * 4 * 8 * 3 * 2 * 32 ** 3
     assert sink.tolist() == [7, 7, 7, 7]
